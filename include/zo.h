@@ -1,0 +1,232 @@
+/*
+ * zo.h — C ABI of the candidate-state evaluation library for Inference-Native
+ * zeroth-order optimisation on AMD MI355X (gfx950).
+ *
+ * The library evaluates a packed batch of token rows in which every sequence
+ * names the candidate state it is scored under (the "ProbePlan" of Sec. 2.2,
+ * Eq. 3 of the paper).  A candidate (direction k, sign s) sees
+ *
+ *     W_c = W_0 + s * eps * U_k V_k^T + P Vb^T            (Sec. 3.2)
+ *
+ * without W_0 ever being written: the side state is applied as factors
+ * (LoRA-style A = V^T, B = +-eps U) next to a persistent low-rank bank
+ * (Eq. "bank").  U_k [m x r] and V_k [n x r] are regenerated on the device from
+ * a 64-bit seed by a counter-based generator (Philox4x32-10 + Box-Muller) and
+ * are never passed across this boundary.  Foreground sequences (candidate id
+ * -1) see W_0 alone and their results are bit-identical to a call in which
+ * every sequence is foreground (Sec. 4, mixed-batch experiment).
+ *
+ * Conventions
+ *   - A linear layer has W [m x n] row-major (m = out features, n = in
+ *     features); X [T x n] holds packed token rows; Y = X W^T is [T x m].
+ *   - Every pointer is a DEVICE pointer unless its name starts with "host_".
+ *   - The caller owns every buffer.  Inputs (const) are never written.  Outputs
+ *     are fully overwritten.  Scratch memory comes from the caller-provided
+ *     `workspace` whose size the *_workspace_bytes queries return (host-only,
+ *     pure functions of the shapes).  The library allocates nothing, keeps no
+ *     pointer after the work it enqueued has run, and never synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream); all
+ *     device work of a call is enqueued on it, in order.
+ *   - Every function returns a zo_status.  All argument validation happens
+ *     before the first HIP call, so error paths can be exercised on a machine
+ *     without a GPU.  zo_last_error() returns a thread-local message.
+ *   - Results are deterministic: no atomics, fixed reduction orders, tile
+ *     shapes that do not depend on the batch.  A row's result does not depend
+ *     on which other rows share the batch.
+ */
+#ifndef ZO_H_
+#define ZO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum zo_status {
+  ZO_OK = 0,
+  ZO_ERR_NULL = -1,        /* a required pointer is NULL */
+  ZO_ERR_SHAPE = -2,       /* negative size, r outside [1,64], R_used > R_cap, bad leading dimension / alignment */
+  ZO_ERR_INDEX = -3,       /* candidate / direction id out of range, malformed cu_seqlens (host mirrors only) */
+  ZO_ERR_BANK_FULL = -4,   /* a direction's column block does not fit in the bank */
+  ZO_ERR_WORKSPACE = -5,   /* workspace missing, misaligned or too small */
+  ZO_ERR_UNSUPPORTED = -6, /* dtype combination or shape the kernels do not cover */
+  ZO_ERR_HIP = -7          /* a HIP call failed; zo_last_error() has the HIP string */
+} zo_status;
+
+typedef enum zo_dtype { ZO_F32 = 0, ZO_BF16 = 1 } zo_dtype;
+
+/*
+ * The packed batch and its candidate table (Sec. 2.2, Eq. 3: each query is a
+ * candidate id, an input and an observation; here the input is a sequence of
+ * packed rows and the observation is its summed token NLL).
+ *
+ *   cu_seqlens [S+1]  row offsets, cu[0] = 0, non-decreasing, cu[S] = n_tokens
+ *                     (variable-length packing, Sec. 3.1; empty sequences allowed)
+ *   seq_cand   [S]    candidate id of each sequence; -1 = foreground (base weights only)
+ *   cand_dir   [C]    direction index in [0, n_dirs) of each candidate; -1 = centre
+ *                     (bank only, no probe)
+ *   cand_sign  [C]    +1, -1 or 0 (0 = centre)
+ *   dir_seed   [K]    64-bit seed of each direction; U uses the stream
+ *                     (seed, tensor_id & ~1), V the stream (seed, tensor_id | 1)
+ *   host_*            optional host copies used only for validation; may be NULL
+ */
+typedef struct zo_batch {
+  int32_t n_tokens;
+  int32_t n_seqs;
+  const int32_t* cu_seqlens;
+  const int32_t* seq_cand;
+  int32_t n_cands;
+  const int32_t* cand_dir;
+  const float* cand_sign;
+  int32_t n_dirs;
+  const uint64_t* dir_seed;
+  const int32_t* host_cu_seqlens;
+  const int32_t* host_seq_cand;
+  const int32_t* host_cand_dir;
+} zo_batch;
+
+/*
+ * Persistent update bank of one layer (Sec. 3.2, Eq. "bank"):
+ * W_eff = W_0 + P[:, :R_used] Vb[:, :R_used]^T.  fp32 state, row-major,
+ * leading dimension R_cap.  P is [m x R_cap], Vb is [n x R_cap].
+ */
+typedef struct zo_bank {
+  int32_t R_cap;
+  int32_t R_used;
+  float* P;
+  float* Vb;
+} zo_bank;
+
+/* Library version (major * 1000 + minor). */
+int32_t zo_version(void);
+
+/* Copies the calling thread's last error message (NUL-terminated, truncated to
+ * cap) into buf; returns the message length. */
+size_t zo_last_error(char* buf, size_t cap);
+
+/*
+ * Raw words of the factor generator (for parity checks of the integer stream).
+ * Block q = first_block + i uses Philox4x32-10 with counter
+ * (q mod 2^32, q div 2^32, tensor_id, 0) and key (seed mod 2^32, seed div 2^32).
+ * out_words: device uint32 [n_blocks x 4].
+ */
+int32_t zo_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block,
+                        int64_t n_blocks, uint32_t* out_words, void* stream);
+
+/*
+ * One factor matrix [rows x r] of i.i.d. standard normals (Sec. 3.3: U and V
+ * have independent standard-normal entries).  Entry (i, j) has flat index
+ * e = i*r + j and is lane e mod 4 of block e div 4 of the stream
+ * (seed, tensor_id): uniforms u(w) = (2 (w >> 9) + 1) 2^-24, lanes (0,1) =
+ * sqrt(-2 ln u(w0)) * (cos, sin)(2 pi u(w1)), lanes (2,3) likewise from
+ * (w2, w3).  dtype ZO_F32 writes float, ZO_BF16 writes the fp32 value rounded
+ * to nearest-even bfloat16.  out: device [rows x r], dense.
+ */
+int32_t zo_factor_fill(uint64_t seed, uint32_t tensor_id, int64_t rows, int32_t r,
+                       zo_dtype dtype, void* out, void* stream);
+
+/*
+ * Packing indices of a batch (Sec. 3.1, variable-length packing):
+ * tok_seq[t] = the sequence whose row range contains t, tok_cand[t] =
+ * seq_cand[tok_seq[t]].  Outputs: device int32 [n_tokens] each (either may be
+ * NULL).  Integer results, exact.
+ */
+int32_t zo_batch_index(const zo_batch* batch, int32_t* tok_seq, int32_t* tok_cand, void* stream);
+
+/*
+ * Probe linear (Sec. 3.2, candidate states W_+-, combined probe and bank):
+ *
+ *   Y[t,:] = act( X[t,:] W^T + s_t eps (X[t,:] V_{k_t}) U_{k_t}^T
+ *                 + (X[t,:] Vb) P^T + bias )
+ *
+ * for rows of candidate sequences; rows of a centre candidate omit the probe
+ * term; rows of foreground sequences get act(X W^T + bias) and are
+ * bit-identical to an all-foreground call.
+ *
+ *   X [T x n] ld ldx, W [m x n] ld ldw, Y [T x m] ld ldy  (elements; row-major)
+ *   in_dtype  type of X and W and of the factors U, V (ZO_F32: everything fp32
+ *             on the vector ALU; ZO_BF16: bf16 operands, fp32 accumulation on
+ *             the matrix cores, U and V rounded to bf16)
+ *   out_dtype type of Y: equal to in_dtype, or ZO_F32 with ZO_BF16 inputs
+ *   bias      fp32 [m] or NULL;  act 0 = none, 1 = ReLU
+ *   r         rank of the probe, 1..64;  eps probe scale;  tensor_id even id of the layer
+ *   bank      NULL or R_used = 0: no bank
+ * ZO_BF16 requires n % 64 == 0, 16-byte aligned X, W, Y and leading dimensions
+ * that keep rows 16-byte aligned.
+ */
+size_t zo_probe_linear_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t n_dirs,
+                                       int32_t m, int32_t n, int32_t r, int32_t R_used,
+                                       zo_dtype in_dtype);
+
+int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx,
+                        const void* W, int64_t ldw, const float* bias,
+                        int32_t m, int32_t n, zo_dtype in_dtype,
+                        int32_t r, float eps, uint32_t tensor_id,
+                        const zo_bank* bank, int32_t act,
+                        void* Y, int64_t ldy, zo_dtype out_dtype,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Fused LM-head scoring (Sec. 2.2 token-scoring observation; Sec. 3.3
+ * "compact active-token logits or per-request NLL"): logits
+ * z_t = H[t,:] W_head^T are never stored;
+ *
+ *   tok_nll[t]  = log sum_v exp(z_tv) - z_t[targets[t]]   (0 when targets[t] < 0)
+ *   seq_nll[s]  = sum of tok_nll over the sequence's rows
+ *   cand_sum[c] = sum of seq_nll over sequences with seq_cand == c
+ *   cand_cnt[c] = number of scored rows (targets >= 0) of candidate c
+ *
+ *   H [T x d] ld ldh, W_head [vocab x d] ld ldw (dtype; ZO_BF16 needs d % 64 == 0)
+ *   targets int32 [T] in [-inf, vocab)
+ *   tok_nll fp32 [T] (nullable), seq_nll fp32 [S], cand_sum fp32 [C], cand_cnt int32 [C]
+ * The head carries no side state.  Foreground sequences get seq_nll but
+ * contribute to no candidate.
+ */
+size_t zo_score_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t vocab, int32_t d,
+                                zo_dtype dtype);
+
+int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh,
+                 const void* W_head, int64_t ldw, int32_t vocab, int32_t d, zo_dtype dtype,
+                 const int32_t* targets, float* tok_nll, float* seq_nll,
+                 float* cand_sum, int32_t* cand_cnt,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Antithetic two-point estimate (Sec. 2.1, Eq. 2):
+ *   cand_loss[c] = cand_sum[c] / max(cand_cnt[c], 1)   (reduction 0, mean)
+ *                = cand_sum[c]                          (reduction 1, sum)
+ *   proj_grad[k] = (cand_loss[c+] - cand_loss[c-]) / (2 eps)
+ * where c+ / c- are the lowest-numbered candidates of direction k with
+ * positive / negative sign; a direction lacking either gets 0.
+ * cand_loss fp32 [C], proj_grad fp32 [K]; needs no workspace.
+ */
+int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t* cand_cnt,
+                    float eps, int32_t reduction, float* cand_loss, float* proj_grad,
+                    void* stream);
+
+/*
+ * Lazy bank update (Sec. 3.2, Eq. "layer-coupling": sum_t beta_t U_t V_k^T =
+ * P_k V_k^T, so only P_k is maintained).  For every direction k, with
+ * beta_k = -lr * proj_grad[k] * dir_weight[k] read on the device:
+ *   append = 0:  P[:, col0[k] : col0[k]+r] += beta_k U_k
+ *   append = 1:  P[:, block] = beta_k U_k;  Vb[:, block] = V_k
+ * U_k, V_k are regenerated from dir_seed[k] (factor_dtype as in
+ * zo_probe_linear's in_dtype).  dir_weight NULL means 1/n_dirs.
+ *   host_col0  HOST int32 [n_dirs]: first column of each direction's block;
+ *              blocks must not overlap each other.
+ * On append, bank->R_used (a host field) is raised to max(col0[k] + r).
+ * Returns ZO_ERR_BANK_FULL when a block does not fit in R_cap.
+ * W_0 is not an argument: the base is never touched.
+ */
+int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs,
+                       const uint64_t* dir_seed, uint32_t tensor_id,
+                       const float* proj_grad, float lr, const float* dir_weight,
+                       const int32_t* host_col0, int32_t append, zo_dtype factor_dtype,
+                       void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZO_H_ */

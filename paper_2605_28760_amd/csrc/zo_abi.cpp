@@ -1,0 +1,405 @@
+// Host side of the C ABI declared in include/zo.h: argument validation (all of
+// it before the first HIP call), workspace planning and kernel sequencing.
+// The ProbePlan -> observations boundary of Sec. 2.3 (Eq. 4) is this file.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+
+#include "../../include/zo.h"
+#include "zo_internal.hpp"
+
+namespace {
+
+thread_local std::string g_err;
+
+int32_t fail(zo_status st, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return (int32_t)st;
+}
+
+int32_t hip_fail(hipError_t e, const char* where) {
+  return fail(ZO_ERR_HIP, "%s: %s", where, hipGetErrorString(e));
+}
+
+#define ZO_HIP(call, where)                              \
+  do {                                                   \
+    hipError_t e__ = (call);                             \
+    if (e__ != hipSuccess) return hip_fail(e__, where);  \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int round16(int x) { return (x + 15) / 16 * 16; }
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+constexpr int64_t kMaxLd = (int64_t)1 << 22;  // keeps 256-row tile offsets inside 32 bits
+
+// Carves 256-byte aligned regions out of the caller's workspace.
+struct Carver {
+  size_t off = 0;
+  size_t take(size_t bytes) {
+    const size_t at = off;
+    off = align_up(off + bytes, 256);
+    return at;
+  }
+};
+
+int32_t check_batch(const zo_batch* b) {
+  if (!b) return fail(ZO_ERR_NULL, "batch is NULL");
+  if (b->n_tokens < 0 || b->n_seqs < 0 || b->n_cands < 0 || b->n_dirs < 0)
+    return fail(ZO_ERR_SHAPE, "negative batch size (T=%d S=%d C=%d K=%d)", b->n_tokens, b->n_seqs, b->n_cands,
+                b->n_dirs);
+  if (b->n_tokens > 0 && b->n_seqs == 0) return fail(ZO_ERR_SHAPE, "n_tokens > 0 with no sequences");
+  if (!b->cu_seqlens) return fail(ZO_ERR_NULL, "batch.cu_seqlens is NULL");
+  if (b->n_seqs > 0 && !b->seq_cand) return fail(ZO_ERR_NULL, "batch.seq_cand is NULL");
+  if (b->n_cands > 0 && (!b->cand_dir || !b->cand_sign)) return fail(ZO_ERR_NULL, "batch.cand_dir / cand_sign is NULL");
+  if (b->n_dirs > 0 && !b->dir_seed) return fail(ZO_ERR_NULL, "batch.dir_seed is NULL");
+  if (b->host_cu_seqlens) {
+    const int32_t* cu = b->host_cu_seqlens;
+    if (cu[0] != 0) return fail(ZO_ERR_INDEX, "cu_seqlens[0] = %d, expected 0", cu[0]);
+    for (int s = 0; s < b->n_seqs; ++s)
+      if (cu[s + 1] < cu[s]) return fail(ZO_ERR_INDEX, "cu_seqlens decreases at sequence %d", s);
+    if (cu[b->n_seqs] != b->n_tokens)
+      return fail(ZO_ERR_INDEX, "cu_seqlens[S] = %d but n_tokens = %d", cu[b->n_seqs], b->n_tokens);
+  }
+  if (b->host_seq_cand)
+    for (int s = 0; s < b->n_seqs; ++s)
+      if (b->host_seq_cand[s] < -1 || b->host_seq_cand[s] >= b->n_cands)
+        return fail(ZO_ERR_INDEX, "seq_cand[%d] = %d outside [-1, %d)", s, b->host_seq_cand[s], b->n_cands);
+  if (b->host_cand_dir)
+    for (int c = 0; c < b->n_cands; ++c)
+      if (b->host_cand_dir[c] < -1 || b->host_cand_dir[c] >= b->n_dirs)
+        return fail(ZO_ERR_INDEX, "cand_dir[%d] = %d outside [-1, %d)", c, b->host_cand_dir[c], b->n_dirs);
+  return ZO_OK;
+}
+
+zo::BatchDev to_dev(const zo_batch* b) {
+  zo::BatchDev d;
+  d.T = b->n_tokens; d.S = b->n_seqs; d.C = b->n_cands; d.K = b->n_dirs;
+  d.cu = b->cu_seqlens; d.seq_cand = b->seq_cand; d.cand_dir = b->cand_dir; d.cand_sign = b->cand_sign;
+  d.seed = b->dir_seed;
+  return d;
+}
+
+// ---- workspace plans --------------------------------------------------------------------
+struct ProbePlan {
+  int RP = 0, Rp = 0, max_items = 0, ksplit = 1;
+  size_t seq_kind, seq_scale, tok_seq, n_items, items;
+  size_t Uh, Vt, Ph, Vbt, Aside, partial;   // bf16 path
+  size_t Uf, Vf, Tside;                      // fp32 path
+  size_t total = 0;
+};
+
+int side_ksplit(int T, int n) {
+  // enough (item, split) waves to cover the chip twice, k-chunks of >= 512 that divide n
+  const int items = (T + zo::kSideRows - 1) / zo::kSideRows;
+  int ks = 1;
+  while (items * ks < 2048 && ks < 16 && n % (ks * 2 * 32) == 0 && n / (ks * 2) >= 512) ks *= 2;
+  return ks;
+}
+
+ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype dt) {
+  ProbePlan p;
+  Carver c;
+  p.seq_kind = c.take((size_t)S * 4);
+  p.seq_scale = c.take((size_t)S * 4);
+  p.tok_seq = c.take((size_t)T * 4);
+  p.n_items = c.take(16);
+  p.max_items = (T + zo::kSideRows - 1) / zo::kSideRows + S;
+  p.items = c.take((size_t)p.max_items * sizeof(zo::SideItem));
+  if (dt == ZO_BF16) {
+    p.RP = round16(r);
+    p.Rp = round16(R);
+    const size_t NC = (size_t)p.RP + p.Rp;
+    p.ksplit = side_ksplit(T, n);
+    p.Uh = c.take((size_t)K * m * p.RP * 2);
+    p.Vt = c.take((size_t)K * p.RP * n * 2);
+    p.Ph = c.take((size_t)m * p.Rp * 2);
+    p.Vbt = c.take((size_t)p.Rp * n * 2);
+    p.Aside = c.take((size_t)T * NC * 2);
+    p.partial = c.take(p.ksplit > 1 ? (size_t)p.ksplit * T * NC * 4 : 0);
+  } else {
+    p.Uf = c.take((size_t)K * m * r * 4);
+    p.Vf = c.take((size_t)K * n * r * 4);
+    p.Tside = c.take((size_t)T * (r + R) * 4);
+  }
+  p.total = c.off;
+  return p;
+}
+
+struct ScorePlan {
+  int n_vt = 0;
+  size_t part_max, part_sum, tgt_logit, tok_nll, seq_cnt, total = 0;
+};
+
+ScorePlan plan_score(int T, int S, int vocab, zo_dtype dt) {
+  ScorePlan p;
+  Carver c;
+  p.n_vt = dt == ZO_BF16 ? zo::head_vocab_tiles_bf16(vocab) : zo::head_vocab_tiles_f32(vocab);
+  p.part_max = c.take((size_t)p.n_vt * T * 4);
+  p.part_sum = c.take((size_t)p.n_vt * T * 4);
+  p.tgt_logit = c.take((size_t)T * 4);
+  p.tok_nll = c.take((size_t)T * 4);
+  p.seq_cnt = c.take((size_t)S * 4);
+  p.total = c.off;
+  return p;
+}
+
+int32_t check_matrix(const char* name, const void* p, int64_t ld, int cols, zo_dtype dt) {
+  if (ld < cols || ld > kMaxLd) return fail(ZO_ERR_SHAPE, "%s: leading dimension %lld invalid for %d columns", name, (long long)ld, cols);
+  if (dt == ZO_BF16) {
+    if (!aligned16(p)) return fail(ZO_ERR_SHAPE, "%s: pointer not 16-byte aligned", name);
+    if (ld % 8 != 0) return fail(ZO_ERR_SHAPE, "%s: leading dimension %lld does not keep rows 16-byte aligned", name, (long long)ld);
+  } else if (((uintptr_t)p & 3u) != 0) {
+    return fail(ZO_ERR_SHAPE, "%s: pointer not 4-byte aligned", name);
+  }
+  return ZO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t zo_version(void) { return 1000; }
+
+size_t zo_last_error(char* buf, size_t cap) {
+  if (buf && cap > 0) {
+    const size_t n = g_err.size() < cap - 1 ? g_err.size() : cap - 1;
+    memcpy(buf, g_err.data(), n);
+    buf[n] = 0;
+  }
+  return g_err.size();
+}
+
+int32_t zo_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block, int64_t n_blocks,
+                        uint32_t* out_words, void* stream) {
+  if (n_blocks < 0) return fail(ZO_ERR_SHAPE, "n_blocks = %lld", (long long)n_blocks);
+  if (n_blocks == 0) return ZO_OK;
+  if (!out_words) return fail(ZO_ERR_NULL, "out_words is NULL");
+  if (!aligned16(out_words)) return fail(ZO_ERR_SHAPE, "out_words not 16-byte aligned");
+  ZO_HIP(zo::launch_philox_words(seed, tensor_id, first_block, n_blocks, out_words, (hipStream_t)stream), "zo_philox_words");
+  return ZO_OK;
+}
+
+int32_t zo_factor_fill(uint64_t seed, uint32_t tensor_id, int64_t rows, int32_t r, zo_dtype dtype, void* out,
+                       void* stream) {
+  if (rows < 0 || r < 1) return fail(ZO_ERR_SHAPE, "rows = %lld, r = %d", (long long)rows, r);
+  if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
+  if (rows == 0) return ZO_OK;
+  if (!out) return fail(ZO_ERR_NULL, "out is NULL");
+  ZO_HIP(zo::launch_factor_fill(seed, tensor_id, rows, r, dtype == ZO_BF16, out, (hipStream_t)stream), "zo_factor_fill");
+  return ZO_OK;
+}
+
+int32_t zo_batch_index(const zo_batch* batch, int32_t* tok_seq, int32_t* tok_cand, void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (batch->n_tokens == 0) return ZO_OK;
+  ZO_HIP(zo::launch_tok_index(to_dev(batch), tok_seq, tok_cand, (hipStream_t)stream), "zo_batch_index");
+  return ZO_OK;
+}
+
+size_t zo_probe_linear_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t n_dirs, int32_t m, int32_t n,
+                                       int32_t r, int32_t R_used, zo_dtype in_dtype) {
+  if (n_tokens < 0 || n_seqs < 0 || n_dirs < 0 || m < 0 || n < 0 || r < 0 || R_used < 0) return 0;
+  return plan_probe(n_tokens, n_seqs, n_dirs, m, n, r, R_used, in_dtype).total;
+}
+
+int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const void* W, int64_t ldw,
+                        const float* bias, int32_t m, int32_t n, zo_dtype in_dtype, int32_t r, float eps,
+                        uint32_t tensor_id, const zo_bank* bank, int32_t act, void* Y, int64_t ldy,
+                        zo_dtype out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (m < 0 || n < 0) return fail(ZO_ERR_SHAPE, "m = %d, n = %d", m, n);
+  if (r < 1 || r > 64) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, 64]", r);
+  if (in_dtype != ZO_F32 && in_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "in_dtype %d", (int)in_dtype);
+  if (!(out_dtype == in_dtype || (in_dtype == ZO_BF16 && out_dtype == ZO_F32)))
+    return fail(ZO_ERR_UNSUPPORTED, "in_dtype %d with out_dtype %d", (int)in_dtype, (int)out_dtype);
+  if (act != 0 && act != 1) return fail(ZO_ERR_UNSUPPORTED, "activation %d", act);
+  const int T = batch->n_tokens;
+  int R = 0;
+  if (bank) {
+    if (bank->R_cap < 0 || bank->R_used < 0 || bank->R_used > bank->R_cap)
+      return fail(ZO_ERR_SHAPE, "bank R_used = %d, R_cap = %d", bank->R_used, bank->R_cap);
+    R = bank->R_used;
+    if (R > 0 && (!bank->P || !bank->Vb)) return fail(ZO_ERR_NULL, "bank.P / bank.Vb is NULL");
+  }
+  if (T == 0 || m == 0) return ZO_OK;
+  if (!X || !W || !Y) return fail(ZO_ERR_NULL, "X, W or Y is NULL");
+  if (int32_t st = check_matrix("X", X, ldx, n, in_dtype)) return st;
+  if (int32_t st = check_matrix("W", W, ldw, n, in_dtype)) return st;
+  if (int32_t st = check_matrix("Y", Y, ldy, m, out_dtype)) return st;
+  if (in_dtype == ZO_BF16 && (n % zo::kTileK != 0 || n == 0))
+    return fail(ZO_ERR_UNSUPPORTED, "bf16 path needs n %% %d == 0 (n = %d)", zo::kTileK, n);
+  const ProbePlan plan = plan_probe(T, batch->n_seqs, batch->n_dirs, m, n, r, R, in_dtype);
+  if (!workspace) return fail(ZO_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total);
+  if (((uintptr_t)workspace & 255u) != 0) return fail(ZO_ERR_WORKSPACE, "workspace not 256-byte aligned");
+  if (workspace_bytes < plan.total)
+    return fail(ZO_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total);
+
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  const zo::BatchDev bd = to_dev(batch);
+  zo::SeqTables tabs;
+  tabs.seq_kind = (int32_t*)(ws + plan.seq_kind);
+  tabs.seq_scale = (float*)(ws + plan.seq_scale);
+  tabs.tok_seq = (int32_t*)(ws + plan.tok_seq);
+  tabs.items = (zo::SideItem*)(ws + plan.items);
+  tabs.n_items = (int32_t*)(ws + plan.n_items);
+  tabs.max_items = plan.max_items;
+  // a batch without candidates (or probes and bank both absent) is a plain GEMM
+  const bool has_side = batch->n_cands > 0;
+  if (has_side) ZO_HIP(zo::launch_seq_tables(bd, eps, tabs, st), "batch tables");
+
+  if (in_dtype == ZO_BF16) {
+    uint16_t* Uh = (uint16_t*)(ws + plan.Uh);
+    uint16_t* Vt = (uint16_t*)(ws + plan.Vt);
+    uint16_t* Ph = (uint16_t*)(ws + plan.Ph);
+    uint16_t* Vbt = (uint16_t*)(ws + plan.Vbt);
+    uint16_t* Aside = (uint16_t*)(ws + plan.Aside);
+    if (has_side) {
+      ZO_HIP(zo::launch_factor_images_bf16(bd, tensor_id, m, n, r, plan.RP, Uh, Vt, st), "factor images");
+      if (R > 0)
+        ZO_HIP(zo::launch_bank_images_bf16(bank->P, bank->Vb, bank->R_cap, R, plan.Rp, m, n, Ph, Vbt, st), "bank images");
+      zo::SideDownArgs sd;
+      sd.X = (const uint16_t*)X; sd.ldx = ldx; sd.Vt = Vt; sd.Vbt = Vbt;
+      sd.n = n; sd.RP = plan.RP; sd.Rp = plan.Rp; sd.T = T;
+      sd.items = tabs.items; sd.n_items = tabs.n_items; sd.max_items = plan.max_items;
+      sd.ksplit = plan.ksplit; sd.partial = (float*)(ws + plan.partial); sd.Aside = Aside;
+      sd.tok_seq = tabs.tok_seq; sd.seq_kind = tabs.seq_kind; sd.seq_scale = tabs.seq_scale;
+      ZO_HIP(zo::launch_side_down_bf16(sd, st), "side-down");
+    }
+    zo::ProbeGemmArgs g;
+    g.X = (const uint16_t*)X; g.ldx = ldx; g.W = (const uint16_t*)W; g.ldw = ldw; g.bias = bias;
+    g.T = T; g.m = m; g.n = n; g.act = act; g.Y = Y; g.ldy = ldy; g.out_bf16 = out_dtype == ZO_BF16;
+    g.has_side = has_side; g.cu = batch->cu_seqlens; g.S = batch->n_seqs; g.tok_seq = tabs.tok_seq;
+    g.seq_kind = tabs.seq_kind; g.Aside = Aside; g.RP = plan.RP; g.Rp = plan.Rp; g.Uh = Uh; g.Ph = Ph;
+    ZO_HIP(zo::launch_probe_gemm_bf16(g, st), "probe GEMM");
+  } else {
+    zo::ProbeF32Args a;
+    a.X = (const float*)X; a.ldx = ldx; a.W = (const float*)W; a.ldw = ldw; a.bias = bias;
+    a.T = T; a.m = m; a.n = n; a.r = r; a.R = R; a.R_cap = bank ? bank->R_cap : 0; a.act = act;
+    a.Y = (float*)Y; a.ldy = ldy; a.has_side = has_side;
+    a.tok_seq = tabs.tok_seq; a.seq_kind = tabs.seq_kind; a.seq_scale = tabs.seq_scale;
+    a.Uf = (float*)(ws + plan.Uf); a.Vf = (float*)(ws + plan.Vf);
+    a.P = bank ? bank->P : nullptr; a.Vb = bank ? bank->Vb : nullptr;
+    a.Tside = (float*)(ws + plan.Tside);
+    if (has_side) ZO_HIP(zo::launch_factors_f32(bd, tensor_id, m, n, r, (float*)(ws + plan.Uf), (float*)(ws + plan.Vf), st), "fp32 factors");
+    ZO_HIP(zo::launch_probe_f32(a, st), "fp32 probe linear");
+  }
+  return ZO_OK;
+}
+
+size_t zo_score_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t vocab, int32_t d, zo_dtype dtype) {
+  (void)d;
+  if (n_tokens < 0 || n_seqs < 0 || vocab < 0) return 0;
+  return plan_score(n_tokens, n_seqs, vocab, dtype).total;
+}
+
+int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh, const void* W_head, int64_t ldw,
+                 int32_t vocab, int32_t d, zo_dtype dtype, const int32_t* targets, float* tok_nll,
+                 float* seq_nll, float* cand_sum, int32_t* cand_cnt, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (vocab < 1 || d < 1) return fail(ZO_ERR_SHAPE, "vocab = %d, d = %d", vocab, d);
+  if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
+  const int T = batch->n_tokens, S = batch->n_seqs, C = batch->n_cands;
+  if (S > 0 && !seq_nll) return fail(ZO_ERR_NULL, "seq_nll is NULL");
+  if (C > 0 && (!cand_sum || !cand_cnt)) return fail(ZO_ERR_NULL, "cand_sum / cand_cnt is NULL");
+  if (T > 0) {
+    if (!H || !W_head || !targets) return fail(ZO_ERR_NULL, "H, W_head or targets is NULL");
+    if (int32_t st = check_matrix("H", H, ldh, d, dtype)) return st;
+    if (int32_t st = check_matrix("W_head", W_head, ldw, d, dtype)) return st;
+    if (dtype == ZO_BF16 && d % zo::kTileK != 0)
+      return fail(ZO_ERR_UNSUPPORTED, "bf16 path needs d %% %d == 0 (d = %d)", zo::kTileK, d);
+  }
+  const ScorePlan plan = plan_score(T, S, vocab, dtype);
+  if (plan.total > 0) {
+    if (!workspace) return fail(ZO_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total);
+    if (((uintptr_t)workspace & 255u) != 0) return fail(ZO_ERR_WORKSPACE, "workspace not 256-byte aligned");
+    if (workspace_bytes < plan.total)
+      return fail(ZO_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, plan.total);
+  }
+  if (S == 0 && C == 0) return ZO_OK;
+
+  hipStream_t st = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* part_max = (float*)(ws + plan.part_max);
+  float* part_sum = (float*)(ws + plan.part_sum);
+  float* tgt = (float*)(ws + plan.tgt_logit);
+  if (T > 0) {
+    if (dtype == ZO_BF16) {
+      zo::HeadScoreArgs a;
+      a.H = (const uint16_t*)H; a.ldh = ldh; a.Wh = (const uint16_t*)W_head; a.ldw = ldw;
+      a.T = T; a.vocab = vocab; a.d = d; a.targets = targets;
+      a.part_max = part_max; a.part_sum = part_sum; a.tgt_logit = tgt;
+      ZO_HIP(zo::launch_head_score_bf16(a, st), "head scoring");
+    } else {
+      zo::HeadScoreF32Args a;
+      a.H = (const float*)H; a.ldh = ldh; a.Wh = (const float*)W_head; a.ldw = ldw;
+      a.T = T; a.vocab = vocab; a.d = d; a.targets = targets;
+      a.part_max = part_max; a.part_sum = part_sum; a.tgt_logit = tgt;
+      ZO_HIP(zo::launch_head_score_f32(a, st), "fp32 head scoring");
+    }
+  }
+  zo::ScoreCombineArgs c;
+  c.T = T; c.S = S; c.C = C; c.n_vt = plan.n_vt;
+  c.part_max = part_max; c.part_sum = part_sum; c.tgt_logit = tgt; c.targets = targets;
+  c.cu = batch->cu_seqlens; c.seq_cand = batch->seq_cand;
+  c.tok_nll = tok_nll ? tok_nll : (float*)(ws + plan.tok_nll);
+  c.seq_nll = seq_nll; c.seq_cnt = (int32_t*)(ws + plan.seq_cnt);
+  c.cand_sum = cand_sum; c.cand_cnt = cand_cnt;
+  ZO_HIP(zo::launch_score_combine(c, st), "score combine");
+  return ZO_OK;
+}
+
+int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                    int32_t reduction, float* cand_loss, float* proj_grad, void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (reduction != 0 && reduction != 1) return fail(ZO_ERR_UNSUPPORTED, "reduction %d", reduction);
+  if (!(eps > 0.0f)) return fail(ZO_ERR_SHAPE, "eps = %g must be positive", (double)eps);
+  if (batch->n_cands > 0 && (!cand_sum || !cand_cnt || !cand_loss)) return fail(ZO_ERR_NULL, "cand_sum, cand_cnt or cand_loss is NULL");
+  if (batch->n_dirs > 0 && !proj_grad) return fail(ZO_ERR_NULL, "proj_grad is NULL");
+  ZO_HIP(zo::launch_estimate(to_dev(batch), cand_sum, cand_cnt, eps, reduction, cand_loss, proj_grad, (hipStream_t)stream), "zo_estimate");
+  return ZO_OK;
+}
+
+int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, const uint64_t* dir_seed,
+                       uint32_t tensor_id, const float* proj_grad, float lr, const float* dir_weight,
+                       const int32_t* host_col0, int32_t append, zo_dtype factor_dtype, void* stream) {
+  if (!bank) return fail(ZO_ERR_NULL, "bank is NULL");
+  if (m < 0 || n < 0 || n_dirs < 0) return fail(ZO_ERR_SHAPE, "m = %d, n = %d, n_dirs = %d", m, n, n_dirs);
+  if (r < 1 || r > 64) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, 64]", r);
+  if (bank->R_cap < 0 || bank->R_used < 0 || bank->R_used > bank->R_cap)
+    return fail(ZO_ERR_SHAPE, "bank R_used = %d, R_cap = %d", bank->R_used, bank->R_cap);
+  if (factor_dtype != ZO_F32 && factor_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "factor_dtype %d", (int)factor_dtype);
+  if (append != 0 && append != 1) return fail(ZO_ERR_UNSUPPORTED, "append = %d", append);
+  if (n_dirs == 0) return ZO_OK;
+  if (!dir_seed || !proj_grad || !host_col0) return fail(ZO_ERR_NULL, "dir_seed, proj_grad or host_col0 is NULL");
+  if (!bank->P || (append && !bank->Vb)) return fail(ZO_ERR_NULL, "bank.P / bank.Vb is NULL");
+  int new_used = bank->R_used;
+  for (int k = 0; k < n_dirs; ++k) {
+    const int c0 = host_col0[k];
+    if (c0 < 0) return fail(ZO_ERR_SHAPE, "col0[%d] = %d", k, c0);
+    if (c0 + r > bank->R_cap) return fail(ZO_ERR_BANK_FULL, "direction %d: columns [%d, %d) exceed R_cap = %d", k, c0, c0 + r, bank->R_cap);
+    if (!append && c0 + r > bank->R_used)
+      return fail(ZO_ERR_SHAPE, "direction %d accumulates into columns [%d, %d) beyond R_used = %d", k, c0, c0 + r, bank->R_used);
+    for (int j = 0; j < k; ++j)
+      if (c0 < host_col0[j] + r && host_col0[j] < c0 + r)
+        return fail(ZO_ERR_SHAPE, "column blocks of directions %d and %d overlap", j, k);
+    if (c0 + r > new_used) new_used = c0 + r;
+  }
+  zo::BankUpdateArgs a;
+  a.P = bank->P; a.Vb = bank->Vb; a.R_cap = bank->R_cap; a.m = m; a.n = n; a.r = r;
+  a.seed = dir_seed; a.tensor_id = tensor_id; a.proj_grad = proj_grad; a.lr = lr; a.dir_weight = dir_weight;
+  a.default_weight = 1.0f / (float)n_dirs; a.append = append; a.bf16 = factor_dtype == ZO_BF16;
+  ZO_HIP(zo::launch_bank_update(a, n_dirs, host_col0, (hipStream_t)stream), "zo_bank_update");
+  if (append) bank->R_used = new_used;
+  return ZO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,156 @@
+// Internal interface between the host-side ABI (validation, workspace
+// planning) and the kernel launchers.  Nothing here is exported.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace zo {
+
+// Row-tile of the MFMA GEMM kernels and row-chunk of the side-down kernel.
+constexpr int kTileM = 256;
+constexpr int kTileN = 256;
+constexpr int kTileK = 64;
+constexpr int kSideRows = 64;     // rows per side-down work item (one wave)
+constexpr int kSideMaxBlocks = 9; // 16-column blocks a side-down wave accumulates at once
+constexpr int kSimtTile = 64;     // tile edge of the fp32 vector-ALU kernels
+
+struct BatchDev {
+  int T, S, C, K;
+  const int32_t* cu;
+  const int32_t* seq_cand;
+  const int32_t* cand_dir;
+  const float* cand_sign;
+  const uint64_t* seed;
+};
+
+// One side-down work item: rows [row0, row0 + nrows) of one sequence.
+struct SideItem {
+  int32_t row0;
+  int32_t nrows;
+  int32_t kind;   // direction index >= 0, kKindCentre or kKindForeground
+  float scale;    // sign * eps
+};
+
+struct SeqTables {
+  int32_t* seq_kind;   // [S]
+  float* seq_scale;    // [S]
+  int32_t* tok_seq;    // [T]
+  SideItem* items;     // [max_items]
+  int32_t* n_items;    // [1]
+  int32_t max_items;
+};
+
+// ---- zo_prep.hip ------------------------------------------------------------
+hipError_t launch_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block,
+                               int64_t n_blocks, uint32_t* out, hipStream_t st);
+hipError_t launch_factor_fill(uint64_t seed, uint32_t tensor_id, int64_t rows, int r, int bf16,
+                              void* out, hipStream_t st);
+hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_cand, hipStream_t st);
+hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, hipStream_t st);
+// bf16 operand images: Uh [K][m][RP] (k-contiguous rows of U, zero padded to RP),
+// Vt [K][RP][n] (V transposed), Ph [m][Rp], Vbt [Rp][n].
+hipError_t launch_factor_images_bf16(const BatchDev& b, uint32_t tensor_id, int m, int n, int r, int RP,
+                                     uint16_t* Uh, uint16_t* Vt, hipStream_t st);
+hipError_t launch_bank_images_bf16(const float* P, const float* Vb, int R_cap, int R_used, int Rp,
+                                   int m, int n, uint16_t* Ph, uint16_t* Vbt, hipStream_t st);
+// fp32 factors: Uf [K][m][r], Vf [K][n][r]
+hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int n, int r,
+                              float* Uf, float* Vf, hipStream_t st);
+
+// ---- zo_side.hip --------------------------------------------------------------
+struct SideDownArgs {
+  const uint16_t* X; int64_t ldx;   // bf16 [T][n]
+  const uint16_t* Vt;               // [K][RP][n]
+  const uint16_t* Vbt;              // [Rp][n]
+  int n, RP, Rp, T;
+  const SideItem* items; const int32_t* n_items; int max_items;
+  int ksplit;                       // >= 1
+  float* partial;                   // [ksplit][T][RP+Rp] when ksplit > 1
+  uint16_t* Aside;                  // bf16 [T][RP+Rp]: [s*eps*X V | X Vb]
+  const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;  // for the split-K reduction
+};
+hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st);
+
+// ---- zo_gemm.hip ---------------------------------------------------------------
+struct ProbeGemmArgs {
+  const uint16_t* X; int64_t ldx;
+  const uint16_t* W; int64_t ldw;
+  const float* bias;
+  int T, m, n;
+  int act;
+  void* Y; int64_t ldy; int out_bf16;
+  // side state (has_side = 0: plain GEMM for every row)
+  int has_side;
+  const int32_t* cu; int S;
+  const int32_t* tok_seq;
+  const int32_t* seq_kind;
+  const uint16_t* Aside; int RP, Rp;
+  const uint16_t* Uh;               // [K][m][RP]
+  const uint16_t* Ph;               // [m][Rp]
+};
+hipError_t launch_probe_gemm_bf16(const ProbeGemmArgs& a, hipStream_t st);
+
+struct HeadScoreArgs {
+  const uint16_t* H; int64_t ldh;
+  const uint16_t* Wh; int64_t ldw;
+  int T, vocab, d;
+  const int32_t* targets;
+  float* part_max;                  // [n_vt][T]
+  float* part_sum;                  // [n_vt][T]
+  float* tgt_logit;                 // [T]
+};
+int head_vocab_tiles_bf16(int vocab);
+hipError_t launch_head_score_bf16(const HeadScoreArgs& a, hipStream_t st);
+
+// ---- zo_simt.hip (fp32 on the vector ALU) ------------------------------------------
+struct ProbeF32Args {
+  const float* X; int64_t ldx;
+  const float* W; int64_t ldw;
+  const float* bias;
+  int T, m, n, r, R, R_cap;
+  int act;
+  float* Y; int64_t ldy;
+  int has_side;
+  const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;
+  const float* Uf; const float* Vf;  // [K][m][r], [K][n][r]
+  const float* P; const float* Vb;   // bank, ld R_cap
+  float* Tside;                      // [T][r+R]
+};
+hipError_t launch_probe_f32(const ProbeF32Args& a, hipStream_t st);
+int head_vocab_tiles_f32(int vocab);
+struct HeadScoreF32Args {
+  const float* H; int64_t ldh;
+  const float* Wh; int64_t ldw;
+  int T, vocab, d;
+  const int32_t* targets;
+  float* part_max; float* part_sum; float* tgt_logit;
+};
+hipError_t launch_head_score_f32(const HeadScoreF32Args& a, hipStream_t st);
+
+// ---- zo_reduce.hip -------------------------------------------------------------------
+struct ScoreCombineArgs {
+  int T, S, C, n_vt;
+  const float* part_max; const float* part_sum; const float* tgt_logit;
+  const int32_t* targets;
+  const int32_t* cu; const int32_t* seq_cand;
+  float* tok_nll;      // [T] (workspace when the caller passes none)
+  float* seq_nll;      // [S]
+  int32_t* seq_cnt;    // [S] workspace
+  float* cand_sum;     // [C]
+  int32_t* cand_cnt;   // [C]
+};
+hipError_t launch_score_combine(const ScoreCombineArgs& a, hipStream_t st);
+hipError_t launch_estimate(const BatchDev& b, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                           int reduction, float* cand_loss, float* proj_grad, hipStream_t st);
+struct BankUpdateArgs {
+  float* P; float* Vb; int R_cap;
+  int m, n, r;
+  const uint64_t* seed; uint32_t tensor_id;
+  const float* proj_grad; float lr; const float* dir_weight; float default_weight;
+  int append; int bf16;
+};
+// col0: host array of n_dirs block offsets (passed to the kernel by value in batches)
+hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st);
+
+}  // namespace zo

@@ -1,0 +1,226 @@
+// Preparation kernels: factor generation (Philox4x32-10 + Box-Muller; the
+// seed-regenerated directions of Sec. 2.2 with the N(0,1) entries of Sec. 3.3),
+// packing indices of the variable-length batch (Sec. 3.1) and the operand
+// images the matrix-core kernels consume.
+#include "zo_device.hpp"
+#include "zo_internal.hpp"
+
+namespace zo {
+
+// ---- raw words / standalone factor fill ------------------------------------------
+__global__ void k_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block,
+                               int64_t n_blocks, uint4* out) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_blocks) return;
+  out[i] = factor_block(seed, tensor_id, first_block + (uint64_t)i);
+}
+
+__global__ void k_factor_fill(uint64_t seed, uint32_t tensor_id, int64_t n_elems, int bf16, void* out) {
+  const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q * 4 >= n_elems) return;
+  const uint4 w = factor_block(seed, tensor_id, (uint64_t)q);
+  float z[4];
+  box_muller(w.x, w.y, z[0], z[1]);
+  box_muller(w.z, w.w, z[2], z[3]);
+#pragma unroll
+  for (int l = 0; l < 4; ++l) {
+    const int64_t e = q * 4 + l;
+    if (e < n_elems) {
+      if (bf16) ((bf16_t*)out)[e] = f32_to_bf16(z[l]);
+      else ((float*)out)[e] = z[l];
+    }
+  }
+}
+
+hipError_t launch_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block,
+                               int64_t n_blocks, uint32_t* out, hipStream_t st) {
+  if (n_blocks == 0) return hipSuccess;
+  const int64_t grid = (n_blocks + 255) / 256;
+  hipLaunchKernelGGL(k_philox_words, dim3((unsigned)grid), dim3(256), 0, st, seed, tensor_id, first_block,
+                     n_blocks, (uint4*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_factor_fill(uint64_t seed, uint32_t tensor_id, int64_t rows, int r, int bf16,
+                              void* out, hipStream_t st) {
+  const int64_t n = rows * r;
+  if (n == 0) return hipSuccess;
+  const int64_t blocks = (n + 3) / 4;
+  hipLaunchKernelGGL(k_factor_fill, dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, st, seed,
+                     tensor_id, n, bf16, out);
+  return hipGetLastError();
+}
+
+// ---- packing indices -----------------------------------------------------------------
+// tok_seq[t] = largest s with cu[s] <= t (empty sequences share an offset with
+// their successor; the last of them is the one that owns row t).
+__device__ __forceinline__ int seq_of_row(const int32_t* cu, int S, int t) {
+  int lo = 0, hi = S;  // invariant: cu[lo] <= t, answer in [lo, hi)
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu[mid] <= t) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+__global__ void k_tok_index(BatchDev b, int32_t* tok_seq, int32_t* tok_cand) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= b.T) return;
+  const int s = seq_of_row(b.cu, b.S, t);
+  if (tok_seq) tok_seq[t] = s;
+  if (tok_cand) tok_cand[t] = b.seq_cand[s];
+}
+
+hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_cand, hipStream_t st) {
+  if (b.T == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_tok_index, dim3((b.T + 255) / 256), dim3(256), 0, st, b, tok_seq, tok_cand);
+  return hipGetLastError();
+}
+
+// Per-sequence kind / scale and the list of side-down work items (chunks of at
+// most kSideRows rows of one sequence).  One workgroup; sequences are scanned in
+// blocks of 1024 so the item order follows the row order.
+__global__ __launch_bounds__(1024) void k_seq_tables(BatchDev b, float eps, SeqTables t) {
+  __shared__ int s_scan[1024];
+  __shared__ int s_carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) s_carry = 0;
+  __syncthreads();
+  for (int base = 0; base < b.S; base += 1024) {
+    const int s = base + tid;
+    int row0 = 0, len = 0, kind = kKindForeground, nchunk = 0;
+    float scale = 0.0f;
+    if (s < b.S) {
+      row0 = b.cu[s];
+      len = max(b.cu[s + 1] - row0, 0);
+      const int c = b.seq_cand[s];
+      if (c >= 0 && c < b.C) {
+        const int d = b.cand_dir[c];
+        const float sg = b.cand_sign[c];
+        if (d >= 0 && d < b.K && sg != 0.0f) { kind = d; scale = sg * eps; }
+        else kind = kKindCentre;
+      }
+      t.seq_kind[s] = kind;
+      t.seq_scale[s] = scale;
+      nchunk = (len + kSideRows - 1) / kSideRows;
+    }
+    s_scan[tid] = nchunk;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+      const int v = (tid >= off) ? s_scan[tid - off] : 0;
+      __syncthreads();
+      s_scan[tid] += v;
+      __syncthreads();
+    }
+    const int first = s_carry + s_scan[tid] - nchunk;
+    for (int j = 0; j < nchunk; ++j) {
+      if (first + j < t.max_items) {
+        SideItem it;
+        it.row0 = row0 + j * kSideRows;
+        it.nrows = min(kSideRows, len - j * kSideRows);
+        it.kind = kind;
+        it.scale = scale;
+        t.items[first + j] = it;
+      }
+    }
+    __syncthreads();
+    if (tid == 1023) s_carry += s_scan[1023];
+    __syncthreads();
+  }
+  if (tid == 0) *t.n_items = min(s_carry, t.max_items);
+}
+
+hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, hipStream_t st) {
+  hipLaunchKernelGGL(k_seq_tables, dim3(1), dim3(1024), 0, st, b, eps, t);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_tok_index(b, t.tok_seq, nullptr, st);
+}
+
+// ---- operand images ----------------------------------------------------------------------
+__global__ void k_image_U(BatchDev b, uint32_t tid_u, int m, int r, int RP, bf16_t* Uh) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_dir = (int64_t)m * RP;
+  if (idx >= per_dir * b.K) return;
+  const int k = (int)(idx / per_dir);
+  const int64_t rem = idx - (int64_t)k * per_dir;
+  const int i = (int)(rem / RP), j = (int)(rem % RP);
+  float z = 0.0f;
+  if (j < r) z = factor_normal(b.seed[k], tid_u, (uint64_t)i * r + j);
+  Uh[idx] = f32_to_bf16(z);
+}
+
+__global__ void k_image_Vt(BatchDev b, uint32_t tid_v, int n, int r, int RP, bf16_t* Vt) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_dir = (int64_t)n * RP;
+  if (idx >= per_dir * b.K) return;
+  const int k = (int)(idx / per_dir);
+  const int64_t rem = idx - (int64_t)k * per_dir;
+  const int j = (int)(rem / n), i = (int)(rem % n);
+  float z = 0.0f;
+  if (j < r) z = factor_normal(b.seed[k], tid_v, (uint64_t)i * r + j);
+  Vt[idx] = f32_to_bf16(z);
+}
+
+hipError_t launch_factor_images_bf16(const BatchDev& b, uint32_t tensor_id, int m, int n, int r, int RP,
+                                     uint16_t* Uh, uint16_t* Vt, hipStream_t st) {
+  if (b.K == 0) return hipSuccess;
+  const int64_t nu = (int64_t)b.K * m * RP, nv = (int64_t)b.K * n * RP;
+  hipLaunchKernelGGL(k_image_U, dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st, b, tensor_id & ~1u, m, r,
+                     RP, Uh);
+  hipLaunchKernelGGL(k_image_Vt, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st, b, tensor_id | 1u, n, r,
+                     RP, Vt);
+  return hipGetLastError();
+}
+
+__global__ void k_image_P(const float* P, int R_cap, int R_used, int Rp, int m, bf16_t* Ph) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)m * Rp) return;
+  const int i = (int)(idx / Rp), j = (int)(idx % Rp);
+  Ph[idx] = f32_to_bf16(j < R_used ? P[(int64_t)i * R_cap + j] : 0.0f);
+}
+
+// Vbt[j][i] = Vb[i][j]: 32x32 tiles through LDS so both sides are coalesced.
+__global__ void k_image_Vbt(const float* Vb, int R_cap, int R_used, int Rp, int n, bf16_t* Vbt) {
+  __shared__ float tile[32][33];
+  const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 256 threads: ty 0..7
+  for (int rr = ty; rr < 32; rr += 8) {
+    const int i = i0 + rr, j = j0 + tx;
+    tile[rr][tx] = (i < n && j < R_used) ? Vb[(int64_t)i * R_cap + j] : 0.0f;
+  }
+  __syncthreads();
+  for (int rr = ty; rr < 32; rr += 8) {
+    const int j = j0 + rr, i = i0 + tx;
+    if (j < Rp && i < n) Vbt[(int64_t)j * n + i] = f32_to_bf16(tile[tx][rr]);
+  }
+}
+
+hipError_t launch_bank_images_bf16(const float* P, const float* Vb, int R_cap, int R_used, int Rp,
+                                   int m, int n, uint16_t* Ph, uint16_t* Vbt, hipStream_t st) {
+  if (Rp == 0) return hipSuccess;
+  const int64_t np = (int64_t)m * Rp;
+  hipLaunchKernelGGL(k_image_P, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, P, R_cap, R_used, Rp, m, Ph);
+  hipLaunchKernelGGL(k_image_Vbt, dim3((n + 31) / 32, (Rp + 31) / 32), dim3(256), 0, st, Vb, R_cap, R_used, Rp,
+                     n, Vbt);
+  return hipGetLastError();
+}
+
+__global__ void k_factors_f32(BatchDev b, uint32_t tid, int rows, int r, float* out) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t per_dir = (int64_t)rows * r;
+  if (idx >= per_dir * b.K) return;
+  const int k = (int)(idx / per_dir);
+  out[idx] = factor_normal(b.seed[k], tid, (uint64_t)(idx - (int64_t)k * per_dir));
+}
+
+hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int n, int r,
+                              float* Uf, float* Vf, hipStream_t st) {
+  if (b.K == 0) return hipSuccess;
+  const int64_t nu = (int64_t)b.K * m * r, nv = (int64_t)b.K * n * r;
+  hipLaunchKernelGGL(k_factors_f32, dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st, b, tensor_id & ~1u, m, r, Uf);
+  hipLaunchKernelGGL(k_factors_f32, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st, b, tensor_id | 1u, n, r, Vf);
+  return hipGetLastError();
+}
+
+}  // namespace zo

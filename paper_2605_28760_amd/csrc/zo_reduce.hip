@@ -1,0 +1,138 @@
+// Small reduction kernels: merging the per-vocabulary-tile softmax partials
+// into token / sequence / candidate NLL (Sec. 3.3: device-resident per-request
+// NLL), the antithetic two-point estimate (Sec. 2.1, Eq. 2) and the lazy bank
+// update (Sec. 3.2, Eq. "layer-coupling").  All reductions run in a fixed
+// order; a sequence's sum is ordered relative to its own first row, so it does
+// not depend on where the sequence sits in the packed batch.
+#include "zo_device.hpp"
+#include "zo_internal.hpp"
+
+namespace zo {
+
+__global__ void k_tok_nll(ScoreCombineArgs a) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= a.T) return;
+  if (a.targets[t] < 0) { a.tok_nll[t] = 0.0f; return; }
+  float M = -INFINITY;
+  for (int j = 0; j < a.n_vt; ++j) M = fmaxf(M, a.part_max[(int64_t)j * a.T + t]);
+  float S = 0.0f;
+  for (int j = 0; j < a.n_vt; ++j)
+    S += a.part_sum[(int64_t)j * a.T + t] * expf(a.part_max[(int64_t)j * a.T + t] - M);
+  a.tok_nll[t] = (M + logf(S)) - a.tgt_logit[t];
+}
+
+// One workgroup per sequence: thread i takes rows i, i+256, ... of the sequence,
+// then a fixed binary tree over the 256 partial sums.
+__global__ __launch_bounds__(256) void k_seq_nll(ScoreCombineArgs a) {
+  __shared__ float s_sum[256];
+  __shared__ int s_cnt[256];
+  const int s = blockIdx.x, tid = threadIdx.x;
+  const int lo = a.cu[s], hi = a.cu[s + 1];
+  float sum = 0.0f;
+  int cnt = 0;
+  for (int t = lo + tid; t < hi; t += 256) {
+    sum += a.tok_nll[t];
+    cnt += a.targets[t] >= 0 ? 1 : 0;
+  }
+  s_sum[tid] = sum;
+  s_cnt[tid] = cnt;
+  __syncthreads();
+  for (int off = 128; off > 0; off >>= 1) {
+    if (tid < off) { s_sum[tid] += s_sum[tid + off]; s_cnt[tid] += s_cnt[tid + off]; }
+    __syncthreads();
+  }
+  if (tid == 0) { a.seq_nll[s] = s_sum[0]; a.seq_cnt[s] = s_cnt[0]; }
+}
+
+// Candidate c sums its sequences in sequence order.
+__global__ void k_cand_sum(ScoreCombineArgs a) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= a.C) return;
+  float sum = 0.0f;
+  int cnt = 0;
+  for (int s = 0; s < a.S; ++s)
+    if (a.seq_cand[s] == c) { sum += a.seq_nll[s]; cnt += a.seq_cnt[s]; }
+  a.cand_sum[c] = sum;
+  a.cand_cnt[c] = cnt;
+}
+
+hipError_t launch_score_combine(const ScoreCombineArgs& a, hipStream_t st) {
+  if (a.T > 0) hipLaunchKernelGGL(k_tok_nll, dim3((a.T + 255) / 256), dim3(256), 0, st, a);
+  if (a.S > 0) hipLaunchKernelGGL(k_seq_nll, dim3(a.S), dim3(256), 0, st, a);
+  if (a.C > 0) hipLaunchKernelGGL(k_cand_sum, dim3((a.C + 63) / 64), dim3(64), 0, st, a);
+  return hipGetLastError();
+}
+
+__global__ void k_estimate(BatchDev b, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                           int reduction, float* cand_loss, float* proj_grad) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  auto loss_of = [&](int c) {
+    return reduction == 0 ? cand_sum[c] / (float)max(cand_cnt[c], 1) : cand_sum[c];
+  };
+  if (i < b.C) cand_loss[i] = loss_of(i);
+  if (i < b.K) {
+    int cp = -1, cm = -1;
+    for (int c = 0; c < b.C; ++c) {
+      if (b.cand_dir[c] != i) continue;
+      const float sg = b.cand_sign[c];
+      if (sg > 0.0f && cp < 0) cp = c;
+      if (sg < 0.0f && cm < 0) cm = c;
+    }
+    proj_grad[i] = (cp >= 0 && cm >= 0) ? (loss_of(cp) - loss_of(cm)) / (2.0f * eps) : 0.0f;
+  }
+}
+
+hipError_t launch_estimate(const BatchDev& b, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                           int reduction, float* cand_loss, float* proj_grad, hipStream_t st) {
+  const int n = b.C > b.K ? b.C : b.K;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_estimate, dim3((n + 63) / 64), dim3(64), 0, st, b, cand_sum, cand_cnt, eps, reduction,
+                     cand_loss, proj_grad);
+  return hipGetLastError();
+}
+
+// ---- lazy bank update ---------------------------------------------------------------------
+constexpr int kBankBatch = 32;
+struct BankCols { int32_t first_dir; int32_t n; int32_t col0[kBankBatch]; };
+
+// grid.y = direction within the batch; grid.x covers max(m, n) * r entries.
+__global__ void k_bank_update(BankUpdateArgs a, BankCols cols) {
+  const int kb = blockIdx.y;
+  const int k = cols.first_dir + kb;
+  const int col0 = cols.col0[kb];
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const uint64_t seed = a.seed[k];
+  if (idx < (int64_t)a.m * a.r) {
+    const int i = (int)(idx / a.r), j = (int)(idx % a.r);
+    const float w = a.dir_weight ? a.dir_weight[k] : a.default_weight;
+    const float beta = -a.lr * a.proj_grad[k] * w;
+    float u = factor_normal(seed, a.tensor_id & ~1u, (uint64_t)idx);
+    if (a.bf16) u = bf16_round(u);
+    float* dst = a.P + (int64_t)i * a.R_cap + col0 + j;
+    *dst = a.append ? beta * u : fmaf(beta, u, *dst);
+  }
+  if (a.append && idx < (int64_t)a.n * a.r) {
+    const int i = (int)(idx / a.r), j = (int)(idx % a.r);
+    float v = factor_normal(seed, a.tensor_id | 1u, (uint64_t)idx);
+    if (a.bf16) v = bf16_round(v);
+    a.Vb[(int64_t)i * a.R_cap + col0 + j] = v;
+  }
+}
+
+hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st) {
+  const int rows = a.append ? (a.m > a.n ? a.m : a.n) : a.m;
+  const int64_t total = (int64_t)rows * a.r;
+  if (total == 0) return hipSuccess;
+  for (int first = 0; first < n_dirs; first += kBankBatch) {
+    BankCols cols;
+    cols.first_dir = first;
+    cols.n = n_dirs - first < kBankBatch ? n_dirs - first : kBankBatch;
+    for (int i = 0; i < kBankBatch; ++i) cols.col0[i] = i < cols.n ? col0[first + i] : 0;
+    hipLaunchKernelGGL(k_bank_update, dim3((unsigned)((total + 255) / 256), cols.n), dim3(256), 0, st, a, cols);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace zo

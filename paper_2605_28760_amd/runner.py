@@ -1,0 +1,122 @@
+"""Device-side driver for a synthetic workload: uploads the arrays once,
+allocates outputs and workspaces with torch (device memory and streams only)
+and sequences the C-ABI calls of one step:
+
+    zo_probe_linear (per layer) -> zo_score -> zo_estimate -> zo_bank_update
+
+Nothing is computed here; every number comes out of libzo.so.
+"""
+import numpy as np
+import torch
+
+from . import binding as zb
+
+
+def _dt(dtype):
+    return zb.ZO_BF16 if dtype == "bf16" else zb.ZO_F32
+
+
+def _tt(dtype):
+    return torch.bfloat16 if dtype == "bf16" else torch.float32
+
+
+class DeviceBatch:
+    """Batch arrays on the device plus the zo_batch struct that points at them."""
+
+    def __init__(self, cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed, device, host_mirrors=True):
+        self.host = dict(cu=np.ascontiguousarray(cu_seqlens, np.int32), seq_cand=np.ascontiguousarray(seq_cand, np.int32),
+                         cand_dir=np.ascontiguousarray(cand_dir, np.int32))
+        self.cu = torch.from_numpy(self.host["cu"]).to(device)
+        self.seq_cand = torch.from_numpy(self.host["seq_cand"]).to(device)
+        self.cand_dir = torch.from_numpy(self.host["cand_dir"]).to(device)
+        self.cand_sign = torch.from_numpy(np.ascontiguousarray(cand_sign, np.float32)).to(device)
+        # torch has no uint64 arithmetic; the seeds travel as the same 64 bits in an int64 tensor
+        self.dir_seed = torch.from_numpy(np.ascontiguousarray(dir_seed, np.uint64).view(np.int64)).to(device)
+        self.T = int(self.host["cu"][-1])
+        self.S, self.C, self.K = len(self.host["seq_cand"]), len(self.host["cand_dir"]), len(dir_seed)
+        mir = self.host if host_mirrors else dict(cu=None, seq_cand=None, cand_dir=None)
+        self.struct = zb.make_batch(self.T, self.cu, self.seq_cand, self.cand_dir, self.cand_sign, self.dir_seed,
+                                    mir["cu"], mir["seq_cand"], mir["cand_dir"],
+                                    n_seqs=self.S, n_cands=self.C, n_dirs=self.K)
+
+
+class DeviceLayer:
+    def __init__(self, layer, dtype, device):
+        self.name, self.m, self.n, self.tensor_id, self.act = layer.name, layer.m, layer.n, layer.tensor_id, layer.act
+        self.W = torch.from_numpy(layer.W).to(device=device, dtype=_tt(dtype)).contiguous()
+        self.X = None if layer.X is None else torch.from_numpy(layer.X).to(device=device, dtype=_tt(dtype)).contiguous()
+        self.bank = None
+        self.P = self.Vb = None
+        if layer.P is not None:
+            self.P = torch.from_numpy(layer.P).to(device).contiguous()
+            self.Vb = torch.from_numpy(layer.Vb).to(device).contiguous()
+            self.bank = zb.make_bank(layer.P.shape[1], layer.R_used, self.P, self.Vb)
+
+
+class DeviceWorkload:
+    def __init__(self, w, device="cuda:0", host_mirrors=True, out_dtype=None):
+        self.w = w
+        self.device = torch.device(device)
+        self.dtype = w.dtype
+        self.out_dtype = out_dtype or w.dtype
+        self.batch = DeviceBatch(w.cu_seqlens, w.seq_cand, w.cand_dir, w.cand_sign, w.dir_seed, self.device, host_mirrors)
+        self.layers = [DeviceLayer(l, w.dtype, self.device) for l in w.layers]
+        self.X = None if w.X is None else torch.from_numpy(w.X).to(device=self.device, dtype=_tt(w.dtype)).contiguous()
+        self.head = None if w.head is None else torch.from_numpy(w.head).to(device=self.device, dtype=_tt(w.dtype)).contiguous()
+        self.targets = None if w.targets is None else torch.from_numpy(np.ascontiguousarray(w.targets, np.int32)).to(self.device)
+        b = self.batch
+        T = b.T
+        self.Y = [torch.empty((T, l.m), device=self.device, dtype=_tt(self.out_dtype)) for l in self.layers]
+        ws = 0
+        for l in self.layers:
+            R = l.bank.R_used if l.bank is not None else 0
+            ws = max(ws, zb.zo_probe_linear_workspace_bytes(T, b.S, b.K, l.m, l.n, w.r, R, _dt(w.dtype)))
+        if self.head is not None:
+            ws = max(ws, zb.zo_score_workspace_bytes(T, b.S, self.head.shape[0], self.head.shape[1], _dt(w.dtype)))
+        self.ws_bytes = ws
+        self.ws = torch.empty(max(ws, 256), device=self.device, dtype=torch.uint8)
+        self.tok_nll = torch.empty(T, device=self.device, dtype=torch.float32)
+        self.seq_nll = torch.empty(b.S, device=self.device, dtype=torch.float32)
+        self.cand_sum = torch.empty(b.C, device=self.device, dtype=torch.float32)
+        self.cand_cnt = torch.empty(b.C, device=self.device, dtype=torch.int32)
+        self.cand_loss = torch.empty(b.C, device=self.device, dtype=torch.float32)
+        self.proj_grad = torch.empty(b.K, device=self.device, dtype=torch.float32)
+
+    # -- single calls -------------------------------------------------------------------
+    def probe_linear(self, i, X=None, stream=None, batch=None):
+        l = self.layers[i]
+        x = X if X is not None else (l.X if l.X is not None else (self.X if i == 0 else self.Y[i - 1]))
+        y = self.Y[i]
+        zb.zo_probe_linear((batch or self.batch).struct, x, x.stride(0), l.W, l.W.stride(0), None, l.m, l.n,
+                           _dt(self.dtype), self.w.r, float(self.w.eps), l.tensor_id, l.bank, l.act,
+                           y, y.stride(0), _dt(self.out_dtype), self.ws, self.ws_bytes, stream)
+        return y
+
+    def score(self, H=None, stream=None, batch=None):
+        h = H if H is not None else self.Y[-1]
+        zb.zo_score((batch or self.batch).struct, h, h.stride(0), self.head, self.head.stride(0), self.head.shape[0],
+                    self.head.shape[1], _dt(self.dtype), self.targets, self.tok_nll, self.seq_nll, self.cand_sum,
+                    self.cand_cnt, self.ws, self.ws_bytes, stream)
+
+    def estimate(self, stream=None):
+        zb.zo_estimate(self.batch.struct, self.cand_sum, self.cand_cnt, float(self.w.eps), self.w.reduction,
+                       self.cand_loss, self.proj_grad, stream)
+
+    def bank_update(self, i, lr, col0, append=0, dir_weight=None, stream=None):
+        l = self.layers[i]
+        col0 = np.ascontiguousarray(col0, np.int32)
+        zb.zo_bank_update(l.bank, l.m, l.n, self.w.r, self.batch.K, self.batch.dir_seed, l.tensor_id,
+                          self.proj_grad, float(lr), dir_weight, col0, append, _dt(self.dtype), stream)
+
+    # -- one pass of the whole path --------------------------------------------------------
+    def step(self, lr=1e-7, update=True, stream=None):
+        for i in range(len(self.layers)):
+            self.probe_linear(i, stream=stream)
+        if self.head is not None and self.w.chain:
+            self.score(stream=stream)
+            self.estimate(stream=stream)
+            if update:
+                for i, l in enumerate(self.layers):
+                    if l.bank is not None and l.bank.R_used >= self.w.r * self.batch.K:
+                        col0 = np.arange(self.batch.K, dtype=np.int32) * self.w.r
+                        self.bank_update(i, lr, col0, 0, stream=stream)

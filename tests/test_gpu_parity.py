@@ -1,0 +1,309 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle,
+element by element, on seeded inputs that span several tiles and ragged tails.
+Tolerances: integers bit-exact; fp32 outputs rel 1e-5; bf16-in / fp32-accumulate
+outputs rel 2e-2; per-candidate mean loss abs 1e-3; projected gradient rel 5e-2
+(rel means |got - want| <= rtol * max(|want|, rms(want)))."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import philox as px
+from oracle import zo_oracle as zo
+from paper_2605_28760_amd import binding as zb
+from paper_2605_28760_amd import workloads as wl
+from paper_2605_28760_amd.runner import DeviceWorkload, DeviceBatch
+from zo_testlib import assert_close, oracle_batch, oracle_bank, oracle_chain, oracle_layer, to_np
+
+DEV = "cuda:0"
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+# ---- integer streams and indices: bit-exact --------------------------------------------
+@pytest.mark.parametrize("seed,tid,first,nblk", [
+    (0, 0, 0, 1), (0x5EED0000, 3, 0, 4097), (0xFFFFFFFFFFFFFFFF, 0xFFFFFFFF, 0xFFFFFFFF - 10, 64),
+    (0x0123456789ABCDEF, 8, (7 << 32) + 5, 1000)])
+def test_philox_words_bit_exact(seed, tid, first, nblk):
+    out = torch.empty((nblk, 4), device=DEV, dtype=torch.int32)
+    zb.zo_philox_words(seed, tid, first, nblk, out); _sync()
+    got = out.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, px.factor_words(seed, tid, nblk, first_block=first))
+
+
+@pytest.mark.parametrize("rows,r", [(1, 1), (5, 3), (1000, 2), (4096, 8), (777, 16), (300, 64)])
+def test_factor_fill_matches_oracle(rows, r):
+    seed, tid = 0x5EED0000 + rows, 6
+    out = torch.empty((rows, r), device=DEV, dtype=torch.float32)
+    zb.zo_factor_fill(seed, tid, rows, r, zb.ZO_F32, out); _sync()
+    want = px.factor_matrix(seed, tid, rows, r, "f32")
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want) + 1e-6)
+    assert np.mean(got == want) > 0.5          # most entries agree to the last bit
+    ob = torch.empty((rows, r), device=DEV, dtype=torch.bfloat16)
+    zb.zo_factor_fill(seed, tid, rows, r, zb.ZO_BF16, ob); _sync()
+    wantb = px.factor_matrix(seed, tid, rows, r, "bf16")
+    gotb = ob.float().cpu().numpy().astype(np.float64)
+    # the rounding decision is taken on fp32 values that may differ in the last bit:
+    # at most one bf16 step apart, and only rarely
+    assert np.all(np.abs(gotb - wantb) <= np.abs(wantb) * 2.0 ** -7 + 1e-30)
+    assert np.mean(gotb == wantb) >= 0.999 or rows * r < 1000
+
+
+def test_batch_index_bit_exact():
+    rng = np.random.default_rng(0)
+    lens = rng.integers(0, 40, size=300); lens[[0, 5, 6, 299]] = 0
+    cu = np.zeros(301, np.int32); cu[1:] = np.cumsum(lens)
+    seq_cand = rng.integers(-1, 6, size=300).astype(np.int32)
+    b = zo.Batch(cu, seq_cand, np.array([0, 0, 1, 1, -1, 2], np.int32), np.array([1, -1, 1, -1, 0, 1], np.float32),
+                 np.arange(3, dtype=np.uint64))
+    db = DeviceBatch(b.cu_seqlens, b.seq_cand, b.cand_dir, b.cand_sign, b.dir_seed, DEV)
+    ts = torch.empty(db.T, device=DEV, dtype=torch.int32); tc = torch.empty_like(ts)
+    zb.zo_batch_index(db.struct, ts, tc); _sync()
+    want_seq, want_cand = zo.batch_indices(b)
+    assert np.array_equal(ts.cpu().numpy(), want_seq) and np.array_equal(tc.cpu().numpy(), want_cand)
+
+
+# ---- config 1: fp32 end to end ------------------------------------------------------------
+def test_config1_fp32_end_to_end():
+    w = wl.tiny_fp32()
+    d = DeviceWorkload(w, DEV)
+    w_before = d.layers[0].W.clone()
+    d.step(update=False); _sync()
+    ref = oracle_chain(w)
+    assert_close(to_np(d.Y[0]), ref["Y"][0].astype(np.float32), 1e-5, "Y")
+    # scoring parity on the GPU's own activations, then end to end
+    tok, seq, cs, cc = zo.score(oracle_batch(w), to_np(d.Y[0]), w.head, w.targets)
+    assert_close(to_np(d.tok_nll), tok, 1e-5, "tok_nll")
+    assert_close(to_np(d.seq_nll), seq, 1e-5, "seq_nll")
+    assert np.array_equal(to_np(d.cand_cnt), ref["cand_cnt"])
+    assert np.max(np.abs(to_np(d.cand_loss) - ref["cand_loss"])) <= 1e-3
+    assert_close(to_np(d.proj_grad), ref["proj_grad"], 5e-2, "proj_grad")
+    assert ref["proj_grad"][0] != 0
+    assert torch.equal(w_before, d.layers[0].W)          # the base is never written
+
+
+def test_fp32_ragged_with_bank_and_mixed_rows():
+    w = wl.mixed_foreground(hidden=72, ffn=100, vocab=333, n_ex=5, n_fg=3, len_lo=1, len_hi=37, r=3, R=5, dtype="f32")
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False); _sync()
+    H = w.X
+    for i in range(2):
+        assert_close(to_np(d.Y[i]), oracle_layer(w, i, H), 1e-5, "Y%d" % i)
+        H = to_np(d.Y[i])
+    tok, seq, cs, cc = zo.score(oracle_batch(w), H, w.head, w.targets)
+    assert_close(to_np(d.tok_nll), tok, 1e-5, "tok_nll")
+    assert_close(to_np(d.cand_sum), cs, 1e-5, "cand_sum")
+    assert np.array_equal(to_np(d.cand_cnt), cc)
+    # foreground rows: bit-identical to an all-foreground call
+    y_mixed = [y.clone() for y in d.Y]
+    fg = wl.foreground_only(w)
+    dfg = DeviceWorkload(fg, DEV)
+    dfg.step(update=False); _sync()
+    rows = torch.from_numpy(np.nonzero(zo.batch_indices(oracle_batch(w))[1] < 0)[0]).to(DEV)
+    assert len(rows) > 0
+    assert torch.equal(y_mixed[0][rows], dfg.Y[0][rows])
+
+
+# ---- bf16 matrix-core path on reduced shapes (several tiles, ragged tails) -----------------
+def _per_layer_parity(w, d, rtol=2e-2):
+    H = w.X
+    for i in range(len(w.layers)):
+        x_in = w.layers[i].X if w.layers[i].X is not None else H
+        want = oracle_layer(w, i, x_in, out_dtype=d.out_dtype)
+        assert_close(to_np(d.Y[i]), want, rtol, "Y[%s]" % w.layers[i].name)
+        H = to_np(d.Y[i])
+    return H
+
+
+def test_bf16_layer_set_with_bank():
+    """Config-2 structure on reduced shapes: six independent linears, r = 8, bank R = 64."""
+    w = wl.opt_layer_set(hidden=320, ffn=1280, n_ex=3, seq_len=111, r=8, R=64)
+    d = DeviceWorkload(w, DEV)
+    for i in range(len(w.layers)):
+        d.probe_linear(i)
+    _sync()
+    _per_layer_parity(w, d)
+
+
+def test_bf16_side_term_isolated_fp32_out():
+    """Y_+ - Y_- on duplicated rows equals 2 eps (X V) U^T: checks the probe term
+    itself to 2e-2 (on Y alone it hides behind the base GEMM)."""
+    w = wl.opt_layer_set(hidden=256, ffn=512, n_ex=2, seq_len=150, r=8, R=0)
+    d = DeviceWorkload(w, DEV, out_dtype="f32")
+    L = 150
+    for i in (0, 4, 5):
+        l = w.layers[i]
+        y = to_np(d.probe_linear(i)); _sync()
+        U = px.factor_matrix(int(w.dir_seed[0]), l.tensor_id, l.m, w.r, "bf16")
+        V = px.factor_matrix(int(w.dir_seed[0]), l.tensor_id + 1, l.n, w.r, "bf16")
+        want = 2 * w.eps * (l.X[:L].astype(np.float64) @ V) @ U.T
+        assert_close(y[:L] - y[L:2 * L], want, 2e-2, "side term of %s" % l.name, atol=2e-5)
+        assert_close(y, oracle_layer(w, i, l.X, out_dtype="f32"), 2e-2, "Y fp32 out")
+
+
+@pytest.mark.parametrize("builder,kw", [
+    (wl.opt_scoring, dict(hidden=256, ffn=512, vocab=1000, n_ex=5, seq_len=77, r=8, R=64)),
+    (wl.ragged_packed, dict(hidden=256, ffn=384, vocab=1187, n_ex=8, n_dirs=4, len_lo=1, len_hi=140, r=16, R=32)),
+    (wl.mixed_foreground, dict(hidden=192, ffn=448, vocab=777, n_ex=6, n_fg=5, len_lo=3, len_hi=160, r=16, R=48)),
+    (wl.ragged_packed, dict(hidden=128, ffn=256, vocab=300, n_ex=6, n_dirs=3, len_lo=1, len_hi=50, r=2, R=0)),
+])
+def test_bf16_chain_parity(builder, kw):
+    w = builder(**kw)
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False); _sync()
+    H = _per_layer_parity(w, d)
+    b = oracle_batch(w)
+    tok, seq, cs, cc = zo.score(b, H, w.head, w.targets)
+    assert_close(to_np(d.tok_nll), tok, 1e-4, "tok_nll", atol=1e-4)
+    assert_close(to_np(d.seq_nll), seq, 1e-4, "seq_nll", atol=1e-3)
+    assert_close(to_np(d.cand_sum), cs, 1e-4, "cand_sum", atol=1e-3)
+    assert np.array_equal(to_np(d.cand_cnt), cc)
+    loss, grad = zo.estimate(b, cs, cc, w.eps, w.reduction)
+    assert_close(to_np(d.cand_loss), loss, 1e-4, "cand_loss", atol=1e-3 if w.reduction == 0 else 1e-2)
+    assert_close(to_np(d.proj_grad), grad, 5e-2, "proj_grad (same activations)")
+    # end to end against the oracle's own chain
+    ref = oracle_chain(w)
+    if w.reduction == 0:
+        assert np.max(np.abs(to_np(d.cand_loss) - ref["cand_loss"])) <= 1e-3
+    assert_close(to_np(d.proj_grad), ref["proj_grad"], 5e-2, "proj_grad (end to end)")
+
+
+def test_foreground_rows_bit_identical_and_base_immutable():
+    """Mixed batch (config 5 structure): foreground rows of every layer and their
+    token NLL equal, bit for bit, (i) the same batch with every sequence
+    foreground and (ii) the foreground sequences run alone; W is never written."""
+    w = wl.mixed_foreground(hidden=192, ffn=448, vocab=777, n_ex=6, n_fg=5, len_lo=3, len_hi=160, r=16, R=48)
+    d = DeviceWorkload(w, DEV)
+    w_sum = [l.W.view(torch.int16).to(torch.int64).sum().item() for l in d.layers]
+    d.step(update=False); _sync()
+    tok_cand = zo.batch_indices(oracle_batch(w))[1]
+    rows = torch.from_numpy(np.nonzero(tok_cand < 0)[0]).to(DEV)
+    assert 0 < len(rows) < d.batch.T
+    mixed = [y[rows].clone() for y in d.Y] + [d.tok_nll[rows].clone()]
+    fg_seqs = np.nonzero(w.seq_cand < 0)[0]
+    mixed_seq = d.seq_nll[torch.from_numpy(fg_seqs).to(DEV)].clone()
+    assert [l.W.view(torch.int16).to(torch.int64).sum().item() for l in d.layers] == w_sum
+
+    allfg = DeviceWorkload(wl.foreground_only(w), DEV)
+    allfg.step(update=False); _sync()
+    for a, y in zip(mixed[:-1], allfg.Y):
+        assert torch.equal(a, y[rows])
+    assert torch.equal(mixed[-1], allfg.tok_nll[rows])
+
+    alone = DeviceWorkload(wl.foreground_only(w, keep_only_foreground=True), DEV)
+    alone.step(update=False); _sync()
+    for a, y in zip(mixed[:-1], alone.Y):
+        assert torch.equal(a, y)
+    assert torch.equal(mixed[-1], alone.tok_nll)
+    assert torch.equal(mixed_seq, alone.seq_nll)
+
+
+def test_batch_invariance_and_determinism():
+    """A sequence's activations and NLL do not depend on what else is in the
+    batch or where it sits (the paper's sample-level batch-invariance check);
+    two runs are bitwise equal (no atomics)."""
+    w = wl.ragged_packed(hidden=256, ffn=384, vocab=1187, n_ex=8, n_dirs=4, len_lo=1, len_hi=140, r=16, R=32)
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False); _sync()
+    first = [y.clone() for y in d.Y] + [d.tok_nll.clone(), d.seq_nll.clone(), d.cand_sum.clone(), d.proj_grad.clone()]
+    d.step(update=False); _sync()
+    for a, b_ in zip(first, d.Y + [d.tok_nll, d.seq_nll, d.cand_sum, d.proj_grad]):
+        assert torch.equal(a, b_)
+    # reverse the sequence order
+    import copy
+    S = len(w.seq_cand)
+    perm = np.arange(S)[::-1]
+    lens = np.diff(w.cu_seqlens)
+    w2 = copy.copy(w)
+    rows = np.concatenate([np.arange(w.cu_seqlens[s], w.cu_seqlens[s + 1]) for s in perm])
+    cu2 = np.zeros(S + 1, np.int32); cu2[1:] = np.cumsum(lens[perm])
+    w2.cu_seqlens, w2.seq_cand, w2.X, w2.targets = cu2, w.seq_cand[perm].copy(), w.X[rows], w.targets[rows]
+    d2 = DeviceWorkload(w2, DEV)
+    d2.step(update=False); _sync()
+    rows_t = torch.from_numpy(rows).to(DEV)
+    for a, b_ in zip(first[:2], d2.Y):
+        assert torch.equal(a[rows_t], b_)
+    assert torch.equal(first[2][rows_t], d2.tok_nll)
+    assert torch.equal(first[3][torch.from_numpy(perm.copy()).to(DEV)], d2.seq_nll)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bank_update_parity(dtype):
+    m, n, r, K, R_cap = 300, 200, 4, 3, 16
+    rng = np.random.default_rng(5)
+    P = (rng.standard_normal((m, R_cap)) * 0.01).astype(np.float32)
+    Vb = (rng.standard_normal((n, R_cap)) * 0.01).astype(np.float32)
+    seeds = np.array([11, 12, 13], np.uint64)
+    b = zo.Batch(np.array([0, 1], np.int32), np.array([0], np.int32), np.array([0], np.int32), np.array([1.0], np.float32), seeds)
+    grads = np.array([0.5, -2.0, 1.25], np.float32)
+    Pd, Vd = torch.from_numpy(P).to(DEV), torch.from_numpy(Vb).to(DEV)
+    bank = zb.make_bank(R_cap, 12, Pd, Vd)
+    g = torch.from_numpy(grads).to(DEV)
+    sd = torch.from_numpy(seeds.view(np.int64)).to(DEV)
+    dt = zb.ZO_BF16 if dtype == "bf16" else zb.ZO_F32
+    # accumulate into three existing blocks with default weights 1/K
+    zb.zo_bank_update(bank, m, n, r, K, sd, 4, g, 0.1, None, np.array([0, 4, 8], np.int32), 0, dt); _sync()
+    want = zo.bank_update(zo.Bank(P, Vb, 12), b, m, n, r, 4, grads, 0.1, [0, 4, 8], factor_dtype=dtype)
+    assert_close(Pd.cpu().numpy(), want.P, 1e-5, "P accumulate")
+    assert torch.equal(Vd.cpu(), torch.from_numpy(Vb)) and bank.R_used == 12
+    # open a new block with explicit weights
+    wts = torch.tensor([2.0], device=DEV)
+    zb.zo_bank_update(bank, m, n, r, 1, sd[2:], 4, g[2:], 0.1, wts, np.array([12], np.int32), 1, dt); _sync()
+    b1 = zo.Batch(b.cu_seqlens, b.seq_cand, b.cand_dir, b.cand_sign, seeds[2:])
+    want2 = zo.bank_update(want, b1, m, n, r, 4, grads[2:], 0.1, [12], dir_weight=[2.0], append=True, factor_dtype=dtype)
+    assert bank.R_used == 16 == want2.R_used
+    assert_close(Pd.cpu().numpy(), want2.P, 1e-5, "P append")
+    tol = 1e-5 if dtype == "f32" else 2.0 ** -7
+    assert np.all(np.abs(Vd.cpu().numpy().astype(np.float64) - want2.Vb) <= tol * np.abs(want2.Vb) + 1e-6)
+    with pytest.raises(zb.ZoError) as e:
+        zb.zo_bank_update(bank, m, n, r, 1, sd, 4, g, 0.1, None, np.array([14], np.int32), 1, dt)
+    assert e.value.status == zb.ZO_ERR_BANK_FULL
+
+
+def test_lazy_update_then_probe_matches_oracle():
+    """One full step with update, then a second forward: the bank the GPU wrote
+    must act in the next probe exactly as the oracle's updated bank does."""
+    w = wl.opt_scoring(hidden=256, ffn=512, vocab=1000, n_ex=4, seq_len=70, r=8, R=64)
+    d = DeviceWorkload(w, DEV)
+    d.step(lr=1e-3, update=True); _sync()
+    grads = to_np(d.proj_grad)
+    ob = oracle_batch(w)
+    import copy
+    w2 = copy.copy(w)
+    w2.layers = [copy.copy(l) for l in w.layers]
+    for l in w2.layers:
+        nb = zo.bank_update(oracle_bank(l), ob, l.m, l.n, w.r, l.tensor_id, grads, 1e-3, [0], factor_dtype="bf16")
+        l.P, l.Vb = nb.P, nb.Vb
+    for i, l in enumerate(w2.layers):
+        assert_close(d.layers[i].P.cpu().numpy(), l.P, 1e-5, "P after update")
+    d.step(update=False); _sync()
+    _per_layer_parity(w2, d)
+
+
+def test_no_candidates_and_empty_batches():
+    w = wl.opt_scoring(hidden=128, ffn=256, vocab=300, n_ex=2, seq_len=40, r=8, R=16)
+    fg = wl.foreground_only(w)
+    d = DeviceWorkload(fg, DEV)
+    d.step(update=False); _sync()
+    H = _per_layer_parity(fg, d)
+    assert np.all(to_np(d.cand_cnt) == 0) and np.all(to_np(d.cand_sum) == 0) and np.all(to_np(d.proj_grad) == 0)
+    tok, seq, _, _ = zo.score(oracle_batch(fg), H, fg.head, fg.targets)
+    assert_close(to_np(d.seq_nll), seq, 1e-4, "foreground seq_nll", atol=1e-3)
+    # unscored rows (negative targets) and an empty sequence in the middle
+    import copy
+    w3 = copy.copy(w)
+    w3.targets = w.targets.copy(); w3.targets[::3] = -1
+    cu = w.cu_seqlens.copy()
+    w3.cu_seqlens = np.concatenate([cu[:2], cu[1:]]).astype(np.int32)       # duplicate an offset: empty sequence 1
+    w3.seq_cand = np.concatenate([w.seq_cand[:1], [1], w.seq_cand[1:]]).astype(np.int32)
+    d3 = DeviceWorkload(w3, DEV)
+    d3.step(update=False); _sync()
+    H3 = _per_layer_parity(w3, d3)
+    tok, seq, cs, cc = zo.score(oracle_batch(w3), H3, w3.head, w3.targets)
+    assert np.array_equal(to_np(d3.cand_cnt), cc) and to_np(d3.seq_nll)[1] == 0
+    assert_close(to_np(d3.tok_nll), tok, 1e-4, "tok_nll with unscored rows", atol=1e-4)
+    assert np.all(to_np(d3.tok_nll)[::3] == 0)
