@@ -1,0 +1,154 @@
+"""Benchmark of the candidate-evaluation hot path on one MI355X.
+
+One "step" is one pass of the whole path over one synthetic batch that is
+already resident in HBM: probe linears (factor generation, side-down
+projection, MFMA GEMM with side state), fused LM-head scoring, two-point
+estimate and lazy bank update.  The default workload is the OPT-13B-shaped
+scoring chain at batch 64 (64 sequences x 128 tokens x {+,-}, r = 8, bank
+rank 64, vocabulary 50272): the configuration of the paper's headline 98.2 %
+query-share figure and the one on which "candidate-tokens scored/sec (probe
+linear + LM-head scoring)" is defined.
+
+Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured for a workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def _cpu_baseline(w, budget_hint_s=20.0):
+    """The oracle as it stands, timed on the host cores over a bounded sample
+    (the first +/- pair of sequences) of the same workload."""
+    import numpy as np
+    from oracle import zo_oracle as zo
+    from paper_2605_28760_amd import workloads as wl
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n_seq = 2
+    sub = wl.subset_sequences(w, list(range(n_seq)))
+    t0 = time.perf_counter()
+    out = zo.run_chain(zo.Batch(sub.cu_seqlens, sub.seq_cand, sub.cand_dir, sub.cand_sign, sub.dir_seed),
+                       sub.X, sub.layers, sub.head, sub.targets, sub.r, sub.eps, sub.dtype, sub.reduction)
+    dt = time.perf_counter() - t0
+    return {"value": sub.T / dt, "unit": "candidate-tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "first %d sequences (%d of %d rows) of the same workload, whole chain in fp64 NumPy, %.1f s"
+                      % (n_seq, sub.T, w.T, dt)}, out, sub
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by sequences; see DESIGN.md); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_28760_amd import binding as zb
+    from paper_2605_28760_amd import workloads as wl
+    from paper_2605_28760_amd.runner import DeviceWorkload
+
+    zb.lib()   # fails loudly if the HIP library is missing
+    t_gen = time.perf_counter()
+    w = wl.BUILDERS[args.workload]()
+    d = DeviceWorkload(w, "cuda:0")
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t_gen
+    stream = torch.cuda.current_stream()
+    T = w.T
+    vocab, hid = w.head.shape
+    col0 = np.arange(d.batch.K, dtype=np.int32) * w.r
+    n_layers = len(d.layers)
+    names = [l.name for l in d.layers] + ["score", "estimate", "bank_update"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record(stream)
+        mark(0)
+        for i in range(n_layers):
+            d.probe_linear(i, stream=stream)
+            mark(i + 1)
+        d.score(stream=stream)
+        mark(n_layers + 1)
+        d.estimate(stream=stream)
+        mark(n_layers + 2)
+        for i in range(n_layers):
+            d.bank_update(i, 1e-7, col0, 0, stream=stream)
+        mark(n_layers + 3)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    n_marks = n_layers + 4
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n_marks)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
+    seg_ms = seg.mean(axis=0)
+    breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
+    ms_per_step = elapsed / args.steps * 1e3
+    value = T * args.steps / elapsed
+
+    # dominant kernel: the fused head GEMM + log-sum-exp (zo_score; its three merge kernels are < 1 % of it)
+    head_flops = 2.0 * T * hid * vocab
+    head_ms = breakdown["score"]
+    achieved = head_flops / (head_ms * 1e-3) / 1e12
+    roofline = {"kernel": "k_head_score (zo_score)", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "avg_ms": head_ms}
+    layer_flops = {l.name: 2.0 * T * l.m * l.n for l in d.layers}
+    calls = {n: {"ms": breakdown[n], "tflops": layer_flops[n] / (breakdown[n] * 1e-3) / 1e12,
+                 "frac_mfma_peak": layer_flops[n] / (breakdown[n] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+             for n in layer_flops}
+    total_flops = head_flops + sum(layer_flops.values())
+
+    result = {
+        "metric": "candidate-tokens scored/sec (probe linear + LM-head scoring)",
+        "value": value, "unit": "candidate-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "rows": T, "sequences": int(len(w.seq_cand)), "candidates": int(len(w.cand_dir)),
+                   "directions": int(len(w.dir_seed)), "r": w.r, "eps": w.eps,
+                   "layers": [[l.name, l.m, l.n] for l in w.layers], "bank_rank": int(w.layers[0].R_used),
+                   "vocab": int(vocab), "hidden": int(hid)},
+        "roofline": roofline,
+        "chain_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "breakdown_ms": breakdown, "probe_linear_calls": calls, "input_setup_s": gen_s,
+    }
+    if not args.no_cpu_baseline:
+        base, _, _ = _cpu_baseline(w)
+        result["cpu_baseline"] = base
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

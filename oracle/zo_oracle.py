@@ -252,3 +252,23 @@ def bank_update(bank: Bank, batch: Batch, m, n, r, tensor_id, proj_grad, lr,
         else:
             P[:, c0:c0 + r] += beta * U
     return Bank(P.astype(np.float32), Vb.astype(np.float32), R_used)
+
+
+def run_chain(batch: Batch, X, layers, head, targets, r, eps, dtype, reduction):
+    """The whole path on one batch, in the order the definition gives it:
+    probe linears in sequence (each output rounded to the declared storage
+    dtype), head scoring, two-point estimate.
+
+    layers: sequence of objects with attributes W, tensor_id, act, P, Vb, R_used
+    (P None = no bank).  Returns a dict of every intermediate.
+    """
+    H = X
+    Ys = []
+    for l in layers:
+        bank = None if l.P is None else Bank(l.P, l.Vb, l.R_used)
+        H = probe_linear(batch, H, l.W, r, eps, l.tensor_id, bank, act=l.act,
+                         factor_dtype=dtype, out_dtype=dtype)
+        Ys.append(H)
+    tok, seq, cs, cc = score(batch, H, head, targets)
+    loss, grad = estimate(batch, cs, cc, eps, reduction)
+    return dict(Y=Ys, tok_nll=tok, seq_nll=seq, cand_sum=cs, cand_cnt=cc, cand_loss=loss, proj_grad=grad)

@@ -74,6 +74,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("%s is missing: build it with `python -m paper_2605_28760_amd.build` "
                                "(there is no fallback path)" % LIB_PATH)
+        # The caller's device memory comes from torch, which ships its own HIP runtime;
+        # load it first so that libzo.so binds to the same runtime instance (two runtimes
+        # in one process do not see each other's device state).
+        import torch  # noqa: F401
         handle = C.CDLL(LIB_PATH)
         for name, (res, args) in _PROTOS.items():
             fn = getattr(handle, name)

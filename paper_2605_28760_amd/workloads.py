@@ -236,5 +236,30 @@ def foreground_only(w: Workload, keep_only_foreground=False):
     return out
 
 
+def subset_sequences(w: Workload, seq_ids):
+    """The workload restricted to the given sequences (kept in the given order);
+    weights, banks, seeds and the candidate table are shared, not copied."""
+    import copy
+    seq_ids = np.asarray(seq_ids, dtype=np.int64)
+    out = copy.copy(w)
+    lens = np.diff(w.cu_seqlens)[seq_ids]
+    rows = np.concatenate([np.arange(w.cu_seqlens[s], w.cu_seqlens[s + 1]) for s in seq_ids]) \
+        if len(seq_ids) else np.zeros(0, np.int64)
+    cu = np.zeros(len(seq_ids) + 1, dtype=np.int32); cu[1:] = np.cumsum(lens)
+    out.cu_seqlens, out.seq_cand = cu, w.seq_cand[seq_ids].copy()
+    if w.X is not None:
+        out.X = w.X[rows]
+    if w.targets is not None:
+        out.targets = w.targets[rows]
+    out.layers = []
+    for l in w.layers:
+        l2 = copy.copy(l)
+        if l.X is not None:
+            l2.X = l.X[rows]
+        out.layers.append(l2)
+    out.meta = dict(w.meta, rows=rows)
+    return out
+
+
 BUILDERS = {"c1": tiny_fp32, "c2": opt_layer_set, "c3": opt_scoring, "c4": ragged_packed,
             "c5": mixed_foreground}

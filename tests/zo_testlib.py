@@ -38,15 +38,7 @@ def oracle_layer(w, i, X, rows=None, out_dtype=None):
 
 def oracle_chain(w):
     """End-to-end oracle: layers in sequence (rounding at each declared dtype), scoring, estimate."""
-    b = oracle_batch(w)
-    H = w.X
-    Ys = []
-    for i in range(len(w.layers)):
-        H = oracle_layer(w, i, H)
-        Ys.append(H)
-    tok, seq, cs, cc = zo.score(b, H, w.head, w.targets)
-    loss, grad = zo.estimate(b, cs, cc, w.eps, w.reduction)
-    return dict(Y=Ys, tok_nll=tok, seq_nll=seq, cand_sum=cs, cand_cnt=cc, cand_loss=loss, proj_grad=grad)
+    return zo.run_chain(oracle_batch(w), w.X, w.layers, w.head, w.targets, w.r, w.eps, w.dtype, w.reduction)
 
 
 def to_np(t):
