@@ -17,7 +17,7 @@
 namespace zo {
 
 constexpr int BM = kTileM, BN = kTileN, BK = kTileK;
-constexpr int kOperandStage = BM * BK * 2;        // 32 KiB: one operand tile
+constexpr int kOperandStage = BM * BK * 2;        // 32 KiB: one operand tile (256 rows x 128 B)
 constexpr int kStage = 2 * kOperandStage;         // A tile then B tile
 constexpr int kGemmLds = 2 * kStage;              // double buffered: 128 KiB
 constexpr int kGroupM = 8;                        // raster: tile rows per group
@@ -43,9 +43,27 @@ __device__ __forceinline__ bool tile_of_block(int bid, int n_tm, int n_tn, int& 
   return true;
 }
 
+__device__ __forceinline__ void block_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 // Main loop: acc[rb][cb] += A[tile rows] * B[tile rows]^T over K (multiple of 64).
 // A and B are row-major with K contiguous; rows beyond M / N are clamped to the
 // last valid row (their results are never stored).
+//
+// Pipeline.  K tiles of 64 (128-byte row segments, so every L2 request is a full
+// line) alternate between two LDS stages.  A tile is four k-steps of 16; MFMA
+// fragments are double buffered in registers and the LDS reads of the next
+// k-step run under the 16 MFMAs of the current one.  The 16 direct-to-LDS loads
+// a wave issues per tile are spread thinly (one per ~3 MFMAs) over k-step 3 of
+// the previous tile and k-steps 0..1 of the current one: a burst would fill the
+// memory pipeline's queues and stall the wave, and with it the MFMA stream.
+// The single barrier of a tile sits before k-step 3: by then every wave has
+// read its last fragments of this tile's stage (so the stage can be refilled)
+// and the next tile has landed (so its first fragments can be fetched under
+// k-step 3).
 __device__ __forceinline__ void gemm_mainloop(const bf16_t* __restrict__ A, int64_t lda, int M, int tile_m0,
                                               const bf16_t* __restrict__ B, int64_t ldb, int N, int tile_n0,
                                               int K, f32x16 (&acc)[4][4], char* lds) {
@@ -54,9 +72,9 @@ __device__ __forceinline__ void gemm_mainloop(const bf16_t* __restrict__ A, int6
   const int lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
 
-  // global -> LDS mapping: load instruction j of this wave fills the 1 KiB block
-  // (wave*8 + j): 8 tile rows x 128 B.  Lane i lands at byte 16*i of the block,
-  // i.e. row i/8, physical chunk i%8, which holds logical chunk (i%8) ^ ((row>>1)&7).
+  // global -> LDS mapping: load j (0..7) of this wave fills the 1 KiB block (wave*8 + j)
+  // of an operand tile: 8 rows x 128 B.  Lane i lands at byte 16*i of the block, i.e. row
+  // i/8, physical chunk i%8, which holds logical chunk (i%8) ^ ((row>>1)&7).
   uint32_t offA[8], offB[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -67,8 +85,15 @@ __device__ __forceinline__ void gemm_mainloop(const bf16_t* __restrict__ A, int6
     offA[j] = (uint32_t)((int64_t)ra * lda * 2 + lch * 16);
     offB[j] = (uint32_t)((int64_t)rbn * ldb * 2 + lch * 16);
   }
-  const char* gA = (const char*)(A + (int64_t)tile_m0 * lda);
-  const char* gB = (const char*)(B + (int64_t)tile_n0 * ldb);
+  // Buffer resources over the rows of this tile: one 32-bit per-lane offset and a scalar
+  // K offset per load, no 64-bit address arithmetic in the loop.  Reads past the end of
+  // the matrix (none are issued: rows are clamped) would return zero instead of faulting.
+  const int64_t bytesA = ((int64_t)(M - tile_m0 - 1) * lda + K) * 2;
+  const int64_t bytesB = ((int64_t)(N - tile_n0 - 1) * ldb + K) * 2;
+  const __amdgpu_buffer_rsrc_t rA = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(A + (int64_t)tile_m0 * lda), 0, (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rB = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(B + (int64_t)tile_n0 * ldb), 0, (int)min(bytesB, (int64_t)0x7FFFFFFF), 0x00020000);
 
   // LDS -> register mapping (32x32x16 fragments: lane l holds row l%32, k-group l/32)
   const int lrow = lane & 31;
@@ -78,39 +103,99 @@ __device__ __forceinline__ void gemm_mainloop(const bf16_t* __restrict__ A, int6
   for (int kk = 0; kk < 4; ++kk) roff[kk] = lrow * 128 + (((kk * 2 + (lane >> 5)) ^ swz) << 4);
   const uint32_t aBase = wm * 128 * 128, bBase = kOperandStage + wn * 128 * 128;
 
-  auto issue = [&](int stage, int k0) {
-    char* sA = lds + stage * kStage + wave * 8 * 1024;
-    char* sB = sA + kOperandStage;
-    const char* a = gA + (int64_t)k0 * 2;
-    const char* b = gB + (int64_t)k0 * 2;
+  // load i (0..15) of tile kt: i < 8 -> A chunk i, else B chunk i - 8
+  auto issue_range = [&](int stage, int kt, int first, int count) {
+    char* sbase = lds + stage * kStage + wave * 8 * 1024;
+    const int koff = kt * (BK * 2);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      __builtin_amdgcn_global_load_lds((global_void*)(a + offA[j]), (lds_void*)(sA + j * 1024), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((global_void*)(b + offB[j]), (lds_void*)(sB + j * 1024), 16, 0, 0);
+    for (int i = first; i < first + count; ++i) {
+      if (i < 8)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rA, (lds_void*)(sbase + i * 1024), 16, (int)offA[i], koff, 0, 0);
+      else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rB, (lds_void*)(sbase + kOperandStage + (i - 8) * 1024), 16,
+                                                 (int)offB[i - 8], koff, 0, 0);
     }
   };
 
+  bf16x8 fa[2][4], fb[2][4];
+  auto load_frags = [&](int set, int stage, int kk) {
+    const char* s = lds + stage * kStage;
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 4096 + roff[kk]);
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) fb[set][cb] = *(const bf16x8*)(s + bBase + cb * 4096 + roff[kk]);
+  };
+  auto mfmas = [&](int set) {
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb)
+        acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
+  };
   const int nk = K / BK;
-  issue(0, 0);
+  issue_range(0, 0, 0, 16);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  block_barrier();
+  load_frags(0, 0, 0);
+  // loads 0..5 of tile 1 belong to "k-step 3 of the previous tile"; there is none, issue them here
+  issue_range(1, min(1, nk - 1), 0, 6);
+
   for (int kt = 0; kt < nk; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < nk) issue((kt + 1) & 1, (kt + 1) * BK);
-    const char* s = lds + (kt & 1) * kStage;
+    const int stage = kt & 1;
+    const int next_tile = min(kt + 1, nk - 1);   // clamped past the end: refills a stage nobody reads again
+    // k-step 0
+    __builtin_amdgcn_sched_barrier(0);
+    issue_range(stage ^ 1, next_tile, 6, 5);
+    load_frags(1, stage, 1);
+    mfmas(0);
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 fa[4], fb[4];
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb) fa[rb] = *(const bf16x8*)(s + aBase + rb * 4096 + roff[kk]);
-#pragma unroll
-      for (int cb = 0; cb < 4; ++cb) fb[cb] = *(const bf16x8*)(s + bBase + cb * 4096 + roff[kk]);
-#pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[rb], fb[cb], acc[rb][cb], 0, 0, 0);
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i % 2 == 1 || i == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
     }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // k-step 1
+    issue_range(stage ^ 1, next_tile, 11, 5);
+    load_frags(0, stage, 2);
+    mfmas(1);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i % 2 == 1 || i == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // k-step 2
+    load_frags(1, stage, 3);
+    mfmas(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    // the next tile has landed; every wave is done reading this tile's stage
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // k-step 3: first fragments of the next tile, first loads of the tile after it
+    issue_range(stage, min(kt + 2, nk - 1), 0, 6);
+    load_frags(0, stage ^ 1, 0);
+    mfmas(1);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      if (i % 2 == 1 || i == 0 || i == 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the clamped tail loads before LDS is reused
 }
 
 // ---------------------------------------------------------------------------------------
