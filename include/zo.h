@@ -153,7 +153,7 @@ int32_t zo_batch_index(const zo_batch* batch, int32_t* tok_seq, int32_t* tok_can
  *   bias      fp32 [m] or NULL;  act 0 = none, 1 = ReLU
  *   r         rank of the probe, 1..64;  eps probe scale;  tensor_id even id of the layer
  *   bank      NULL or R_used = 0: no bank
- * ZO_BF16 requires n % 64 == 0, 16-byte aligned X, W, Y and leading dimensions
+ * ZO_BF16 requires n % 64 == 0 (and m % 8 == 0 for bf16 output), 16-byte aligned X, W, Y and leading dimensions
  * that keep rows 16-byte aligned.
  */
 size_t zo_probe_linear_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t n_dirs,

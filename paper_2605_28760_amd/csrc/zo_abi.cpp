@@ -235,6 +235,8 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   if (int32_t st = check_matrix("Y", Y, ldy, m, out_dtype)) return st;
   if (in_dtype == ZO_BF16 && (n % zo::kTileK != 0 || n == 0))
     return fail(ZO_ERR_UNSUPPORTED, "bf16 path needs n %% %d == 0 (n = %d)", zo::kTileK, n);
+  if (out_dtype == ZO_BF16 && m % 8 != 0)
+    return fail(ZO_ERR_UNSUPPORTED, "bf16 output needs m %% 8 == 0 (m = %d)", m);
   const ProbePlan plan = plan_probe(T, batch->n_seqs, batch->n_dirs, m, n, r, R, in_dtype);
   if (!workspace) return fail(ZO_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total);
   if (((uintptr_t)workspace & 255u) != 0) return fail(ZO_ERR_WORKSPACE, "workspace not 256-byte aligned");
