@@ -96,10 +96,10 @@ struct ProbePlan {
 };
 
 int side_ksplit(int T, int n) {
-  // enough (item, split) waves to cover the chip twice, k-chunks of >= 512 that divide n
-  const int items = (T + zo::kSideRows - 1) / zo::kSideRows;
+  // about three workgroups (of four 64-row items each) per CU; k-chunks are multiples of 64 and >= 512
+  const int groups = ((T + zo::kSideRows - 1) / zo::kSideRows + 3) / 4;
   int ks = 1;
-  while (items * ks < 2048 && ks < 16 && n % (ks * 2 * 32) == 0 && n / (ks * 2) >= 512) ks *= 2;
+  while (groups * ks < 768 && ks < 16 && n % (ks * 2 * 64) == 0 && n / (ks * 2) >= 512) ks *= 2;
   return ks;
 }
 

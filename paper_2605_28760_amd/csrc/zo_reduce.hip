@@ -9,16 +9,37 @@
 
 namespace zo {
 
-__global__ void k_tok_nll(ScoreCombineArgs a) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= a.T) return;
-  if (a.targets[t] < 0) { a.tok_nll[t] = 0.0f; return; }
-  float M = -INFINITY;
-  for (int j = 0; j < a.n_vt; ++j) M = fmaxf(M, a.part_max[(int64_t)j * a.T + t]);
-  float S = 0.0f;
-  for (int j = 0; j < a.n_vt; ++j)
-    S += a.part_sum[(int64_t)j * a.T + t] * expf(a.part_max[(int64_t)j * a.T + t] - M);
-  a.tok_nll[t] = (M + logf(S)) - a.tgt_logit[t];
+// 32 tokens per workgroup, 8 threads per token: thread j of a token folds vocabulary
+// tiles j, j+8, ... (coalesced over tokens), then the 8 partial (max, sum) pairs are
+// merged in a fixed order.
+__global__ __launch_bounds__(256) void k_tok_nll(ScoreCombineArgs a) {
+  __shared__ float s_m[8][33], s_s[8][33];
+  const int tl = threadIdx.x & 31, j0 = threadIdx.x >> 5;
+  const int t = blockIdx.x * 32 + tl;
+  float M = -INFINITY, S = 0.0f;
+  if (t < a.T) {
+    for (int j = j0; j < a.n_vt; j += 8) {
+      const float m = a.part_max[(int64_t)j * a.T + t];
+      const float s = a.part_sum[(int64_t)j * a.T + t];
+      const float Mn = fmaxf(M, m);
+      if (Mn > -INFINITY) S = S * expf(M - Mn) + s * expf(m - Mn);
+      M = Mn;
+    }
+  }
+  s_m[j0][tl] = M;
+  s_s[j0][tl] = S;
+  __syncthreads();
+  if (j0 == 0 && t < a.T) {
+    if (a.targets[t] < 0) { a.tok_nll[t] = 0.0f; return; }
+    float Mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) Mx = fmaxf(Mx, s_m[j][tl]);
+    float Sx = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (s_m[j][tl] > -INFINITY) Sx += s_s[j][tl] * expf(s_m[j][tl] - Mx);
+    a.tok_nll[t] = (Mx + logf(Sx)) - a.tgt_logit[t];
+  }
 }
 
 // One workgroup per sequence: thread i takes rows i, i+256, ... of the sequence,
@@ -44,22 +65,34 @@ __global__ __launch_bounds__(256) void k_seq_nll(ScoreCombineArgs a) {
   if (tid == 0) { a.seq_nll[s] = s_sum[0]; a.seq_cnt[s] = s_cnt[0]; }
 }
 
-// Candidate c sums its sequences in sequence order.
-__global__ void k_cand_sum(ScoreCombineArgs a) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= a.C) return;
+// One wave per candidate.  The candidate's sequences are folded strictly in sequence
+// order (64 candidates-id loads at a time, then the matching ones one by one), so the sum
+// depends only on the ordered list of that candidate's own sequences, not on what else
+// is in the batch.
+__global__ __launch_bounds__(64) void k_cand_sum(ScoreCombineArgs a) {
+  const int c = blockIdx.x, lane = threadIdx.x;
   float sum = 0.0f;
   int cnt = 0;
-  for (int s = 0; s < a.S; ++s)
-    if (a.seq_cand[s] == c) { sum += a.seq_nll[s]; cnt += a.seq_cnt[s]; }
-  a.cand_sum[c] = sum;
-  a.cand_cnt[c] = cnt;
+  for (int base = 0; base < a.S; base += 64) {
+    const int s = base + lane;
+    const bool match = s < a.S && a.seq_cand[s] == c;
+    const float v = match ? a.seq_nll[s] : 0.0f;
+    const int n = match ? a.seq_cnt[s] : 0;
+    uint64_t mask = __ballot(match);
+    while (mask) {
+      const int b = __ffsll((unsigned long long)mask) - 1;
+      sum += __shfl(v, b);
+      cnt += __shfl(n, b);
+      mask &= mask - 1;
+    }
+  }
+  if (lane == 0) { a.cand_sum[c] = sum; a.cand_cnt[c] = cnt; }
 }
 
 hipError_t launch_score_combine(const ScoreCombineArgs& a, hipStream_t st) {
-  if (a.T > 0) hipLaunchKernelGGL(k_tok_nll, dim3((a.T + 255) / 256), dim3(256), 0, st, a);
+  if (a.T > 0) hipLaunchKernelGGL(k_tok_nll, dim3((a.T + 31) / 32), dim3(256), 0, st, a);
   if (a.S > 0) hipLaunchKernelGGL(k_seq_nll, dim3(a.S), dim3(256), 0, st, a);
-  if (a.C > 0) hipLaunchKernelGGL(k_cand_sum, dim3((a.C + 63) / 64), dim3(64), 0, st, a);
+  if (a.C > 0) hipLaunchKernelGGL(k_cand_sum, dim3(a.C), dim3(64), 0, st, a);
   return hipGetLastError();
 }
 

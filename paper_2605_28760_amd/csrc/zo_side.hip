@@ -2,79 +2,129 @@
 // Sec. 3.2.  For every candidate row t it forms
 //     Aside[t, :] = [ s_t eps (X[t,:] V_{k_t})  |  X[t,:] Vb ]        (bf16)
 // which the probe GEMM then multiplies by [U_{k_t} | P]^T.  The kernel streams
-// X once (it is bound by HBM bandwidth); work items are chunks of one
-// sequence, so all rows of an item share one direction.
+// X once and is bound by HBM bandwidth; the skinny contraction runs on
+// v_mfma_f32_16x16x32_bf16 so that the arithmetic (about 2 (r + R) flop per
+// byte of X) stays out of the way.
+//
+// Work items are chunks of at most 64 rows of one sequence, so all rows of an
+// item share one direction.  One wave per (item, k-split); the four waves of a
+// workgroup walk the same K range, so the bank operand Vb is staged once per
+// workgroup in LDS (direct-to-LDS loads, double buffered) while each wave keeps
+// its own rows of X and its own direction's V in registers.  Three workgroups per
+// CU hide the memory latency of one another.
+#include <type_traits>
+
 #include "zo_device.hpp"
 #include "zo_internal.hpp"
 
 namespace zo {
 
-// One wave per (item, k-split).  16x16x32 bf16 MFMA: A fragment = 16 rows x 32 k
-// (lane l: row l%16, k = 8*(l/16)..+7), B fragment = 32 k x 16 cols (lane l: col
-// l%16, same k), D: lane l holds rows 4*(l/16)+v, col l%16.
-template <int NB>
-__global__ __launch_bounds__(256) void k_side_down(SideDownArgs a, int cb0) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int item = blockIdx.x * 4 + wave;
+typedef __attribute__((address_space(3))) void lds_void;
+
+// 16x16x32 bf16 MFMA: A fragment = 16 rows x 32 k (lane l: row l%16, k = 8*(l/16)..+7),
+// B fragment = 32 k x 16 cols (lane l: col l%16, same k), D: lane l holds rows 4*(l/16)+v, col l%16.
+//
+// NBB = number of 16-column bank blocks this pass accumulates; kDir = whether the pass
+// also carries the (single) 16-column direction block.  cb0 = first bank block of the pass.
+template <int NBB, bool kDir>
+__global__ __launch_bounds__(256, (NBB <= 4 ? 3 : 2)) void k_side_down(SideDownArgs a, int cb0) {
+  // Vb stage: [half h of the K step][16-col block][col][4 chunks of 16 B], chunk index XOR (col>>2)&3
+  __shared__ __attribute__((aligned(1024))) char s_vb[2][NBB > 0 ? NBB * 2048 : 16];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int n_items = *a.n_items;
-  if (item >= n_items) return;
-  const SideItem it = a.items[item];
-  const int split = blockIdx.y;
+  if ((int)blockIdx.y * 4 >= n_items) return;   // the grid is sized for the worst case; whole workgroups without items leave
+  const int item_raw = blockIdx.y * 4 + wave;
+  const bool live = item_raw < n_items;
+  // waves without an item still take part in the workgroup's Vb loads and barriers
+  const SideItem it = a.items[live ? item_raw : (n_items > 0 ? n_items - 1 : 0)];
+  const int split = blockIdx.x;
   const int NC = a.RP + a.Rp;
   const int lr = lane & 15, lg = lane >> 4;
-  const int ndir_blocks = a.RP >> 4;
-
-  if (it.kind == kKindForeground) {
-    if (a.ksplit == 1) {
-      for (int idx = lane; idx < it.nrows * NB * 16; idx += 64) {
-        const int row = idx / (NB * 16), c = idx % (NB * 16);
-        a.Aside[(int64_t)(it.row0 + row) * NC + cb0 * 16 + c] = 0;
-      }
-    }
-    return;
-  }
-
+  // each split walks its own contiguous K range in steps of 64
   const int kchunk = a.n / a.ksplit;
   const int k_begin = split * kchunk;
+  constexpr int kstride = 64;
+  const int nsteps = kchunk / kstride;
+  const bool has_dir = kDir && it.kind >= 0;
+  const bool work = live && it.kind != kKindForeground;   // wave-uniform
 
+  // per-lane addresses: 16 B at (row, k + h*32 + lg*8)
   const bf16_t* pa[4];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
     const int row = it.row0 + min(rb * 16 + lr, it.nrows - 1);
     pa[rb] = a.X + (int64_t)row * a.ldx + k_begin + lg * 8;
   }
-  const bf16_t* pb[NB];
-#pragma unroll
-  for (int cb = 0; cb < NB; ++cb) {
-    const int gcb = cb0 + cb;
-    if (gcb < ndir_blocks) {
-      // a centre item has no direction: read a valid address (its own X rows) and discard the result
-      pb[cb] = it.kind >= 0 ? a.Vt + ((int64_t)it.kind * a.RP + gcb * 16 + lr) * a.n + k_begin + lg * 8 : pa[0];
-    } else {
-      pb[cb] = a.Vbt + ((int64_t)(gcb - ndir_blocks) * 16 + lr) * a.n + k_begin + lg * 8;
-    }
-  }
+  // a centre / foreground item has no direction: read a valid address (its own X rows), discard the result
+  const bf16_t* pv = has_dir ? a.Vt + ((int64_t)it.kind * a.RP + lr) * a.n + k_begin + lg * 8 : pa[0];
+  // Vb -> LDS: load j (0 .. 2*NBB-1) = (half h = j & 1, block b = j >> 1); lane i fills byte 16*i of
+  // the 1 KiB block: col i/4, physical chunk i%4 = logical chunk ^ ((col>>2)&3)
+  const int vcol = lane >> 2;
+  const int vchunk = (lane & 3) ^ ((vcol >> 2) & 3);
+  const bf16_t* pvb = NBB > 0 ? a.Vbt + ((int64_t)cb0 * 16 + vcol) * a.n + k_begin + vchunk * 8 : nullptr;
+  const uint32_t rd_off = lr * 64 + ((lg ^ ((lr >> 2) & 3)) << 4);
 
-  f32x4 acc[4][NB];
+  auto issue_vb = [&](int stage, int step) {
+#pragma unroll
+    for (int j = 0; j < 2 * NBB; ++j) {
+      if ((j & 3) != wave) continue;
+      const int h = j & 1, b = j >> 1;
+      __builtin_amdgcn_global_load_lds(
+          (const __attribute__((address_space(1))) void*)(pvb + (int64_t)b * 16 * a.n + step * kstride + h * 32),
+          (lds_void*)(&s_vb[stage][0] + (h * NBB + b) * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x4 acc[4][NBB + 1];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
-    for (int cb = 0; cb < NB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int cb = 0; cb < NBB + 1; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-
-  for (int k = 0; k < kchunk; k += 32) {
-    bf16x8 fa[4], fb[NB];
+  // One K step: issue this step's loads (X rows and V into registers, Vb into LDS stage step&1),
+  // wait for them, compute.  Latency is hidden by the other waves resident on the CU (three
+  // per SIMD), not by a register double buffer: the step's registers are free for them.
+  // Refilling stage (step+1)&1 is safe once a wave is past barrier `step`: every wave has then
+  // finished the MFMAs of step-1, the last reader of that stage.
+  for (int step = 0; step < nsteps; ++step) {
+    bf16x8 fa[2][4], fv[2];   // [half][row block], [half]
+    if (work) {   // foreground rows are not read at all: they only get zeros written
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) fa[rb] = load_frag(pa[rb] + k);
+      for (int h = 0; h < 2; ++h) {
 #pragma unroll
-    for (int cb = 0; cb < NB; ++cb) fb[cb] = load_frag(pb[cb] + k);
+        for (int rb = 0; rb < 4; ++rb) fa[h][rb] = load_frag(pa[rb] + step * kstride + h * 32);
+        if (kDir) fv[h] = load_frag(pv + step * kstride + h * 32);
+      }
+    } else {
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+      for (int h = 0; h < 2; ++h) {
 #pragma unroll
-      for (int cb = 0; cb < NB; ++cb)
-        acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rb], fb[cb], acc[rb][cb], 0, 0, 0);
+        for (int rb = 0; rb < 4; ++rb) fa[h][rb] = zero_frag();
+        fv[h] = zero_frag();
+      }
+    }
+    issue_vb(step & 1, step);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const char* stage = &s_vb[step & 1][0];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      bf16x8 fb[NBB > 0 ? NBB : 1];
+#pragma unroll
+      for (int b = 0; b < NBB; ++b) fb[b] = *(const bf16x8*)(stage + (h * NBB + b) * 1024 + rd_off);
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) {
+        if (kDir) acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[h][rb], fv[h], acc[rb][0], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < NBB; ++b)
+          acc[rb][b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[h][rb], fb[b], acc[rb][b + 1], 0, 0, 0);
+      }
+    }
   }
+  if (!live) return;
 
+  const bool fg = it.kind == kKindForeground;
+  const int ndir_cols = a.RP;
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
 #pragma unroll
@@ -83,13 +133,14 @@ __global__ __launch_bounds__(256) void k_side_down(SideDownArgs a, int cb0) {
       if (lrow >= it.nrows) continue;
       const int64_t row = it.row0 + lrow;
 #pragma unroll
-      for (int cb = 0; cb < NB; ++cb) {
-        const int gcb = cb0 + cb;
-        const int col = gcb * 16 + lr;
+      for (int cb = 0; cb < NBB + 1; ++cb) {
+        if (cb == 0 && !kDir) continue;
+        const int col = cb == 0 ? lr : ndir_cols + (cb0 + cb - 1) * 16 + lr;
         const float x = acc[rb][cb][v];
         if (a.ksplit == 1) {
           float y = x;
-          if (gcb < ndir_blocks) y = (it.kind >= 0) ? it.scale * x : 0.0f;
+          if (cb == 0) y = has_dir ? it.scale * x : 0.0f;
+          if (fg) y = 0.0f;
           a.Aside[row * NC + col] = f32_to_bf16(y);
         } else {
           a.partial[((int64_t)split * a.T + row) * NC + col] = x;
@@ -97,6 +148,48 @@ __global__ __launch_bounds__(256) void k_side_down(SideDownArgs a, int cb0) {
       }
     }
   }
+  // direction columns 16 .. RP-1 exist only for ranks above 16 and are handled by extra passes below
+}
+
+// Direction blocks beyond the first (ranks 17..64): same kernel shape with no bank blocks.
+// cbd = index of the 16-column direction block.
+__global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int cbd) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int item = blockIdx.x * 4 + wave;
+  if (item >= *a.n_items) return;
+  const SideItem it = a.items[item];
+  const int split = blockIdx.y;
+  const int NC = a.RP + a.Rp;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int kchunk = a.n / a.ksplit, k_begin = split * kchunk;
+  const bool has_dir = it.kind >= 0;
+  f32x4 acc[4];
+#pragma unroll
+  for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (has_dir) {
+    const bf16_t* pv = a.Vt + ((int64_t)it.kind * a.RP + cbd * 16 + lr) * a.n + k_begin + lg * 8;
+    const bf16_t* pa[4];
+#pragma unroll
+    for (int rb = 0; rb < 4; ++rb)
+      pa[rb] = a.X + (int64_t)(it.row0 + min(rb * 16 + lr, it.nrows - 1)) * a.ldx + k_begin + lg * 8;
+    for (int k = 0; k < kchunk; k += 32) {
+      const bf16x8 fb = load_frag(pv + k);
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb)
+        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(load_frag(pa[rb] + k), fb, acc[rb], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int lrow = rb * 16 + lg * 4 + v;
+      if (lrow >= it.nrows) continue;
+      const int64_t row = it.row0 + lrow;
+      const int col = cbd * 16 + lr;
+      if (a.ksplit == 1) a.Aside[row * NC + col] = f32_to_bf16(has_dir ? it.scale * acc[rb][v] : 0.0f);
+      else a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][v];
+    }
 }
 
 // Fixed-order sum of the k-split partials, scaling and rounding to bf16.
@@ -116,31 +209,44 @@ __global__ void k_side_reduce(SideDownArgs a) {
   a.Aside[idx] = f32_to_bf16(y);
 }
 
-template <int NB>
+template <int NBB, bool kDir>
 static void launch_pass(const SideDownArgs& a, int cb0, hipStream_t st) {
-  dim3 grid((a.max_items + 3) / 4, a.ksplit);
-  hipLaunchKernelGGL(k_side_down<NB>, grid, dim3(256), 0, st, a, cb0);
+  dim3 grid(a.ksplit, (a.max_items + 3) / 4);
+  hipLaunchKernelGGL((k_side_down<NBB, kDir>), grid, dim3(256), 0, st, a, cb0);
+}
+
+template <bool kDir>
+static void launch_pass_n(int nbb, const SideDownArgs& a, int cb0, hipStream_t st) {
+  switch (nbb) {
+    case 0: launch_pass<0, kDir>(a, cb0, st); break;
+    case 1: launch_pass<1, kDir>(a, cb0, st); break;
+    case 2: launch_pass<2, kDir>(a, cb0, st); break;
+    case 3: launch_pass<3, kDir>(a, cb0, st); break;
+    case 4: launch_pass<4, kDir>(a, cb0, st); break;
+    case 5: launch_pass<5, kDir>(a, cb0, st); break;
+    case 6: launch_pass<6, kDir>(a, cb0, st); break;
+    case 7: launch_pass<7, kDir>(a, cb0, st); break;
+    default: launch_pass<8, kDir>(a, cb0, st); break;
+  }
 }
 
 hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
   if (a.T == 0 || a.max_items == 0) return hipSuccess;
-  const int nblocks = (a.RP + a.Rp) / 16;
-  for (int cb0 = 0; cb0 < nblocks; cb0 += kSideMaxBlocks) {
-    const int nb = nblocks - cb0 < kSideMaxBlocks ? nblocks - cb0 : kSideMaxBlocks;
-    switch (nb) {
-      case 1: launch_pass<1>(a, cb0, st); break;
-      case 2: launch_pass<2>(a, cb0, st); break;
-      case 3: launch_pass<3>(a, cb0, st); break;
-      case 4: launch_pass<4>(a, cb0, st); break;
-      case 5: launch_pass<5>(a, cb0, st); break;
-      case 6: launch_pass<6>(a, cb0, st); break;
-      case 7: launch_pass<7>(a, cb0, st); break;
-      case 8: launch_pass<8>(a, cb0, st); break;
-      default: launch_pass<9>(a, cb0, st); break;
-    }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+  const int bank_blocks = a.Rp / 16;
+  // first pass: direction block 0 together with up to 8 bank blocks
+  int done = bank_blocks < kSideMaxBlocks - 1 ? bank_blocks : kSideMaxBlocks - 1;
+  launch_pass_n<true>(done, a, 0, st);
+  while (done < bank_blocks) {   // bank ranks above 128: further passes over X
+    const int nb = bank_blocks - done < kSideMaxBlocks - 1 ? bank_blocks - done : kSideMaxBlocks - 1;
+    launch_pass_n<false>(nb, a, done, st);
+    done += nb;
   }
+  for (int cbd = 1; cbd < a.RP / 16; ++cbd) {   // ranks above 16
+    dim3 grid((a.max_items + 3) / 4, a.ksplit);
+    hipLaunchKernelGGL(k_side_down_dirblock, grid, dim3(256), 0, st, a, cbd);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   if (a.ksplit > 1) {
     const int64_t total = (int64_t)a.T * (a.RP + a.Rp);
     hipLaunchKernelGGL(k_side_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);

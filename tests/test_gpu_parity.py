@@ -150,6 +150,8 @@ def test_bf16_side_term_isolated_fp32_out():
     (wl.ragged_packed, dict(hidden=256, ffn=384, vocab=1187, n_ex=8, n_dirs=4, len_lo=1, len_hi=140, r=16, R=32)),
     (wl.mixed_foreground, dict(hidden=192, ffn=448, vocab=777, n_ex=6, n_fg=5, len_lo=3, len_hi=160, r=16, R=48)),
     (wl.ragged_packed, dict(hidden=128, ffn=256, vocab=300, n_ex=6, n_dirs=3, len_lo=1, len_hi=50, r=2, R=0)),
+    (wl.ragged_packed, dict(hidden=128, ffn=256, vocab=300, n_ex=4, n_dirs=2, len_lo=1, len_hi=90, r=40, R=160)),
+    (wl.mixed_foreground, dict(hidden=64, ffn=192, vocab=515, n_ex=3, n_fg=2, len_lo=60, len_hi=300, r=64, R=16)),
 ])
 def test_bf16_chain_parity(builder, kw):
     w = builder(**kw)
