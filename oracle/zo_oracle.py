@@ -137,7 +137,7 @@ def probe_linear(batch: Batch, X, W, r, eps, tensor_id, bank: Optional[Bank] = N
     rows: optional index array restricting the computation to those token
     rows (the returned array then has len(rows) rows, in that order).
     """
-    X = np.asarray(X, dtype=np.float64)
+    X = np.asarray(X)
     m = np.asarray(W).shape[0]
     _, tok_cand = batch_indices(batch)
     sel = np.arange(X.shape[0]) if rows is None else np.asarray(rows, dtype=np.int64)
@@ -146,7 +146,7 @@ def probe_linear(batch: Batch, X, W, r, eps, tensor_id, bank: Optional[Bank] = N
     for cand in np.unique(cands_here):
         Wc = candidate_weight(W, batch, int(cand), r, eps, tensor_id, bank, factor_dtype)
         pick = np.nonzero(cands_here == cand)[0]
-        Y[pick] = X[sel[pick]] @ Wc.T
+        Y[pick] = np.asarray(X[sel[pick]], dtype=np.float64) @ Wc.T
     if bias is not None:
         Y += np.asarray(bias, dtype=np.float64)[None, :]
     if act == 1:

@@ -1,0 +1,132 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times.  The oracle cannot evaluate these sizes whole in
+reasonable time, so it evaluates sampled token rows one candidate at a time
+(each sampled candidate's dense weight is still materialised in fp64), and the
+reductions are checked through properties that hold at any size."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import zo_oracle as zo
+from paper_2605_28760_amd import workloads as wl
+from paper_2605_28760_amd.runner import DeviceWorkload
+from zo_testlib import assert_close, oracle_batch, oracle_layer, to_np
+
+DEV = "cuda:0"
+
+
+def _sample_rows(w, n_cands=3, per_cand=6, seed=0):
+    """Token rows of a few candidates (and of foreground sequences when present): first and
+    last row of some of their sequences plus random interior rows, and rows next to the
+    256-row tile boundaries."""
+    rng = np.random.default_rng(seed)
+    tok_seq, tok_cand = zo.batch_indices(oracle_batch(w))
+    cands = list(np.unique(tok_cand[tok_cand >= 0]))
+    pick = [cands[0], cands[-1]] + list(rng.choice(cands, size=min(n_cands, len(cands)), replace=False))
+    pick = sorted(set(int(c) for c in pick))[:n_cands + 1]
+    if (tok_cand < 0).any():
+        pick.append(-1)
+    rows = []
+    for c in pick:
+        idx = np.nonzero(tok_cand == c)[0]
+        near_tiles = idx[(idx % 256 == 0) | (idx % 256 == 255)]
+        chosen = np.concatenate([idx[:1], idx[-1:], rng.choice(idx, size=min(per_cand, len(idx)), replace=False),
+                                 near_tiles[:2]])
+        rows.extend(chosen.tolist())
+    return np.array(sorted(set(rows)), dtype=np.int64)
+
+
+def _check_layers(w, d, rows):
+    H_rows = None
+    for i, l in enumerate(w.layers):
+        if l.X is not None:
+            x_rows_full = l.X
+        else:
+            x_rows_full = w.X if i == 0 else None
+        if x_rows_full is None:      # input of this layer = the GPU's previous output
+            x_in = np.zeros((w.T, l.n), dtype=np.float32)
+            x_in[rows] = to_np(d.Y[i - 1][torch.from_numpy(rows).to(DEV)])
+        else:
+            x_in = x_rows_full
+        want = oracle_layer(w, i, x_in, rows=rows)
+        got = to_np(d.Y[i][torch.from_numpy(rows).to(DEV)])
+        assert_close(got, want, 2e-2, "Y[%s] sampled rows" % l.name)
+    return rows
+
+
+def _check_scoring(w, d, rows):
+    rows_t = torch.from_numpy(rows).to(DEV)
+    H = to_np(d.Y[-1][rows_t])
+    want = zo.token_nll(H, w.head, w.targets[rows])
+    assert_close(to_np(d.tok_nll[rows_t]), want, 1e-4, "tok_nll sampled rows", atol=1e-3)
+    # reductions: properties that hold at any size, on the GPU's own token values
+    tok = to_np(d.tok_nll).astype(np.float64)
+    assert np.isfinite(tok).all() and (tok >= 0).all()
+    cu = w.cu_seqlens
+    seq_want = np.array([tok[cu[s]:cu[s + 1]].sum() for s in range(len(w.seq_cand))])
+    assert_close(to_np(d.seq_nll), seq_want, 1e-5, "seq_nll = sum of its tok_nll", atol=1e-3)
+    seq = to_np(d.seq_nll).astype(np.float64)
+    C = len(w.cand_dir)
+    cand_want = np.array([seq[w.seq_cand == c].sum() for c in range(C)])
+    cnt_want = np.array([np.diff(cu)[w.seq_cand == c].sum() for c in range(C)])
+    assert_close(to_np(d.cand_sum), cand_want, 1e-5, "cand_sum = sum of its seq_nll", atol=1e-2)
+    assert np.array_equal(to_np(d.cand_cnt), cnt_want)
+    loss, grad = zo.estimate(oracle_batch(w), to_np(d.cand_sum), to_np(d.cand_cnt), w.eps, w.reduction)
+    assert_close(to_np(d.cand_loss), loss, 1e-5, "cand_loss", atol=1e-3 if w.reduction == 0 else 1.0)
+    assert_close(to_np(d.proj_grad), grad, 5e-2, "proj_grad from the GPU's candidate sums")
+
+
+def test_config2_layer_set_full_size():
+    w = wl.opt_layer_set()
+    d = DeviceWorkload(w, DEV)
+    for i in range(len(w.layers)):
+        d.probe_linear(i)
+    torch.cuda.synchronize()
+    _check_layers(w, d, _sample_rows(w, n_cands=2, per_cand=8))
+
+
+def test_config3_scoring_full_size():
+    w = wl.opt_scoring()
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False)
+    torch.cuda.synchronize()
+    rows = _check_layers(w, d, _sample_rows(w, n_cands=2, per_cand=8))
+    _check_scoring(w, d, rows)
+    first = [y.clone() for y in d.Y] + [d.tok_nll.clone(), d.cand_sum.clone()]
+    d.step(update=False)
+    torch.cuda.synchronize()
+    for a, b in zip(first, d.Y + [d.tok_nll, d.cand_sum]):
+        assert torch.equal(a, b)            # no atomics: two runs are bitwise equal
+
+
+def test_config4_ragged_full_size():
+    w = wl.ragged_packed()
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False)
+    torch.cuda.synchronize()
+    rows = _check_layers(w, d, _sample_rows(w, n_cands=3, per_cand=5))
+    _check_scoring(w, d, rows)
+
+
+def test_config5_mixed_full_size_with_foreground_identity():
+    w = wl.mixed_foreground()
+    d = DeviceWorkload(w, DEV)
+    w_sum = [l.W.view(torch.int16).to(torch.int64).sum().item() for l in d.layers]
+    d.step(update=False)
+    torch.cuda.synchronize()
+    rows = _check_layers(w, d, _sample_rows(w, n_cands=3, per_cand=5))
+    _check_scoring(w, d, rows)
+    assert [l.W.view(torch.int16).to(torch.int64).sum().item() for l in d.layers] == w_sum   # base immutable
+    tok_cand = zo.batch_indices(oracle_batch(w))[1]
+    fg_rows = torch.from_numpy(np.nonzero(tok_cand < 0)[0]).to(DEV)
+    mixed = [y[fg_rows].clone() for y in d.Y] + [d.tok_nll[fg_rows].clone()]
+    del d
+    torch.cuda.empty_cache()
+    allfg = DeviceWorkload(wl.foreground_only(w), DEV)
+    allfg.step(update=False)
+    torch.cuda.synchronize()
+    for a, y in zip(mixed[:-1], allfg.Y):
+        assert torch.equal(a, y[fg_rows])                 # foreground rows: bit-identical to the plain base GEMM
+    assert torch.equal(mixed[-1], allfg.tok_nll[fg_rows])
