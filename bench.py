@@ -24,9 +24,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured for a workload.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes per launch of the dominant kernel that crossed the L2 <-> fabric boundary, from the rocprofv3
+# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/hbm_bytes_bench_c3.txt (FETCH_SIZE scaled by
+# the factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  None where not measured.
+MEASURED_TRAFFIC_BYTES = {"c3": 1.977e10}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):
@@ -40,14 +41,14 @@ def _cpu_baseline(w, budget_hint_s=20.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
     except Exception:
         cores = os.cpu_count() or 1
-    n_seq = 2
+    n_seq = 16
     sub = wl.subset_sequences(w, list(range(n_seq)))
     t0 = time.perf_counter()
     out = zo.run_chain(zo.Batch(sub.cu_seqlens, sub.seq_cand, sub.cand_dir, sub.cand_sign, sub.dir_seed),
                        sub.X, sub.layers, sub.head, sub.targets, sub.r, sub.eps, sub.dtype, sub.reduction)
     dt = time.perf_counter() - t0
     return {"value": sub.T / dt, "unit": "candidate-tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "first %d sequences (%d of %d rows) of the same workload, whole chain in fp64 NumPy, %.1f s"
+            "sample": "first %d sequences (%d of %d rows) of the same workload, whole chain (dense W_c per candidate, full logits) in fp64 NumPy, %.1f s"
                       % (n_seq, sub.T, w.T, dt)}, out, sub
 
 
@@ -58,6 +59,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (the path shards by sequences; see DESIGN.md); "
@@ -99,6 +102,12 @@ def main():
             d.bank_update(i, 1e-7, col0, 0, stream=stream)
         mark(n_layers + 3)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
