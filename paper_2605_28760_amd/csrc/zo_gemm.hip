@@ -19,6 +19,8 @@
 // Determinism / batch invariance: the tile shape and the K order never depend
 // on the batch, there is no split-K and no atomic, so a token's result depends
 // only on that token's operands.
+#include <type_traits>
+
 #include "zo_device.hpp"
 #include "zo_internal.hpp"
 
@@ -32,6 +34,9 @@ constexpr int kEpiLds = 32 * 1024;                // epilogue scratch, disjoint 
 constexpr int kGemmLds = kStagesLds + kEpiLds;    // 160 KiB: the whole LDS of a CU
 constexpr int kGroupM = 8;                        // raster: weight-row tiles per group
 constexpr int kXcds = 8;
+#ifndef ZO_HEAD_WAVES
+#define ZO_HEAD_WAVES 4
+#endif
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -59,17 +64,19 @@ __device__ __forceinline__ void block_barrier() {
 // byte 16*i of the block, i.e. row i/8, physical chunk i%8, which holds logical chunk
 // (i%8) ^ ((row>>1)&7).  Rows past the end of a matrix are clamped to its last row (their
 // results are never stored); the buffer resources bound every access to the matrix anyway.
+template <int LPW>   // loads per wave per operand tile (8 with four waves, 4 with eight)
 struct OperandStream {
   __amdgpu_buffer_rsrc_t rA, rB;
-  uint32_t offA[8], offB[8];
+  uint32_t offA[LPW], offB[LPW];
 };
 
-__device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
+template <int LPW>
+__device__ __forceinline__ void setup_stream(OperandStream<LPW>& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
                                              const bf16_t* B, int64_t ldb, int N, int tile_n0, int K, int wave,
                                              int lane) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int row = (wave * 8 + j) * 8 + (lane >> 3);
+  for (int j = 0; j < LPW; ++j) {
+    const int row = (wave * LPW + j) * 8 + (lane >> 3);
     const int lch = (lane & 7) ^ ((row >> 1) & 7);
     const int ra = min(tile_m0 + row, M - 1) - tile_m0;
     const int rbn = min(tile_n0 + row, N - 1) - tile_n0;
@@ -102,14 +109,30 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
 // fetched under k-step 3).  The load cursor runs ahead of the compute cursor across
 // output-tile boundaries; past the workgroup's last tile it stays on the final K tile
 // (those loads refill stages nobody reads again).
-template <class Pre, class Post>
+// Wave layouts.  WAVES = 4: 2x2 waves of 128x128 (one wave per SIMD, all 256 accumulators of a
+// lane in use).  WAVES = 8: 2x4 waves of 128 weight rows x 64 tokens (two waves per SIMD: while
+// one wave is held up issuing a memory instruction the other keeps the matrix core fed, at the
+// price of 1.5x the LDS fragment reads).
+template <int WAVES>
+struct WaveShape {
+  static constexpr int kWN = WAVES / 2;            // waves along tokens
+  static constexpr int kRB = 4;                    // 32-row blocks per wave (128 weight rows)
+  static constexpr int kCB = (BN / kWN) / 32;      // 32-token blocks per wave (4 or 2)
+  static constexpr int kLPW = 32 / WAVES;          // loads per wave per operand tile
+};
+
+template <int WAVES, class Pre, class Post>
 __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
                                                 int n_tm, int n_tn, char* lds, Pre pre, Post post) {
+  using WS = WaveShape<WAVES>;
+  constexpr int RB = WS::kRB, CB = WS::kCB, LPW = WS::kLPW;
+  constexpr int NL = 2 * LPW;                      // loads per wave per K tile
+  constexpr int L3 = (NL * 3 + 7) / 8, L0 = (NL - L3 + 1) / 2, L1 = NL - L3 - L0;   // 16 -> 6,5,5;  8 -> 3,3,2
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WS::kWN, wn = wave % WS::kWN;
 
   // this workgroup's tiles: positions first, first + stride, ... of its XCD's share of the raster
   const int total = n_tm * n_tn;
@@ -127,27 +150,27 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   uint32_t roff[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) roff[kk] = lrow * 128 + (((kk * 2 + (lane >> 5)) ^ swz) << 4);
-  const uint32_t aBase = wm * 128 * 128, bBase = kOperandStage + wn * 128 * 128;
+  const uint32_t aBase = wm * 128 * 128, bBase = kOperandStage + wn * (CB * 32) * 128;
 
   // load cursor
-  OperandStream ld;
+  OperandStream<LPW> ld;
   int ld_L = L, ld_kt = 0;
   {
     int tm, tn;
     tile_at(ld_L, n_tm, n_tn, tm, tn);
     setup_stream(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane);
   }
-  // load i (0..15) of the cursor's K tile: i < 8 -> A chunk i, else B chunk i - 8
+  // load i (0..NL-1) of the cursor's K tile: i < LPW -> A chunk i, else B chunk i - LPW
   auto issue_range = [&](int stage, int first, int count) {
-    char* sbase = lds + stage * kStage + wave * 8 * 1024;
+    char* sbase = lds + stage * kStage + wave * LPW * 1024;
     const int koff = ld_kt * (BK * 2);
 #pragma unroll
     for (int i = first; i < first + count; ++i) {
-      if (i < 8)
+      if (i < LPW)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rA, (lds_void*)(sbase + i * 1024), 16, (int)ld.offA[i], koff, 0, 0);
       else
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rB, (lds_void*)(sbase + kOperandStage + (i - 8) * 1024), 16,
-                                                 (int)ld.offB[i - 8], koff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rB, (lds_void*)(sbase + kOperandStage + (i - LPW) * 1024), 16,
+                                                 (int)ld.offB[i - LPW], koff, 0, 0);
     }
   };
   auto advance_cursor = [&]() {
@@ -161,79 +184,74 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     }
   };
 
-  bf16x8 fa[2][4], fb[2][4];
+  bf16x8 fa[2][RB], fb[2][CB];
   auto load_frags = [&](int set, int stage, int kk) {
     const char* s = lds + stage * kStage;
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 4096 + roff[kk]);
+    for (int rb = 0; rb < RB; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 4096 + roff[kk]);
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) fb[set][cb] = *(const bf16x8*)(s + bBase + cb * 4096 + roff[kk]);
+    for (int cb = 0; cb < CB; ++cb) fb[set][cb] = *(const bf16x8*)(s + bBase + cb * 4096 + roff[kk]);
+  };
+  // scheduling of one k-step: the RB+CB LDS reads and `loads` direct-to-LDS loads go under the
+  // first MFMAs (one read per MFMA, a load after every other one), the rest of the MFMAs follow
+  auto pattern = [&](auto loads_tag) {
+    constexpr int loads = decltype(loads_tag)::value;
+#pragma unroll
+    for (int i = 0; i < RB + CB; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+      if (i < loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // direct-to-LDS load
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, RB * CB - (RB + CB), 0);
   };
 
   // prologue: first K tile of the first output tile, and the head of the second K tile
-  issue_range(0, 0, 16);
+  issue_range(0, 0, NL);
   advance_cursor();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   block_barrier();
   load_frags(0, 0, 0);
-  issue_range(1, 0, 6);
+  issue_range(1, 0, L3);
 
   int stage = 0;
   for (; L < L_end; L += stride) {
     int tm, tn;
     tile_at(L, n_tm, n_tn, tm, tn);
-    f32x16 acc[4][4];
+    f32x16 acc[RB][CB];
 #pragma unroll
-    for (int rb = 0; rb < 4; ++rb)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb)
+      for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
     pre(tm, tn, acc);
 
     auto mfmas = [&](int set) {
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
+        for (int cb = 0; cb < CB; ++cb)
           acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
     };
 
     for (int kt = 0; kt < nk; ++kt) {
       // k-step 0
       __builtin_amdgcn_sched_barrier(0);
-      issue_range(stage ^ 1, 6, 5);
+      issue_range(stage ^ 1, L3, L0);
       load_frags(1, stage, 1);
       mfmas(0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-        if (i % 2 == 1 || i == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // direct-to-LDS load
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      pattern(std::integral_constant<int, L0>{});
       __builtin_amdgcn_sched_barrier(0);
       // k-step 1
-      issue_range(stage ^ 1, 11, 5);
+      issue_range(stage ^ 1, L3 + L0, L1);
       load_frags(0, stage, 2);
       mfmas(1);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (i % 2 == 1 || i == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      pattern(std::integral_constant<int, L1>{});
       __builtin_amdgcn_sched_barrier(0);
       // k-step 2
       load_frags(1, stage, 3);
       mfmas(0);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      pattern(std::integral_constant<int, 0>{});
       __builtin_amdgcn_sched_barrier(0);
       // the next K tile has landed; every wave is done reading this K tile's stage
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -241,16 +259,10 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
       advance_cursor();
       __builtin_amdgcn_sched_barrier(0);
       // k-step 3: first fragments of the next K tile, first loads of the one after it
-      issue_range(stage, 0, 6);
+      issue_range(stage, 0, L3);
       load_frags(0, stage ^ 1, 0);
       mfmas(1);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        if (i % 2 == 1 || i == 0 || i == 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      pattern(std::integral_constant<int, L3>{});
       __builtin_amdgcn_sched_barrier(0);
       stage ^= 1;
     }
@@ -410,7 +422,7 @@ __global__ __launch_bounds__(256, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm
     }
   };
 
-  persistent_gemm(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
+  persistent_gemm<4>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
 }
 
 template <bool kSide, bool kOutBf16, bool kBias>
@@ -446,24 +458,27 @@ hipError_t launch_probe_gemm_bf16(const ProbeGemmArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------------------------------
 int head_vocab_tiles_bf16(int vocab) { return (vocab + BM - 1) / BM; }
 
-__global__ __launch_bounds__(256, 1) void k_head_score(HeadScoreArgs p, int n_tm, int n_tn) {
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 1) void k_head_score(HeadScoreArgs p, int n_tm, int n_tn) {
+  using WS = WaveShape<WAVES>;
+  constexpr int CB = WS::kCB;
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WS::kWN, wn = wave % WS::kWN;
   const int lrow = lane & 31, lhalf = lane >> 5;
   float* s_max = (float*)(lds + kStagesLds);   // [2][256]
   float* s_sum = s_max + 2 * BN;                // [2][256]
   constexpr float kLog2e = 1.4426950408889634f;
 
-  auto no_side = [](int, int, f32x16 (&)[4][4]) {};
-  auto epilogue = [&](int tm, int tn, f32x16 (&acc)[4][4]) {
+  auto no_side = [](int, int, f32x16 (&)[4][CB]) {};
+  auto epilogue = [&](int tm, int tn, f32x16 (&acc)[4][CB]) {
     const int tile_v0 = tm * BM, tile_t0 = tn * BN;
     const int vbase = tile_v0 + wm * 128;  // first vocabulary row of this wave
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) {
-      const int tl = wn * 128 + cb * 32 + lrow;   // token within the tile
+    for (int cb = 0; cb < CB; ++cb) {
+      const int tl = wn * (CB * 32) + cb * 32 + lrow;   // token within the tile
       const int t = tile_t0 + tl;
       float mx = -INFINITY;
 #pragma unroll
@@ -501,7 +516,7 @@ __global__ __launch_bounds__(256, 1) void k_head_score(HeadScoreArgs p, int n_tm
     __syncthreads();
     {
       const int t = tile_t0 + tid;
-      if (t < p.T) {
+      if (tid < BN && t < p.T) {
         const float m0 = s_max[tid], m1 = s_max[BN + tid];
         const float Mx = fmaxf(m0, m1);
         const float mref = (Mx == -INFINITY) ? 0.0f : Mx;
@@ -514,19 +529,21 @@ __global__ __launch_bounds__(256, 1) void k_head_score(HeadScoreArgs p, int n_tm
     __syncthreads();   // the exchange buffers are free again for the next tile
   };
 
-  persistent_gemm(p.Wh, p.ldw, p.vocab, p.H, p.ldh, p.T, p.d, n_tm, n_tn, lds, no_side, epilogue);
+  persistent_gemm<WAVES>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, p.T, p.d, n_tm, n_tn, lds, no_side, epilogue);
 }
+
+constexpr int kHeadWaves = ZO_HEAD_WAVES;
 
 hipError_t launch_head_score_bf16(const HeadScoreArgs& a, hipStream_t st) {
   if (a.T == 0) return hipSuccess;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_head_score, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    hipError_t e = hipFuncSetAttribute((const void*)k_head_score<kHeadWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int n_tm = (a.vocab + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL(k_head_score, dim3(gemm_grid(n_tm * n_tn)), dim3(256), kGemmLds, st, a, n_tm, n_tn);
+  hipLaunchKernelGGL((k_head_score<kHeadWaves>), dim3(gemm_grid(n_tm * n_tn)), dim3(kHeadWaves * 64), kGemmLds, st, a, n_tm, n_tn);
   return hipGetLastError();
 }
 
