@@ -3,11 +3,16 @@
 // LM-head scoring (Sec. 3.3: per-request NLL without materialising logits).
 //
 // Both are one persistent 256x256x64-tiled bf16 GEMM with fp32 accumulation on
-// v_mfma_f32_32x32x16_bf16.  One workgroup per CU; four waves in a 2x2 grid own
-// 128x128 each.  MFMA rows are the rows of the weight matrix (out features /
-// vocabulary), MFMA columns are tokens: a lane then holds 16 weight-row values
-// of ONE token per 32x32 block, which keeps the vocabulary reduction of the
-// head in registers and packs probe outputs into contiguous bf16.
+// v_mfma_f32_16x16x32_bf16.  One workgroup of eight waves per CU (two per
+// SIMD); the waves form a 2x4 grid, each owning 128 weight rows x 64 tokens
+// (8x4 blocks of 16x16, 128 accumulator registers per lane).  With two waves
+// per SIMD the matrix core stays fed while the other wave is held up issuing
+// memory instructions, and on this power-limited part the K=32 instruction
+// sustains the highest MFMA rate.  MFMA rows are the rows of the weight matrix
+// (out features / vocabulary), MFMA columns are tokens: a lane holds 4
+// consecutive weight-row values of ONE token per block, which keeps the
+// vocabulary reduction of the head in registers and packs probe outputs into
+// contiguous bf16.
 //
 // Operand tiles stream global -> LDS with direct-to-LDS buffer loads into a
 // double-buffered, XOR-swizzled layout.  The stream of K tiles does not stop at
@@ -34,14 +39,22 @@ constexpr int kEpiLds = 32 * 1024;                // epilogue scratch, disjoint 
 constexpr int kGemmLds = kStagesLds + kEpiLds;    // 160 KiB: the whole LDS of a CU
 constexpr int kGroupM = 8;                        // raster: weight-row tiles per group
 constexpr int kXcds = 8;
-#ifndef ZO_HEAD_WAVES
-#define ZO_HEAD_WAVES 4
+constexpr int kWaves = 8;                         // 2 (weight rows) x 4 (tokens)
+constexpr int kThreads = kWaves * 64;
+constexpr int RB = 8;                             // 16-row blocks per wave: 128 weight rows
+constexpr int CB = 4;                             // 16-token blocks per wave: 64 tokens
+constexpr int kLPW = 32 / kWaves;                 // direct-to-LDS loads per wave per operand tile
+#ifndef ZO_LOADS_AFTER_BARRIER
+#define ZO_LOADS_AFTER_BARRIER 4
 #endif
+constexpr int kLoadsLate = ZO_LOADS_AFTER_BARRIER;   // loads of a K tile issued in the k-step after the barrier
+constexpr int kLoadsEarly = 2 * kLPW - kLoadsLate;   // ... and in the k-step before the next barrier
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef u32x2 __attribute__((may_alias)) u32x2_alias;   // LDS staging is written and read back with different widths
 typedef u32x4 __attribute__((may_alias)) u32x4_alias;
+typedef f32x4 Acc[RB][CB];
 
 // Position L of the grouped raster -> output tile (tm = weight-row tile, tn = token tile).
 __device__ __forceinline__ void tile_at(int L, int n_tm, int n_tn, int& tm, int& tn) {
@@ -53,35 +66,42 @@ __device__ __forceinline__ void tile_at(int L, int n_tm, int n_tn, int& tm, int&
   tn = in_g / gsize;
 }
 
+// A copy of x the optimiser cannot see through.  Per-tile code derives its lane-dependent
+// addressing from such a copy so that those values are recomputed per tile instead of being
+// hoisted out of the tile loop, where they would occupy registers throughout the K loop.
+__device__ __forceinline__ int opaque(int x) {
+  asm volatile("" : "+v"(x));
+  return x;
+}
+
 __device__ __forceinline__ void block_barrier() {
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 }
 
-// Per-lane addressing of one output tile's operand stream.  Load j (0..7) of a wave
-// fills the 1 KiB block (wave*8 + j) of an operand tile: 8 rows x 128 B.  Lane i lands at
+// Per-lane addressing of one output tile's operand stream.  Load j (0..3) of a wave
+// fills the 1 KiB block (wave*4 + j) of an operand tile: 8 rows x 128 B.  Lane i lands at
 // byte 16*i of the block, i.e. row i/8, physical chunk i%8, which holds logical chunk
 // (i%8) ^ ((row>>1)&7).  Rows past the end of a matrix are clamped to its last row (their
 // results are never stored); the buffer resources bound every access to the matrix anyway.
-template <int LPW>   // loads per wave per operand tile (8 with four waves, 4 with eight)
 struct OperandStream {
   __amdgpu_buffer_rsrc_t rA, rB;
-  uint32_t offA[LPW], offB[LPW];
+  uint32_t offA[kLPW], offB[kLPW];
 };
 
-template <int LPW>
-__device__ __forceinline__ void setup_stream(OperandStream<LPW>& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
+__device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
                                              const bf16_t* B, int64_t ldb, int N, int tile_n0, int K, int wave,
                                              int lane) {
 #pragma unroll
-  for (int j = 0; j < LPW; ++j) {
-    const int row = (wave * LPW + j) * 8 + (lane >> 3);
+  for (int j = 0; j < kLPW; ++j) {
+    const int row = (wave * kLPW + j) * 8 + (lane >> 3);
     const int lch = (lane & 7) ^ ((row >> 1) & 7);
     const int ra = min(tile_m0 + row, M - 1) - tile_m0;
     const int rbn = min(tile_n0 + row, N - 1) - tile_n0;
-    o.offA[j] = (uint32_t)((int64_t)ra * lda * 2 + lch * 16);
-    o.offB[j] = (uint32_t)((int64_t)rbn * ldb * 2 + lch * 16);
+    // 24-bit multiply: a tile has 256 rows and the launchers reject row pitches of 16 MiB or more
+    o.offA[j] = __umul24((uint32_t)ra, (uint32_t)lda * 2u) + lch * 16;
+    o.offB[j] = __umul24((uint32_t)rbn, (uint32_t)ldb * 2u) + lch * 16;
   }
   const int64_t bytesA = ((int64_t)(M - tile_m0 - 1) * lda + K) * 2;
   const int64_t bytesB = ((int64_t)(N - tile_n0 - 1) * ldb + K) * 2;
@@ -96,43 +116,28 @@ __device__ __forceinline__ void setup_stream(OperandStream<LPW>& o, const bf16_t
 //   acc[rb][cb] += A[tile rows] * B[tile rows]^T over K (multiple of 64),
 //   post(tm, tn, acc)  consumes the accumulators (it may use lds + kStagesLds .. +kEpiLds
 //                      and workgroup barriers; it must not touch the operand stages).
+// 16x16x32 fragments: lane l holds row l%16 and the 8 k-values of group l/16; D: lane l holds
+// rows 4*(l/16) + v (v = 0..3) of column l%16.
 //
 // Pipeline of the K loop.  K tiles of 64 (128-byte row segments, so every L2 request is a
-// full line) alternate between two LDS stages.  A K tile is four k-steps of 16; MFMA
-// fragments are double buffered in registers and the LDS reads of the next k-step run
-// under the 16 MFMAs of the current one.  The 16 direct-to-LDS loads a wave issues per
-// K tile are spread thinly (one per ~3 MFMAs) over k-step 3 of the previous K tile and
-// k-steps 0..1 of the current one: a burst would fill the memory pipeline's queues and
-// stall the wave, and with it the MFMA stream.  The single barrier of a K tile sits before
-// k-step 3: by then every wave has read its last fragments of this K tile's stage (so the
-// stage can be refilled) and the next K tile has landed (so its first fragments can be
-// fetched under k-step 3).  The load cursor runs ahead of the compute cursor across
-// output-tile boundaries; past the workgroup's last tile it stays on the final K tile
-// (those loads refill stages nobody reads again).
-// Wave layouts.  WAVES = 4: 2x2 waves of 128x128 (one wave per SIMD, all 256 accumulators of a
-// lane in use).  WAVES = 8: 2x4 waves of 128 weight rows x 64 tokens (two waves per SIMD: while
-// one wave is held up issuing a memory instruction the other keeps the matrix core fed, at the
-// price of 1.5x the LDS fragment reads).
-template <int WAVES>
-struct WaveShape {
-  static constexpr int kWN = WAVES / 2;            // waves along tokens
-  static constexpr int kRB = 4;                    // 32-row blocks per wave (128 weight rows)
-  static constexpr int kCB = (BN / kWN) / 32;      // 32-token blocks per wave (4 or 2)
-  static constexpr int kLPW = 32 / WAVES;          // loads per wave per operand tile
-};
-
-template <int WAVES, class Pre, class Post>
+// full line) alternate between two LDS stages.  A K tile is two k-steps of 32; the 12 LDS
+// reads of the next k-step's fragments are spread under the 32 MFMAs of the current one
+// (an A fragment's registers are reused once its four MFMAs have issued).  The 8
+// direct-to-LDS loads a wave issues per K tile are spread thinly over the two k-steps: a
+// burst fills the memory pipeline's queues and stalls the wave at issue.  The single
+// barrier of a K tile sits between its two k-steps: by then every wave has read its last
+// fragments of this K tile's stage (so the stage can be refilled) and the next K tile has
+// landed (so its first fragments can be fetched under the second k-step).  The load cursor
+// runs ahead of the compute cursor across output-tile boundaries; past the workgroup's
+// last tile it stays on the final K tile (those loads refill stages nobody reads again).
+template <class Pre, class Post>
 __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
                                                 int n_tm, int n_tn, char* lds, Pre pre, Post post) {
-  using WS = WaveShape<WAVES>;
-  constexpr int RB = WS::kRB, CB = WS::kCB, LPW = WS::kLPW;
-  constexpr int NL = 2 * LPW;                      // loads per wave per K tile
-  constexpr int L3 = (NL * 3 + 7) / 8, L0 = (NL - L3 + 1) / 2, L1 = NL - L3 - L0;   // 16 -> 6,5,5;  8 -> 3,3,2
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int wm = wave / WS::kWN, wn = wave % WS::kWN;
+  const int wm = wave >> 2, wn = wave & 3;
 
   // this workgroup's tiles: positions first, first + stride, ... of its XCD's share of the raster
   const int total = n_tm * n_tn;
@@ -144,33 +149,33 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   if (L >= L_end) return;
   const int nk = K / BK;
 
-  // LDS -> register mapping (32x32x16 fragments: lane l holds row l%32, k-group l/32)
-  const int lrow = lane & 31;
-  const int swz = (lrow >> 1) & 7;
-  uint32_t roff[4];
+  // LDS -> register mapping
+  const int r16 = lane & 15;
+  const int swz = (r16 >> 1) & 7;
+  uint32_t roff[2];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) roff[kk] = lrow * 128 + (((kk * 2 + (lane >> 5)) ^ swz) << 4);
-  const uint32_t aBase = wm * 128 * 128, bBase = kOperandStage + wn * (CB * 32) * 128;
+  for (int ks = 0; ks < 2; ++ks) roff[ks] = r16 * 128 + (((ks * 4 + (lane >> 4)) ^ swz) << 4);
+  const uint32_t aBase = wm * 128 * 128, bBase = kOperandStage + wn * 64 * 128;
 
   // load cursor
-  OperandStream<LPW> ld;
+  OperandStream ld;
   int ld_L = L, ld_kt = 0;
   {
     int tm, tn;
     tile_at(ld_L, n_tm, n_tn, tm, tn);
     setup_stream(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane);
   }
-  // load i (0..NL-1) of the cursor's K tile: i < LPW -> A chunk i, else B chunk i - LPW
+  // load i (0..7) of the cursor's K tile: i < 4 -> A chunk i, else B chunk i - 4
   auto issue_range = [&](int stage, int first, int count) {
-    char* sbase = lds + stage * kStage + wave * LPW * 1024;
+    char* sbase = lds + stage * kStage + wave * kLPW * 1024;
     const int koff = ld_kt * (BK * 2);
 #pragma unroll
     for (int i = first; i < first + count; ++i) {
-      if (i < LPW)
+      if (i < kLPW)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rA, (lds_void*)(sbase + i * 1024), 16, (int)ld.offA[i], koff, 0, 0);
       else
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rB, (lds_void*)(sbase + kOperandStage + (i - LPW) * 1024), 16,
-                                                 (int)ld.offB[i - LPW], koff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rB, (lds_void*)(sbase + kOperandStage + (i - kLPW) * 1024), 16,
+                                                 (int)ld.offB[i - kLPW], koff, 0, 0);
     }
   };
   auto advance_cursor = [&]() {
@@ -185,84 +190,76 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   };
 
   bf16x8 fa[2][RB], fb[2][CB];
-  auto load_frags = [&](int set, int stage, int kk) {
+  // token fragments first: every MFMA of the next k-step needs one of them
+  auto load_frags = [&](int set, int stage, int ks) {
     const char* s = lds + stage * kStage;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 4096 + roff[kk]);
+    for (int cb = 0; cb < CB; ++cb) fb[set][cb] = *(const bf16x8*)(s + bBase + cb * 2048 + roff[ks]);
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb) fb[set][cb] = *(const bf16x8*)(s + bBase + cb * 4096 + roff[kk]);
+    for (int rb = 0; rb < RB; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 2048 + roff[ks]);
   };
-  // scheduling of one k-step: the RB+CB LDS reads and `loads` direct-to-LDS loads go under the
-  // first MFMAs (one read per MFMA, a load after every other one), the rest of the MFMAs follow
-  auto pattern = [&](auto loads_tag) {
-    constexpr int loads = decltype(loads_tag)::value;
+  // scheduling of one k-step with n_loads direct-to-LDS loads: in every group of 8 MFMAs,
+  // 3 LDS reads and n_loads/4 loads
+  auto pattern = [&](auto n_loads_c) {
+    constexpr int n_loads = decltype(n_loads_c)::value;
 #pragma unroll
-    for (int i = 0; i < RB + CB; ++i) {
+    for (int i = 0; i < RB * CB; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
-      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-      if (i < loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // direct-to-LDS load
+      const int j = i & 7;
+      if (j == 0 || j == 3 || j == 5) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+      if (n_loads * (i + 1) / (RB * CB) != n_loads * i / (RB * CB))
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // direct-to-LDS load
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, RB * CB - (RB + CB), 0);
   };
 
-  // prologue: first K tile of the first output tile, and the head of the second K tile
-  issue_range(0, 0, NL);
+  // prologue: first K tile of the first output tile, and the late part of the second K tile's loads
+  issue_range(0, 0, 2 * kLPW);
   advance_cursor();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   block_barrier();
   load_frags(0, 0, 0);
-  issue_range(1, 0, L3);
+  issue_range(1, 0, kLoadsLate);
 
   int stage = 0;
   for (; L < L_end; L += stride) {
     int tm, tn;
     tile_at(L, n_tm, n_tn, tm, tn);
-    f32x16 acc[RB][CB];
+    Acc acc;
 #pragma unroll
     for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[rb][cb][v] = 0.0f;
+      for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
     pre(tm, tn, acc);
+    // The first fragments of this tile were already fetched under the previous tile's last
+    // k-step; fetching them again here keeps their 48 registers free during post() and pre().
+    load_frags(0, stage, 0);
 
     auto mfmas = [&](int set) {
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb)
-          acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
     };
 
     for (int kt = 0; kt < nk; ++kt) {
-      // k-step 0
+      // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
       __builtin_amdgcn_sched_barrier(0);
-      issue_range(stage ^ 1, L3, L0);
+      issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
       load_frags(1, stage, 1);
       mfmas(0);
-      pattern(std::integral_constant<int, L0>{});
-      __builtin_amdgcn_sched_barrier(0);
-      // k-step 1
-      issue_range(stage ^ 1, L3 + L0, L1);
-      load_frags(0, stage, 2);
-      mfmas(1);
-      pattern(std::integral_constant<int, L1>{});
-      __builtin_amdgcn_sched_barrier(0);
-      // k-step 2
-      load_frags(1, stage, 3);
-      mfmas(0);
-      pattern(std::integral_constant<int, 0>{});
+      pattern(std::integral_constant<int, kLoadsEarly>{});
       __builtin_amdgcn_sched_barrier(0);
       // the next K tile has landed; every wave is done reading this K tile's stage
       asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
       block_barrier();
       advance_cursor();
       __builtin_amdgcn_sched_barrier(0);
-      // k-step 3: first fragments of the next K tile, first loads of the one after it
-      issue_range(stage, 0, L3);
+      // k-step 1: first fragments of the next K tile, first loads of the one after it
+      issue_range(stage, 0, kLoadsLate);
       load_frags(0, stage ^ 1, 0);
       mfmas(1);
-      pattern(std::integral_constant<int, L3>{});
+      pattern(std::integral_constant<int, kLoadsLate>{});
       __builtin_amdgcn_sched_barrier(0);
       stage ^= 1;
     }
@@ -291,25 +288,27 @@ static int gemm_grid(int total_tiles) {
 // all-foreground call.
 // ---------------------------------------------------------------------------------------
 template <bool kSide, bool kOutBf16, bool kBias>
-__global__ __launch_bounds__(256, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn) {
+__global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int lrow = lane & 31, lhalf = lane >> 5, kg = lhalf * 8;
+  const int wm = wave >> 2, wn = wave & 3;
 
-  auto side_phase = [&](int tm, int tn, f32x16 (&acc)[4][4]) {
+  // side operands have K = RP (direction) and K = Rp (bank), multiples of 16; the K=32
+  // instruction takes them 32 at a time, lanes whose k-group lies past the end supply zeros
+  auto side_phase = [&](int tm, int tn, Acc& acc) {
     if constexpr (!kSide) return;
+    const int lane_t = opaque(lane);
+    const int r16 = lane_t & 15, kg = (lane_t >> 4) * 8;
     const int tile_o0 = tm * BM, tile_t0 = tn * BN;
     const int NC = p.RP + p.Rp;
     const int tile_end = min(tile_t0 + BN, p.T);
-    int feat[4], tok[4];
+    int feat[RB], tok[CB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      feat[i] = min(tile_o0 + wm * 128 + i * 32 + lrow, p.m - 1);
-      tok[i] = tile_t0 + wn * 128 + i * 32 + lrow;
-    }
+    for (int i = 0; i < RB; ++i) feat[i] = min(tile_o0 + wm * 128 + i * 16 + r16, p.m - 1);
+#pragma unroll
+    for (int i = 0; i < CB; ++i) tok[i] = tile_t0 + wn * 64 + i * 16 + r16;
     // walk the sequences that intersect this token tile
     int s = __builtin_amdgcn_readfirstlane(p.tok_seq[tile_t0]);
     bool any_cand = false;
@@ -321,108 +320,109 @@ __global__ __launch_bounds__(256, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm
       if (seg_hi > seg_lo && kind >= kKindCentre) any_cand = true;
       if (seg_hi > seg_lo && kind >= 0) {
         const bf16_t* Ud = p.Uh + (int64_t)kind * p.m * p.RP;
-        for (int ks = 0; ks < p.RP; ks += 16) {
-          bf16x8 fa[4], fb[4];
+        for (int ks = 0; ks < p.RP; ks += 32) {
+          const bool kin = ks + kg < p.RP;
+          bf16x8 sa[RB], sb[CB];
 #pragma unroll
-          for (int rb = 0; rb < 4; ++rb) fa[rb] = load_frag(Ud + (int64_t)feat[rb] * p.RP + ks + kg);
+          for (int rb = 0; rb < RB; ++rb) sa[rb] = kin ? load_frag(Ud + (int64_t)feat[rb] * p.RP + ks + kg) : zero_frag();
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) {
-            const bool in = tok[cb] >= seg_lo && tok[cb] < seg_hi;
-            fb[cb] = in ? load_frag(p.Aside + (int64_t)tok[cb] * NC + ks + kg) : zero_frag();
+          for (int cb = 0; cb < CB; ++cb) {
+            const bool in = kin && tok[cb] >= seg_lo && tok[cb] < seg_hi;
+            sb[cb] = in ? load_frag(p.Aside + (int64_t)tok[cb] * NC + ks + kg) : zero_frag();
           }
 #pragma unroll
-          for (int rb = 0; rb < 4; ++rb)
+          for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int cb = 0; cb < 4; ++cb)
-              acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[rb], fb[cb], acc[rb][cb], 0, 0, 0);
+            for (int cb = 0; cb < CB; ++cb)
+              acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[rb], sb[cb], acc[rb][cb], 0, 0, 0);
         }
       }
       if (seq_end >= tile_end || s + 1 >= p.S) break;
       ++s;
     }
     if (any_cand && p.Rp > 0) {
-      for (int ks = 0; ks < p.Rp; ks += 16) {
-        bf16x8 fa[4], fb[4];
+      for (int ks = 0; ks < p.Rp; ks += 32) {
+        const bool kin = ks + kg < p.Rp;
+        bf16x8 sa[RB], sb[CB];
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) fa[rb] = load_frag(p.Ph + (int64_t)feat[rb] * p.Rp + ks + kg);
+        for (int rb = 0; rb < RB; ++rb) sa[rb] = kin ? load_frag(p.Ph + (int64_t)feat[rb] * p.Rp + ks + kg) : zero_frag();
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-          fb[cb] = load_frag(p.Aside + (int64_t)min(tok[cb], p.T - 1) * NC + p.RP + ks + kg);
+        for (int cb = 0; cb < CB; ++cb)
+          sb[cb] = kin ? load_frag(p.Aside + (int64_t)min(tok[cb], p.T - 1) * NC + p.RP + ks + kg) : zero_frag();
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[rb], fb[cb], acc[rb][cb], 0, 0, 0);
+          for (int cb = 0; cb < CB; ++cb)
+            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[rb], sb[cb], acc[rb][cb], 0, 0, 0);
       }
     }
   };
 
-  // D[i][j]: i = 8*(v/4) + 4*(lane/32) + v%4 (out feature), j = lane%32 (token).
-  auto epilogue = [&](int tm, int tn, f32x16 (&acc)[4][4]) {
+  // D block (rb, cb): out feature = obase + rb*16 + 4*g + v, token = tbase + cb*16 + r16.
+  auto epilogue = [&](int tm, int tn, Acc& acc) {
+    const int lane_t = opaque(lane);
+    const int r16 = lane_t & 15, g = lane_t >> 4;
     const int obase = tm * BM + wm * 128;   // first out feature of this wave
-    const int tbase = tn * BN + wn * 128;   // first token of this wave
+    const int tbase = tn * BN + wn * 64;    // first token of this wave
+    const float floor_val = p.act == 1 ? 0.0f : -INFINITY;   // ReLU as a clamp: no branch in the tile epilogue
     if constexpr (!kOutBf16) {
       float* Y = (float*)p.Y;
 #pragma unroll
-      for (int cb = 0; cb < 4; ++cb) {
-        const int t = tbase + cb * 32 + lrow;
+      for (int cb = 0; cb < CB; ++cb) {
+        const int t = tbase + cb * 16 + r16;
         if (t >= p.T) continue;
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int o = obase + rb * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+          for (int v = 0; v < 4; ++v) {
+            const int o = obase + rb * 16 + 4 * g + v;
             if (o >= p.m) continue;
             float y = acc[rb][cb][v];
             if constexpr (kBias) y += p.bias[o];
-            if (p.act == 1) y = fmaxf(y, 0.0f);
-            Y[(int64_t)t * p.ldy + o] = y;
+            Y[(int64_t)t * p.ldy + o] = fmaxf(y, floor_val);
           }
       }
       return;
     }
-    // bf16: bias / activation / rounding in registers, then 32 tokens x 128 features at a
-    // time through this wave's own 8 KiB of LDS (XOR-swizzled 16-byte slots) so that the
+    // bf16: bias / activation / rounding in registers, then 16 tokens x 128 features at a
+    // time through this wave's own 4 KiB of LDS (XOR-swizzled 16-byte slots) so that the
     // global stores are 16 bytes per lane and cover 256 contiguous bytes per token row.
-    char* region = lds + kStagesLds + wave * 8192;
+    char* region = lds + kStagesLds + wave * 4096;
     bf16_t* Y = (bf16_t*)p.Y;
-    const int chunk = lane & 15;              // 8 out features (16 bytes) of a token row
+    const int chunk = lane_t & 15;            // 8 out features (16 bytes) of a token row
     const int o = obase + chunk * 8;
-    const float floor_val = p.act == 1 ? 0.0f : -INFINITY;   // ReLU as a clamp: no branch in the tile epilogue
-    const uint32_t wr_base = lrow * 256 + lhalf * 8;
-    const uint32_t wr_swz = (lrow & 15) * 16;
+    const uint32_t wr_base = r16 * 256 + (g & 1) * 8;
+    const uint32_t wr_swz = r16 * 16;
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) {
+    for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
+      for (int rb = 0; rb < RB; ++rb) {
+        float y[4];
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          float y[4];
+        for (int e = 0; e < 4; ++e) y[e] = acc[rb][cb][e];
+        if constexpr (kBias) {
+          const int ob = obase + rb * 16 + 4 * g;   // this lane's 4 consecutive out features
 #pragma unroll
-          for (int e = 0; e < 4; ++e) y[e] = acc[rb][cb][g * 4 + e];
-          if constexpr (kBias) {
-            const int ob = obase + rb * 32 + 8 * g + 4 * lhalf;   // this lane's 4 consecutive out features
-#pragma unroll
-            for (int e = 0; e < 4; ++e) y[e] += p.bias[min(ob + e, p.m - 1)];
-          }
-#pragma unroll
-          for (int e = 0; e < 4; ++e) y[e] = fmaxf(y[e], floor_val);
-          *(u32x2_alias*)(region + wr_base + (((rb * 4 + g) * 16) ^ wr_swz)) =
-              u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+          for (int e = 0; e < 4; ++e) y[e] += p.bias[min(ob + e, p.m - 1)];
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) y[e] = fmaxf(y[e], floor_val);
+        // 16-byte slot rb*2 + g/2 of the token's row, half g&1
+        *(u32x2_alias*)(region + wr_base + (((rb * 2 + (g >> 1)) * 16) ^ wr_swz)) =
+            u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
       }
       // the wave reads back what it wrote itself: LDS operations of one wave complete in order
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int tl = it * 4 + (lane >> 4);
-        const int t = tbase + cb * 32 + tl;
-        const u32x4 val = *(const u32x4_alias*)(region + tl * 256 + ((chunk ^ (tl & 15)) * 16));
+      for (int it = 0; it < 4; ++it) {
+        const int tl = it * 4 + (lane_t >> 4);
+        const int t = tbase + cb * 16 + tl;
+        const u32x4 val = *(const u32x4_alias*)(region + tl * 256 + ((chunk ^ tl) * 16));
         if (t < p.T && o < p.m) *(u32x4_alias*)(Y + (int64_t)t * p.ldy + o) = val;   // m % 8 == 0
       }
     }
   };
 
-  persistent_gemm<4>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
+  persistent_gemm(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
 }
 
 template <bool kSide, bool kOutBf16, bool kBias>
@@ -435,8 +435,8 @@ static hipError_t launch_probe_variant(const ProbeGemmArgs& a, hipStream_t st) {
     configured = true;
   }
   const int n_tm = (a.m + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias>), dim3(gemm_grid(n_tm * n_tn)), dim3(256), kGemmLds, st,
-                     a, n_tm, n_tn);
+  hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias>), dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds,
+                     st, a, n_tm, n_tn);
   return hipGetLastError();
 }
 
@@ -458,92 +458,93 @@ hipError_t launch_probe_gemm_bf16(const ProbeGemmArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------------------------------
 int head_vocab_tiles_bf16(int vocab) { return (vocab + BM - 1) / BM; }
 
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 1) void k_head_score(HeadScoreArgs p, int n_tm, int n_tn) {
-  using WS = WaveShape<WAVES>;
-  constexpr int CB = WS::kCB;
+__global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int n_tm, int n_tn) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int wm = wave / WS::kWN, wn = wave % WS::kWN;
-  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int wm = wave >> 2, wn = wave & 3;
   float* s_max = (float*)(lds + kStagesLds);   // [2][256]
   float* s_sum = s_max + 2 * BN;                // [2][256]
   constexpr float kLog2e = 1.4426950408889634f;
 
-  auto no_side = [](int, int, f32x16 (&)[4][CB]) {};
-  auto epilogue = [&](int tm, int tn, f32x16 (&acc)[4][CB]) {
+  auto no_side = [](int, int, Acc&) {};
+  // D block (rb, cb): vocabulary row = vbase + rb*16 + 4*g + v, token = tile_t0 + wn*64 + cb*16 + r16.
+  auto epilogue = [&](int tm, int tn, Acc& acc) {
+    const int lane_t = opaque(lane), tid_t = opaque(tid);
+    const int r16 = lane_t & 15, g = lane_t >> 4;
     const int tile_v0 = tm * BM, tile_t0 = tn * BN;
     const int vbase = tile_v0 + wm * 128;  // first vocabulary row of this wave
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
-      const int tl = wn * (CB * 32) + cb * 32 + lrow;   // token within the tile
+      const int tl = wn * 64 + cb * 16 + r16;   // token within the tile
       const int t = tile_t0 + tl;
       float mx = -INFINITY;
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int vr = vbase + rb * 32 + 8 * (v >> 2) + 4 * lhalf + (v & 3);
+        for (int v = 0; v < 4; ++v) {
+          const int vr = vbase + rb * 16 + 4 * g + v;
           if (vr >= p.vocab) acc[rb][cb][v] = -INFINITY;
           mx = fmaxf(mx, acc[rb][cb][v]);
         }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
       const float mref = (mx == -INFINITY) ? 0.0f : mx;
       float sum = 0.0f;
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb)
+      for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f((acc[rb][cb][v] - mref) * kLog2e);
+        for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f((acc[rb][cb][v] - mref) * kLog2e);
+      sum += __shfl_xor(sum, 16);
       sum += __shfl_xor(sum, 32);
-      if (lhalf == 0) { s_max[wm * BN + tl] = mx; s_sum[wm * BN + tl] = sum; }
+      if (g == 0) { s_max[wm * BN + tl] = mx; s_sum[wm * BN + tl] = sum; }
       // target logit: exactly one lane of the whole grid holds it
       if (t < p.T) {
         const int loc = p.targets[t] - vbase;
-        if (loc >= 0 && loc < 128 && ((loc >> 2) & 1) == lhalf) {
-          const int sel = (loc >> 5) * 16 + ((loc & 31) >> 3) * 4 + (loc & 3);
+        if (loc >= 0 && loc < 128 && ((loc >> 2) & 3) == g) {
+          const int sel = (loc >> 4) * 4 + (loc & 3);
           float z = 0.0f;
 #pragma unroll
-          for (int rb = 0; rb < 4; ++rb)
+          for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-              if (sel == rb * 16 + v) z = acc[rb][cb][v];
+            for (int v = 0; v < 4; ++v)
+              if (sel == rb * 4 + v) z = acc[rb][cb][v];
           p.tgt_logit[t] = z;
         }
       }
     }
-    __syncthreads();
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    block_barrier();   // (not __syncthreads: the operand loads of the next tile stay in flight)
     {
-      const int t = tile_t0 + tid;
-      if (tid < BN && t < p.T) {
-        const float m0 = s_max[tid], m1 = s_max[BN + tid];
+      const int t = tile_t0 + tid_t;
+      if (tid_t < BN && t < p.T) {
+        const float m0 = s_max[tid_t], m1 = s_max[BN + tid_t];
         const float Mx = fmaxf(m0, m1);
         const float mref = (Mx == -INFINITY) ? 0.0f : Mx;
-        const float S = s_sum[tid] * __builtin_amdgcn_exp2f((m0 - mref) * kLog2e) +
-                        s_sum[BN + tid] * __builtin_amdgcn_exp2f((m1 - mref) * kLog2e);
+        const float S = s_sum[tid_t] * __builtin_amdgcn_exp2f((m0 - mref) * kLog2e) +
+                        s_sum[BN + tid_t] * __builtin_amdgcn_exp2f((m1 - mref) * kLog2e);
         p.part_max[(int64_t)tm * p.T + t] = Mx;
         p.part_sum[(int64_t)tm * p.T + t] = S;
       }
     }
-    __syncthreads();   // the exchange buffers are free again for the next tile
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    block_barrier();   // the exchange buffers are free again for the next tile
   };
 
-  persistent_gemm<WAVES>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, p.T, p.d, n_tm, n_tn, lds, no_side, epilogue);
+  persistent_gemm(p.Wh, p.ldw, p.vocab, p.H, p.ldh, p.T, p.d, n_tm, n_tn, lds, no_side, epilogue);
 }
-
-constexpr int kHeadWaves = ZO_HEAD_WAVES;
 
 hipError_t launch_head_score_bf16(const HeadScoreArgs& a, hipStream_t st) {
   if (a.T == 0) return hipSuccess;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_head_score<kHeadWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    hipError_t e = hipFuncSetAttribute((const void*)k_head_score, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int n_tm = (a.vocab + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL((k_head_score<kHeadWaves>), dim3(gemm_grid(n_tm * n_tn)), dim3(kHeadWaves * 64), kGemmLds, st, a, n_tm, n_tn);
+  hipLaunchKernelGGL(k_head_score, dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds, st, a, n_tm, n_tn);
   return hipGetLastError();
 }
 
