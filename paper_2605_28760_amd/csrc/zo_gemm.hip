@@ -45,7 +45,7 @@ constexpr int RB = 8;                             // 16-row blocks per wave: 128
 constexpr int CB = 4;                             // 16-token blocks per wave: 64 tokens
 constexpr int kLPW = 32 / kWaves;                 // direct-to-LDS loads per wave per operand tile
 #ifndef ZO_LOADS_AFTER_BARRIER
-#define ZO_LOADS_AFTER_BARRIER 4
+#define ZO_LOADS_AFTER_BARRIER 8
 #endif
 constexpr int kLoadsLate = ZO_LOADS_AFTER_BARRIER;   // loads of a K tile issued in the k-step after the barrier
 constexpr int kLoadsEarly = 2 * kLPW - kLoadsLate;   // ... and in the k-step before the next barrier
