@@ -19,7 +19,8 @@
 // the end of an output tile: while a tile's epilogue runs, the first K tiles of
 // the workgroup's next output tile are already landing.  Workgroups walk a
 // grouped raster so that the 32 workgroups resident on one XCD share an 8x4
-// block of output tiles in that XCD's L2.
+// block of output tiles in that XCD's L2, and the eight XCDs work on
+// neighbouring blocks that share their weight rows.
 //
 // Determinism / batch invariance: the tile shape and the K order never depend
 // on the batch, there is no split-K and no atomic, so a token's result depends
@@ -139,13 +140,18 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   const int lane = tid & 63;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // this workgroup's tiles: positions first, first + stride, ... of its XCD's share of the raster
+  // Workgroup -> tiles.  Consecutive workgroup ids land on consecutive XCDs, so blockIdx.x % 8
+  // is the XCD and blockIdx.x / 8 a slot on it.  The raster is cut into chunks of `slots`
+  // positions (32 on a full chip: an 8x4 block of tiles, 12 operand slices for 32 tiles in
+  // that XCD's L2); chunk c goes to XCD c % 8, so at any time the eight XCDs work on eight
+  // neighbouring chunks, which share their eight weight-row tiles: the weight slices reach
+  // the chip once per step, not once per XCD.
   const int total = n_tm * n_tn;
-  const int per_xcd = (total + kXcds - 1) / kXcds;
   const int xcd = blockIdx.x % kXcds;
-  const int stride = gridDim.x / kXcds;
-  const int L_end = min((xcd + 1) * per_xcd, total);
-  int L = xcd * per_xcd + blockIdx.x / kXcds;
+  const int slots = gridDim.x / kXcds;
+  const int stride = kXcds * slots;
+  const int L_end = total;
+  int L = xcd * slots + blockIdx.x / kXcds;
   if (L >= L_end) return;
   const int nk = K / BK;
 
