@@ -120,6 +120,29 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    # Secondary, outside the timed region: the same forward with every sequence foreground
+    # (candidate id -1: plain base GEMMs and plain scoring), for the probe / plain ratio.
+    from paper_2605_28760_amd.runner import DeviceBatch
+    fg = DeviceBatch(w.cu_seqlens, np.full_like(w.seq_cand, -1), w.cand_dir, w.cand_sign, w.dir_seed, "cuda:0")
+
+    def forward(batch):
+        for i in range(n_layers):
+            d.probe_linear(i, stream=stream, batch=batch)
+        d.score(stream=stream, batch=batch)
+
+    def time_forward(batch, n):
+        forward(batch)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            forward(batch)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    n_sec = max(3, min(10, args.steps))
+    plain_ms = time_forward(fg, n_sec)
+    probe_ms = time_forward(None, n_sec)
+
     seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
     seg_ms = seg.mean(axis=0)
     breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
@@ -152,6 +175,13 @@ def main():
         "chain_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "breakdown_ms": breakdown, "probe_linear_calls": calls, "input_setup_s": gen_s,
+        # forward (probe linears + scoring) with candidates / the same rows all foreground
+        "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},
+        # bytes the update step moves (P read + write per layer) against rewriting the dense weights
+        # once per candidate state and restoring them (4 x read + write of every probed W)
+        "state_transition_bytes": {
+            "bank_update": int(sum(2 * l.m * w.r * 4 * len(w.dir_seed) for l in w.layers)),
+            "dense_rewrite": int(sum(4 * 2 * l.m * l.n * 2 for l in w.layers))},
     }
     if not args.no_cpu_baseline:
         base, _, _ = _cpu_baseline(w)

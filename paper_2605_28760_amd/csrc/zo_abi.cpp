@@ -96,10 +96,10 @@ struct ProbePlan {
 };
 
 int side_ksplit(int T, int n) {
-  // about three workgroups (of four 64-row items each) per CU; k-chunks are multiples of 64 and >= 512
+  // about two workgroups (of four 64-row items each) per CU; k-chunks are multiples of 64 and >= 512
   const int groups = ((T + zo::kSideRows - 1) / zo::kSideRows + 3) / 4;
   int ks = 1;
-  while (groups * ks < 768 && ks < 16 && n % (ks * 2 * 64) == 0 && n / (ks * 2) >= 512) ks *= 2;
+  while (groups * ks < 512 && ks < 16 && n % (ks * 2 * 64) == 0 && n / (ks * 2) >= 512) ks *= 2;
   return ks;
 }
 
@@ -122,7 +122,11 @@ ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype d
     p.Ph = c.take((size_t)m * p.Rp * 2);
     p.Vbt = c.take((size_t)p.Rp * n * 2);
     p.Aside = c.take((size_t)T * NC * 2);
-    p.partial = c.take(p.ksplit > 1 ? (size_t)p.ksplit * T * NC * 4 : 0);
+    // k-split partial sums: ksplit * T rows are needed, which shrinks again once T alone fills the
+    // chip; reserve a bound that only grows with T (ksplit <= 16 and ksplit * T < 1024 * 256), so a
+    // workspace sized for a large batch also serves every smaller one
+    const size_t partial_rows = (size_t)T * 16 < 262144 ? (size_t)T * 16 : 262144;
+    p.partial = c.take(partial_rows * NC * 4);
   } else {
     p.Uf = c.take((size_t)K * m * r * 4);
     p.Vf = c.take((size_t)K * n * r * 4);
