@@ -27,7 +27,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # Bytes per launch of the dominant kernel that crossed the L2 <-> fabric boundary, from the rocprofv3
 # --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/hbm_bytes_bench_c3.txt (FETCH_SIZE scaled by
 # the factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"c3": 1.977e10}
+MEASURED_TRAFFIC_BYTES = {"c3": 1.241e10}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):
