@@ -82,7 +82,9 @@ def main():
     stream = torch.cuda.current_stream()
     T = w.T
     vocab, hid = w.head.shape
-    col0 = np.arange(d.batch.K, dtype=np.int32) * w.r
+    # as many directions as the bank has blocks for (c4, c5 probe more directions per step than their banks hold)
+    n_upd = min(d.batch.K, int(w.layers[0].R_used) // w.r)
+    col0 = np.arange(n_upd, dtype=np.int32) * w.r
     n_layers = len(d.layers)
     names = [l.name for l in d.layers] + ["score", "estimate", "bank_update"]
 
@@ -98,8 +100,9 @@ def main():
         mark(n_layers + 1)
         d.estimate(stream=stream)
         mark(n_layers + 2)
-        for i in range(n_layers):
-            d.bank_update(i, 1e-7, col0, 0, stream=stream)
+        if n_upd > 0:
+            for i in range(n_layers):
+                d.bank_update(i, 1e-7, col0, 0, stream=stream)
         mark(n_layers + 3)
 
     if args.calibrate_copy:
@@ -180,7 +183,7 @@ def main():
         # bytes the update step moves (P read + write per layer) against rewriting the dense weights
         # once per candidate state and restoring them (4 x read + write of every probed W)
         "state_transition_bytes": {
-            "bank_update": int(sum(2 * l.m * w.r * 4 * len(w.dir_seed) for l in w.layers)),
+            "bank_update": int(sum(2 * l.m * w.r * 4 * n_upd for l in w.layers)),
             "dense_rewrite": int(sum(4 * 2 * l.m * l.n * 2 for l in w.layers))},
     }
     if not args.no_cpu_baseline:

@@ -103,9 +103,10 @@ class DeviceWorkload:
                        self.cand_loss, self.proj_grad, stream)
 
     def bank_update(self, i, lr, col0, append=0, dir_weight=None, stream=None):
+        """Updates the blocks of the first len(col0) directions."""
         l = self.layers[i]
         col0 = np.ascontiguousarray(col0, np.int32)
-        zb.zo_bank_update(l.bank, l.m, l.n, self.w.r, self.batch.K, self.batch.dir_seed, l.tensor_id,
+        zb.zo_bank_update(l.bank, l.m, l.n, self.w.r, len(col0), self.batch.dir_seed, l.tensor_id,
                           self.proj_grad, float(lr), dir_weight, col0, append, _dt(self.dtype), stream)
 
     # -- one pass of the whole path --------------------------------------------------------
