@@ -146,6 +146,27 @@ def main():
     plain_ms = time_forward(fg, n_sec)
     probe_ms = time_forward(None, n_sec)
 
+    # Secondary: scoring when only the last 16 tokens of every sequence carry a target (answer tokens):
+    # the head multiplies only those rows.
+    def time_score(n):
+        d.score(stream=stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n):
+            d.score(stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+    all_targets = d.targets.clone()
+    tail = np.full(T, -1, np.int32)
+    for s_ in range(len(w.seq_cand)):
+        lo = max(int(w.cu_seqlens[s_]), int(w.cu_seqlens[s_ + 1]) - 16)
+        tail[lo:w.cu_seqlens[s_ + 1]] = w.targets[lo:w.cu_seqlens[s_ + 1]]
+    d.targets.copy_(torch.from_numpy(tail))
+    active_ms = time_score(n_sec)
+    d.targets.copy_(all_targets)
+    torch.cuda.synchronize()
+
     seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
     seg_ms = seg.mean(axis=0)
     breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
@@ -179,6 +200,7 @@ def main():
         "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "breakdown_ms": breakdown, "probe_linear_calls": calls, "input_setup_s": gen_s,
         # forward (probe linears + scoring) with candidates / the same rows all foreground
+        "active_token_scoring": {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms},
         "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},
         # bytes the update step moves (P read + write per layer) against rewriting the dense weights
         # once per candidate state and restoring them (4 x read + write of every probed W)

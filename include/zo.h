@@ -182,7 +182,10 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx,
  *   targets int32 [T] in [-inf, vocab)
  *   tok_nll fp32 [T] (nullable), seq_nll fp32 [S], cand_sum fp32 [C], cand_cnt int32 [C]
  * The head carries no side state.  Foreground sequences get seq_nll but
- * contribute to no candidate.
+ * contribute to no candidate.  With ZO_BF16 only the rows with a target are
+ * multiplied (active-token scoring): the cost of a call follows the number
+ * of scored tokens, not T (when H spans less than 2 GiB; a larger H is
+ * multiplied whole, with the same results).
  */
 size_t zo_score_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t vocab, int32_t d,
                                 zo_dtype dtype);

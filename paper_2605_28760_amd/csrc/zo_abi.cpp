@@ -138,7 +138,7 @@ ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype d
 
 struct ScorePlan {
   int n_vt = 0;
-  size_t part_max, part_sum, tgt_logit, tok_nll, seq_cnt, total = 0;
+  size_t part_max, part_sum, tgt_logit, tok_nll, seq_cnt, rows, pos, n_rows, total = 0;
 };
 
 ScorePlan plan_score(int T, int S, int vocab, zo_dtype dt) {
@@ -150,6 +150,9 @@ ScorePlan plan_score(int T, int S, int vocab, zo_dtype dt) {
   p.tgt_logit = c.take((size_t)T * 4);
   p.tok_nll = c.take((size_t)T * 4);
   p.seq_cnt = c.take((size_t)S * 4);
+  p.rows = c.take((size_t)T * 4);     // list of scored tokens
+  p.pos = c.take((size_t)T * 4);      // position of a token in that list
+  p.n_rows = c.take(16);
   p.total = c.off;
   return p;
 }
@@ -337,12 +340,23 @@ int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh, const void* 
   float* part_max = (float*)(ws + plan.part_max);
   float* part_sum = (float*)(ws + plan.part_sum);
   float* tgt = (float*)(ws + plan.tgt_logit);
+  const int32_t* pos = nullptr;
   if (T > 0) {
     if (dtype == ZO_BF16) {
       zo::HeadScoreArgs a;
       a.H = (const uint16_t*)H; a.ldh = ldh; a.Wh = (const uint16_t*)W_head; a.ldw = ldw;
       a.T = T; a.vocab = vocab; a.d = d; a.targets = targets;
       a.part_max = part_max; a.part_sum = part_sum; a.tgt_logit = tgt;
+      a.rows = nullptr; a.n_rows = nullptr;
+      // Only tokens with a target need logits: the head multiplies the rows of a device-built list of
+      // them.  The list addresses H through one 2 GiB buffer window; a larger H is multiplied whole.
+      if (((int64_t)(T - 1) * ldh + d) * 2 < ((int64_t)1 << 31)) {
+        int32_t* rows = (int32_t*)(ws + plan.rows);
+        ZO_HIP(zo::launch_active_rows(targets, T, rows, (int32_t*)(ws + plan.pos), (int32_t*)(ws + plan.n_rows), st),
+               "scored-token list");
+        a.rows = rows; a.n_rows = (const int32_t*)(ws + plan.n_rows);
+        pos = (const int32_t*)(ws + plan.pos);
+      }
       ZO_HIP(zo::launch_head_score_bf16(a, st), "head scoring");
     } else {
       zo::HeadScoreF32Args a;
@@ -354,7 +368,7 @@ int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh, const void* 
   }
   zo::ScoreCombineArgs c;
   c.T = T; c.S = S; c.C = C; c.n_vt = plan.n_vt;
-  c.part_max = part_max; c.part_sum = part_sum; c.tgt_logit = tgt; c.targets = targets;
+  c.part_max = part_max; c.part_sum = part_sum; c.tgt_logit = tgt; c.targets = targets; c.pos = pos;
   c.cu = batch->cu_seqlens; c.seq_cand = batch->seq_cand;
   c.tok_nll = tok_nll ? tok_nll : (float*)(ws + plan.tok_nll);
   c.seq_nll = seq_nll; c.seq_cnt = (int32_t*)(ws + plan.seq_cnt);

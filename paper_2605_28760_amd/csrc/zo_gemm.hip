@@ -91,24 +91,34 @@ struct OperandStream {
   uint32_t offA[kLPW], offB[kLPW];
 };
 
+// Rows of B that a lane's kLPW loads of a tile cover, when B's rows are gathered through a list
+// (b_rows[j] = row of B behind position j; positions past n_b - 1 repeat the last one).
+__device__ __forceinline__ void gather_rows(int (&idx)[kLPW], const int32_t* b_rows, int n_b, int tile_n0, int wave,
+                                            int lane) {
+#pragma unroll
+  for (int j = 0; j < kLPW; ++j) idx[j] = b_rows[min(tile_n0 + (wave * kLPW + j) * 8 + (lane >> 3), n_b - 1)];
+}
+
+// B_rows_total: rows of the matrix B (only used with a gather list: the whole matrix is the buffer then).
+template <bool kGather>
 __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
                                              const bf16_t* B, int64_t ldb, int N, int tile_n0, int K, int wave,
-                                             int lane) {
+                                             int lane, const int (&idx)[kLPW], int B_rows_total) {
 #pragma unroll
   for (int j = 0; j < kLPW; ++j) {
     const int row = (wave * kLPW + j) * 8 + (lane >> 3);
     const int lch = (lane & 7) ^ ((row >> 1) & 7);
     const int ra = min(tile_m0 + row, M - 1) - tile_m0;
-    const int rbn = min(tile_n0 + row, N - 1) - tile_n0;
-    // 24-bit multiply: a tile has 256 rows and the launchers reject row pitches of 16 MiB or more
+    const int rbn = kGather ? idx[j] : min(tile_n0 + row, N - 1) - tile_n0;
+    // 24-bit multiply: fewer than 2^24 rows, and the launchers reject row pitches of 16 MiB or more
     o.offA[j] = __umul24((uint32_t)ra, (uint32_t)lda * 2u) + lch * 16;
     o.offB[j] = __umul24((uint32_t)rbn, (uint32_t)ldb * 2u) + lch * 16;
   }
   const int64_t bytesA = ((int64_t)(M - tile_m0 - 1) * lda + K) * 2;
-  const int64_t bytesB = ((int64_t)(N - tile_n0 - 1) * ldb + K) * 2;
+  const int64_t bytesB = kGather ? ((int64_t)(B_rows_total - 1) * ldb + K) * 2 : ((int64_t)(N - tile_n0 - 1) * ldb + K) * 2;
   o.rA = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (int64_t)tile_m0 * lda), 0,
                                            (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
-  o.rB = __builtin_amdgcn_make_buffer_rsrc((void*)(B + (int64_t)tile_n0 * ldb), 0,
+  o.rB = __builtin_amdgcn_make_buffer_rsrc((void*)(kGather ? B : B + (int64_t)tile_n0 * ldb), 0,
                                            (int)min(bytesB, (int64_t)0x7FFFFFFF), 0x00020000);
 }
 
@@ -131,10 +141,14 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
 // landed (so its first fragments can be fetched under the second k-step).  The load cursor
 // runs ahead of the compute cursor across output-tile boundaries; past the workgroup's
 // last tile it stays on the final K tile (those loads refill stages nobody reads again).
-template <class Pre, class Post>
+//
+// With kGather the N rows of the B operand are rows b_rows[0..N-1] of a matrix of B_rows_total rows
+// (smaller than 2 GiB); the row list of a tile is fetched one tile ahead of the load cursor.
+template <bool kGather, class Pre, class Post>
 __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
-                                                int n_tm, int n_tn, char* lds, Pre pre, Post post) {
+                                                int n_tm, int n_tn, char* lds, Pre pre, Post post,
+                                                const int32_t* __restrict__ b_rows = nullptr, int B_rows_total = 0) {
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -166,10 +180,17 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   // load cursor
   OperandStream ld;
   int ld_L = L, ld_kt = 0;
+  int idx_next[kLPW] = {};   // gather: B rows of the tile after the cursor's
   {
     int tm, tn;
     tile_at(ld_L, n_tm, n_tn, tm, tn);
-    setup_stream(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane);
+    int idx[kLPW] = {};
+    if (kGather) gather_rows(idx, b_rows, N, tn * BN, wave, lane);
+    setup_stream<kGather>(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane, idx, B_rows_total);
+    if (kGather) {
+      tile_at(min(ld_L + stride, L_end - 1), n_tm, n_tn, tm, tn);
+      gather_rows(idx_next, b_rows, N, tn * BN, wave, lane);
+    }
   }
   // load i (0..7) of the cursor's K tile: i < 4 -> A chunk i, else B chunk i - 4
   auto issue_range = [&](int stage, int first, int count) {
@@ -191,7 +212,11 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
       ld_kt = 0;
       int tm, tn;
       tile_at(ld_L, n_tm, n_tn, tm, tn);
-      setup_stream(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane);
+      setup_stream<kGather>(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane, idx_next, B_rows_total);
+      if (kGather) {
+        tile_at(min(ld_L + stride, L_end - 1), n_tm, n_tn, tm, tn);
+        gather_rows(idx_next, b_rows, N, tn * BN, wave, lane);
+      }
     }
   };
 
@@ -428,7 +453,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
     }
   };
 
-  persistent_gemm(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
+  persistent_gemm<false>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
 }
 
 template <bool kSide, bool kOutBf16, bool kBias>
@@ -464,8 +489,14 @@ hipError_t launch_probe_gemm_bf16(const ProbeGemmArgs& a, hipStream_t st) {
 // ---------------------------------------------------------------------------------------
 int head_vocab_tiles_bf16(int vocab) { return (vocab + BM - 1) / BM; }
 
-__global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int n_tm, int n_tn) {
+// kGather: only the scored tokens (rows p.rows[0 .. *p.n_rows - 1] of H) are multiplied; token tiles
+// and the partial outputs then run over positions in that list.
+template <bool kGather>
+__global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int n_tm) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int n_tok = kGather ? __builtin_amdgcn_readfirstlane(*p.n_rows) : p.T;   // tokens to score
+  if (n_tok == 0) return;
+  const int n_tn = (n_tok + BN - 1) / BN;
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
@@ -484,7 +515,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       const int tl = wn * 64 + cb * 16 + r16;   // token within the tile
-      const int t = tile_t0 + tl;
+      const int t = tile_t0 + tl;               // its position (in the list of scored tokens, or its row)
       float mx = -INFINITY;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
@@ -506,8 +537,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
       sum += __shfl_xor(sum, 32);
       if (g == 0) { s_max[wm * BN + tl] = mx; s_sum[wm * BN + tl] = sum; }
       // target logit: exactly one lane of the whole grid holds it
-      if (t < p.T) {
-        const int loc = p.targets[t] - vbase;
+      if (t < n_tok) {
+        const int loc = p.targets[kGather ? p.rows[t] : t] - vbase;
         if (loc >= 0 && loc < 128 && ((loc >> 2) & 3) == g) {
           const int sel = (loc >> 4) * 4 + (loc & 3);
           float z = 0.0f;
@@ -524,7 +555,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
     block_barrier();   // (not __syncthreads: the operand loads of the next tile stay in flight)
     {
       const int t = tile_t0 + tid_t;
-      if (tid_t < BN && t < p.T) {
+      if (tid_t < BN && t < n_tok) {
         const float m0 = s_max[tid_t], m1 = s_max[BN + tid_t];
         const float Mx = fmaxf(m0, m1);
         const float mref = (Mx == -INFINITY) ? 0.0f : Mx;
@@ -538,20 +569,26 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
     block_barrier();   // the exchange buffers are free again for the next tile
   };
 
-  persistent_gemm(p.Wh, p.ldw, p.vocab, p.H, p.ldh, p.T, p.d, n_tm, n_tn, lds, no_side, epilogue);
+  persistent_gemm<kGather>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, lds, no_side, epilogue, p.rows, p.T);
+}
+
+template <bool kGather>
+static hipError_t launch_head_variant(const HeadScoreArgs& a, hipStream_t st) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)k_head_score<kGather>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  // the grid is sized for every token being scored; with fewer, the surplus workgroups find no tile
+  const int n_tm = (a.vocab + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
+  hipLaunchKernelGGL(k_head_score<kGather>, dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds, st, a, n_tm);
+  return hipGetLastError();
 }
 
 hipError_t launch_head_score_bf16(const HeadScoreArgs& a, hipStream_t st) {
   if (a.T == 0) return hipSuccess;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_head_score, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
-  const int n_tm = (a.vocab + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL(k_head_score, dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds, st, a, n_tm, n_tn);
-  return hipGetLastError();
+  return a.rows ? launch_head_variant<true>(a, st) : launch_head_variant<false>(a, st);
 }
 
 }  // namespace zo

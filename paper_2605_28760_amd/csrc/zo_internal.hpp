@@ -99,6 +99,9 @@ struct HeadScoreArgs {
   float* part_max;                  // [n_vt][T]
   float* part_sum;                  // [n_vt][T]
   float* tgt_logit;                 // [T]
+  // scored rows only (both null: every row of H is multiplied).  rows[j] = row of H of the j-th scored
+  // token, *n_rows = their number; the partial outputs are then indexed by j instead of the row
+  const int32_t* rows; const int32_t* n_rows;
 };
 int head_vocab_tiles_bf16(int vocab);
 hipError_t launch_head_score_bf16(const HeadScoreArgs& a, hipStream_t st);
@@ -133,6 +136,7 @@ struct ScoreCombineArgs {
   int T, S, C, n_vt;
   const float* part_max; const float* part_sum; const float* tgt_logit;
   const int32_t* targets;
+  const int32_t* pos;  // [T] index of a scored token in the partial arrays (null: the token's own row)
   const int32_t* cu; const int32_t* seq_cand;
   float* tok_nll;      // [T] (workspace when the caller passes none)
   float* seq_nll;      // [S]
@@ -141,6 +145,8 @@ struct ScoreCombineArgs {
   int32_t* cand_cnt;   // [C]
 };
 hipError_t launch_score_combine(const ScoreCombineArgs& a, hipStream_t st);
+// rows[j] = j-th token with targets >= 0 (ascending), pos[t] = number of such tokens before t, *n_rows = their count
+hipError_t launch_active_rows(const int32_t* targets, int T, int32_t* rows, int32_t* pos, int32_t* n_rows, hipStream_t st);
 hipError_t launch_estimate(const BatchDev& b, const float* cand_sum, const int32_t* cand_cnt, float eps,
                            int reduction, float* cand_loss, float* proj_grad, hipStream_t st);
 struct BankUpdateArgs {

@@ -17,10 +17,11 @@ __global__ __launch_bounds__(256) void k_tok_nll(ScoreCombineArgs a) {
   const int tl = threadIdx.x & 31, j0 = threadIdx.x >> 5;
   const int t = blockIdx.x * 32 + tl;
   float M = -INFINITY, S = 0.0f;
-  if (t < a.T) {
+  const int at = (t < a.T && a.pos) ? a.pos[t] : t;   // where this token's partials are
+  if (t < a.T && a.targets[t] >= 0) {
     for (int j = j0; j < a.n_vt; j += 8) {
-      const float m = a.part_max[(int64_t)j * a.T + t];
-      const float s = a.part_sum[(int64_t)j * a.T + t];
+      const float m = a.part_max[(int64_t)j * a.T + at];
+      const float s = a.part_sum[(int64_t)j * a.T + at];
       const float Mn = fmaxf(M, m);
       if (Mn > -INFINITY) S = S * expf(M - Mn) + s * expf(m - Mn);
       M = Mn;
@@ -38,7 +39,7 @@ __global__ __launch_bounds__(256) void k_tok_nll(ScoreCombineArgs a) {
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       if (s_m[j][tl] > -INFINITY) Sx += s_s[j][tl] * expf(s_m[j][tl] - Mx);
-    a.tok_nll[t] = (Mx + logf(Sx)) - a.tgt_logit[t];
+    a.tok_nll[t] = (Mx + logf(Sx)) - a.tgt_logit[at];
   }
 }
 
@@ -87,6 +88,46 @@ __global__ __launch_bounds__(64) void k_cand_sum(ScoreCombineArgs a) {
     }
   }
   if (lane == 0) { a.cand_sum[c] = sum; a.cand_cnt[c] = cnt; }
+}
+
+// The scored tokens (Sec. 3.3: only active tokens need logits), in ascending order.  One
+// workgroup of 16 waves; wave w owns a contiguous range of tokens and walks it 64 at a time
+// (coalesced reads, ballot + popcount), first counting, then, after a scan over the 16 wave
+// totals, writing the list and every token's position in it.
+__global__ __launch_bounds__(1024) void k_active_rows(const int32_t* targets, int T, int32_t* rows, int32_t* pos,
+                                                      int32_t* n_rows) {
+  __shared__ int s_tot[16];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int per_wave = ((T + 15) / 16 + 63) / 64 * 64;
+  const int lo = min(wave * per_wave, T), hi = min(lo + per_wave, T);
+  int cnt = 0;
+  for (int t0 = lo; t0 < hi; t0 += 64) {
+    const int t = t0 + lane;
+    cnt += __popcll(__ballot(t < hi && targets[t] >= 0));
+  }
+  if (lane == 0) s_tot[wave] = cnt;
+  __syncthreads();
+  int base = 0, total = 0;
+  for (int w = 0; w < 16; ++w) {
+    if (w < wave) base += s_tot[w];
+    total += s_tot[w];
+  }
+  for (int t0 = lo; t0 < hi; t0 += 64) {
+    const int t = t0 + lane;
+    const bool on = t < hi && targets[t] >= 0;
+    const uint64_t m = __ballot(on);
+    const int before = __popcll(m & ((1ull << lane) - 1ull));
+    if (t < hi) pos[t] = base + before;
+    if (on) rows[base + before] = t;
+    base += __popcll(m);
+  }
+  if (threadIdx.x == 0) *n_rows = total;
+}
+
+hipError_t launch_active_rows(const int32_t* targets, int T, int32_t* rows, int32_t* pos, int32_t* n_rows,
+                              hipStream_t st) {
+  hipLaunchKernelGGL(k_active_rows, dim3(1), dim3(1024), 0, st, targets, T, rows, pos, n_rows);
+  return hipGetLastError();
 }
 
 hipError_t launch_score_combine(const ScoreCombineArgs& a, hipStream_t st) {

@@ -70,7 +70,8 @@ def _check_scoring(w, d, rows):
     seq = to_np(d.seq_nll).astype(np.float64)
     C = len(w.cand_dir)
     cand_want = np.array([seq[w.seq_cand == c].sum() for c in range(C)])
-    cnt_want = np.array([np.diff(cu)[w.seq_cand == c].sum() for c in range(C)])
+    scored = np.array([(w.targets[cu[s]:cu[s + 1]] >= 0).sum() for s in range(len(w.seq_cand))])
+    cnt_want = np.array([scored[w.seq_cand == c].sum() for c in range(C)])
     assert_close(to_np(d.cand_sum), cand_want, 1e-5, "cand_sum = sum of its seq_nll", atol=1e-2)
     assert np.array_equal(to_np(d.cand_cnt), cnt_want)
     loss, grad = zo.estimate(oracle_batch(w), to_np(d.cand_sum), to_np(d.cand_cnt), w.eps, w.reduction)
@@ -130,3 +131,24 @@ def test_config5_mixed_full_size_with_foreground_identity():
     for a, y in zip(mixed[:-1], allfg.Y):
         assert torch.equal(a, y[fg_rows])                 # foreground rows: bit-identical to the plain base GEMM
     assert torch.equal(mixed[-1], allfg.tok_nll[fg_rows])
+
+
+def test_config3_active_token_scoring_full_size():
+    """c3 with only the last 16 tokens of every sequence scored: the head multiplies 2048 of the 16384
+    rows; sampled scored rows against the oracle, unscored rows exactly zero, sums as properties."""
+    w = wl.opt_scoring()
+    cu = w.cu_seqlens
+    tg = np.full(w.T, -1, np.int32)
+    for s in range(len(cu) - 1):
+        tg[cu[s + 1] - 16:cu[s + 1]] = w.targets[cu[s + 1] - 16:cu[s + 1]]
+    w.targets = tg
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False)
+    torch.cuda.synchronize()
+    on = np.nonzero(tg >= 0)[0]
+    rng = np.random.default_rng(3)
+    rows = np.sort(np.concatenate([on[:2], on[-2:], rng.choice(on, size=12, replace=False)]))
+    _check_scoring(w, d, rows)
+    tok = to_np(d.tok_nll)
+    assert np.all(tok[tg < 0] == 0) and np.all(tok[on] > 0)
+    assert np.array_equal(to_np(d.cand_cnt), np.array([1024, 1024]))

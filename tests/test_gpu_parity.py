@@ -309,3 +309,49 @@ def test_no_candidates_and_empty_batches():
     assert np.array_equal(to_np(d3.cand_cnt), cc) and to_np(d3.seq_nll)[1] == 0
     assert_close(to_np(d3.tok_nll), tok, 1e-4, "tok_nll with unscored rows", atol=1e-4)
     assert np.all(to_np(d3.tok_nll)[::3] == 0)
+
+
+def _score_with_targets(d, w, targets):
+    d.targets.copy_(torch.from_numpy(np.ascontiguousarray(targets, np.int32)))
+    d.score(); _sync()
+    return [to_np(x).copy() for x in (d.tok_nll, d.seq_nll, d.cand_sum, d.cand_cnt)]
+
+
+def test_scoring_only_active_tokens():
+    """Only tokens with a target get logits (Sec. 3.3, active-token scoring): the head runs over a
+    device-built list of them.  Every pattern must match the oracle, and a scored token's NLL must not
+    depend on which other tokens are scored."""
+    w = wl.opt_scoring(hidden=128, ffn=256, vocab=777, n_ex=5, seq_len=150, r=8, R=16)   # T = 1500: 6 token tiles
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False); _sync()
+    H = to_np(d.Y[-1])
+    full_tok = to_np(d.tok_nll).copy()
+    ob = oracle_batch(w)
+    rng = np.random.default_rng(5)
+    T, cu = w.T, w.cu_seqlens
+    patterns = {}
+    last16 = np.full(T, -1, np.int32)
+    for s in range(len(cu) - 1):
+        last16[cu[s + 1] - 16:cu[s + 1]] = w.targets[cu[s + 1] - 16:cu[s + 1]]
+    patterns["last 16 of every sequence"] = last16
+    patterns["random tenth"] = np.where(rng.random(T) < 0.1, w.targets, -1).astype(np.int32)
+    patterns["none"] = np.full(T, -1, np.int32)
+    one = np.full(T, -1, np.int32); one[T // 2] = w.targets[T // 2]
+    patterns["a single token"] = one
+    for n_on in (256, 257, 511):
+        t = np.full(T, -1, np.int32)
+        keep = np.sort(rng.choice(T, size=n_on, replace=False))
+        t[keep] = w.targets[keep]
+        patterns["%d tokens" % n_on] = t
+    first_seq_off = w.targets.copy(); first_seq_off[cu[0]:cu[1]] = -1
+    patterns["one sequence unscored"] = first_seq_off
+    for name, tg in patterns.items():
+        tok, seq, cs, cc = _score_with_targets(d, w, tg)
+        otok, oseq, ocs, occ = zo.score(ob, H, w.head, tg)
+        assert np.array_equal(cc, occ), name
+        assert_close(tok, otok, 1e-4, "tok_nll, " + name, atol=1e-3)
+        assert_close(seq, oseq, 1e-4, "seq_nll, " + name, atol=1e-3)
+        assert_close(cs, ocs, 1e-4, "cand_sum, " + name, atol=1e-2)
+        on = tg >= 0
+        assert np.all(tok[~on] == 0)
+        assert np.array_equal(tok[on], full_tok[on]), name   # same bits as when every token is scored
