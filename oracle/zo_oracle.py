@@ -49,12 +49,16 @@ class Batch:
     cand_dir   [C]    direction index of each candidate, -1 = centre
     cand_sign  [C]    +1, -1 or 0
     dir_seed   [K]    64-bit seed of each direction
+    dir_seed_v [K]    optional separate seed of each direction's V (None: V uses
+                      dir_seed too).  Sec. 3.2 reuses one V_k over an interval of
+                      steps while U_t is drawn afresh: two seeds express that.
     """
     cu_seqlens: np.ndarray
     seq_cand: np.ndarray
     cand_dir: np.ndarray
     cand_sign: np.ndarray
     dir_seed: np.ndarray
+    dir_seed_v: Optional[np.ndarray] = None
 
     @property
     def n_tokens(self):
@@ -94,9 +98,10 @@ def batch_indices(batch: Batch):
 
 def direction_factors(batch: Batch, k, m, n, r, tensor_id, factor_dtype):
     """U_k [m, r] and V_k [n, r] of direction k for the layer `tensor_id`."""
-    seed = int(batch.dir_seed[k])
-    U = _px.factor_matrix(seed, _px.u_tensor_id(tensor_id), m, r, factor_dtype)
-    V = _px.factor_matrix(seed, _px.v_tensor_id(tensor_id), n, r, factor_dtype)
+    seed_u = int(batch.dir_seed[k])
+    seed_v = seed_u if batch.dir_seed_v is None else int(batch.dir_seed_v[k])
+    U = _px.factor_matrix(seed_u, _px.u_tensor_id(tensor_id), m, r, factor_dtype)
+    V = _px.factor_matrix(seed_v, _px.v_tensor_id(tensor_id), n, r, factor_dtype)
     return U, V
 
 
