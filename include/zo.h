@@ -71,6 +71,9 @@ typedef enum zo_dtype { ZO_F32 = 0, ZO_BF16 = 1 } zo_dtype;
  *   dir_seed   [K]    64-bit seed of each direction; U uses the stream
  *                     (seed, tensor_id & ~1), V the stream (seed, tensor_id | 1)
  *   host_*            optional host copies used only for validation; may be NULL
+ *   dir_seed_v [K]    optional (NULL: V is drawn from dir_seed too): separate seeds
+ *                     for V, so that one V_k can be reused over an interval of steps
+ *                     while U_t is drawn afresh (Sec. 3.2)
  */
 typedef struct zo_batch {
   int32_t n_tokens;
@@ -85,6 +88,7 @@ typedef struct zo_batch {
   const int32_t* host_cu_seqlens;
   const int32_t* host_seq_cand;
   const int32_t* host_cand_dir;
+  const uint64_t* dir_seed_v;
 } zo_batch;
 
 /*
@@ -215,8 +219,9 @@ int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t*
  * beta_k = -lr * proj_grad[k] * dir_weight[k] read on the device:
  *   append = 0:  P[:, col0[k] : col0[k]+r] += beta_k U_k
  *   append = 1:  P[:, block] = beta_k U_k;  Vb[:, block] = V_k
- * U_k, V_k are regenerated from dir_seed[k] (factor_dtype as in
- * zo_probe_linear's in_dtype).  dir_weight NULL means 1/n_dirs.
+ * U_k is regenerated from dir_seed[k], V_k from dir_seed_v[k] (dir_seed[k]
+ * when dir_seed_v is NULL); factor_dtype as in zo_probe_linear's in_dtype.
+ * dir_weight NULL means 1/n_dirs.
  *   host_col0  HOST int32 [n_dirs]: first column of each direction's block;
  *              blocks must not overlap each other.
  * On append, bank->R_used (a host field) is raised to max(col0[k] + r).
@@ -224,10 +229,56 @@ int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t*
  * W_0 is not an argument: the base is never touched.
  */
 int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs,
-                       const uint64_t* dir_seed, uint32_t tensor_id,
+                       const uint64_t* dir_seed, const uint64_t* dir_seed_v, uint32_t tensor_id,
                        const float* proj_grad, float lr, const float* dir_weight,
                        const int32_t* host_col0, int32_t append, zo_dtype factor_dtype,
                        void* stream);
+
+/*
+ * Device-resident schedule of the multi-step loop (Sec. 3.2: V_k reused over an
+ * interval of nu steps, U_t fresh every step, one bank block per interval; with
+ * B blocks the reuse covers nu * B steps before the bank must be folded or the
+ * run stops).  The state lives in device memory so that a captured HIP graph of
+ * one step can be replayed without any host update.
+ *
+ * zo_schedule_step reads t = sched->next_step and writes, for step t with
+ * K = n_dirs directions:
+ *     interval = t / nu,  block = interval % n_blocks,  append = (t % nu == 0)
+ *     dir_seed[j]   = base_u + t * K + j          (mod 2^64)
+ *     dir_seed_v[j] = base_v + interval * K + j   (mod 2^64)
+ * then sched->step = t and sched->next_step = t + 1.  The numbering of seeds
+ * and blocks is this library's own; the paper fixes none.  Wrapping onto a
+ * block that still holds an earlier interval reopens it (that interval's
+ * update is discarded): the caller stops or folds after nu * n_blocks steps.
+ *   sched       DEVICE zo_sched; set next_step (usually 0) before the first call
+ *   dir_seed, dir_seed_v  DEVICE uint64 [n_dirs], overwritten
+ */
+typedef struct zo_sched {
+  int64_t next_step;
+  int64_t step;
+  int32_t interval;
+  int32_t block;
+  int32_t append;
+  int32_t reserved;
+} zo_sched;
+
+int32_t zo_schedule_step(zo_sched* sched, int32_t nu, int32_t n_blocks, int32_t n_dirs,
+                         uint64_t base_u, uint64_t base_v,
+                         uint64_t* dir_seed, uint64_t* dir_seed_v, void* stream);
+
+/*
+ * zo_bank_update driven by the device-resident schedule: direction k updates
+ * columns [(sched->block * n_dirs + k) * r, +r), opening the block
+ * (P = beta U, Vb = V) when sched->append is set and accumulating otherwise.
+ * The bank must span all blocks from the start: R_used >= n_blocks * n_dirs * r,
+ * unopened blocks zero (ZO_ERR_BANK_FULL / ZO_ERR_SHAPE otherwise); R_used is
+ * not changed.  sched is a DEVICE pointer; everything else as zo_bank_update.
+ */
+int32_t zo_bank_update_scheduled(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs,
+                                 const uint64_t* dir_seed, const uint64_t* dir_seed_v,
+                                 uint32_t tensor_id, const float* proj_grad, float lr,
+                                 const float* dir_weight, const zo_sched* sched, int32_t n_blocks,
+                                 zo_dtype factor_dtype, void* stream);
 
 #ifdef __cplusplus
 }

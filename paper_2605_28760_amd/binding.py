@@ -28,11 +28,17 @@ class zo_batch(C.Structure):
                 ("n_cands", C.c_int32), ("cand_dir", C.c_void_p), ("cand_sign", C.c_void_p),
                 ("n_dirs", C.c_int32), ("dir_seed", C.c_void_p),
                 ("host_cu_seqlens", C.c_void_p), ("host_seq_cand", C.c_void_p),
-                ("host_cand_dir", C.c_void_p)]
+                ("host_cand_dir", C.c_void_p), ("dir_seed_v", C.c_void_p)]
 
 
 class zo_bank(C.Structure):
     _fields_ = [("R_cap", C.c_int32), ("R_used", C.c_int32), ("P", C.c_void_p), ("Vb", C.c_void_p)]
+
+
+class zo_sched(C.Structure):
+    """Layout of the device-resident schedule state (for host-side initialisation and read-back)."""
+    _fields_ = [("next_step", C.c_int64), ("step", C.c_int64), ("interval", C.c_int32), ("block", C.c_int32),
+                ("append", C.c_int32), ("reserved", C.c_int32)]
 
 
 class ZoError(RuntimeError):
@@ -61,8 +67,13 @@ _PROTOS = {
     "zo_estimate": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p,
                                 C.c_void_p, C.c_void_p]),
     "zo_bank_update": (C.c_int32, [C.POINTER(zo_bank), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
-                                   C.c_uint32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_int,
-                                   C.c_void_p]),
+                                   C.c_void_p, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int32,
+                                   C.c_int, C.c_void_p]),
+    "zo_schedule_step": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint64,
+                                     C.c_void_p, C.c_void_p, C.c_void_p]),
+    "zo_bank_update_scheduled": (C.c_int32, [C.POINTER(zo_bank), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p,
+                                             C.c_void_p, C.c_int32, C.c_int, C.c_void_p]),
 }
 EXPORTS = tuple(_PROTOS)
 
@@ -118,7 +129,7 @@ def _stream(stream):
 
 def make_batch(n_tokens, cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed,
                host_cu_seqlens=None, host_seq_cand=None, host_cand_dir=None,
-               n_seqs=None, n_cands=None, n_dirs=None):
+               n_seqs=None, n_cands=None, n_dirs=None, dir_seed_v=None):
     """Fills a zo_batch from device tensors (and optional host numpy mirrors).
     The caller keeps the tensors alive for as long as the struct is used."""
     b = zo_batch()
@@ -129,7 +140,9 @@ def make_batch(n_tokens, cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed,
     b.cu_seqlens, b.seq_cand = _ptr(cu_seqlens), _ptr(seq_cand)
     b.cand_dir, b.cand_sign, b.dir_seed = _ptr(cand_dir), _ptr(cand_sign), _ptr(dir_seed)
     b.host_cu_seqlens, b.host_seq_cand, b.host_cand_dir = _ptr(host_cu_seqlens), _ptr(host_seq_cand), _ptr(host_cand_dir)
-    b._keep = (cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed, host_cu_seqlens, host_seq_cand, host_cand_dir)
+    b.dir_seed_v = _ptr(dir_seed_v)
+    b._keep = (cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed, host_cu_seqlens, host_seq_cand, host_cand_dir,
+               dir_seed_v)
     return b
 
 
@@ -184,6 +197,19 @@ def zo_estimate(batch, cand_sum, cand_cnt, eps, reduction, cand_loss, proj_grad,
 
 
 def zo_bank_update(bank, m, n, r, n_dirs, dir_seed, tensor_id, proj_grad, lr, dir_weight, host_col0, append,
-                   factor_dtype, stream=None):
-    _check(lib().zo_bank_update(C.byref(bank), m, n, r, n_dirs, _ptr(dir_seed), tensor_id, _ptr(proj_grad), lr,
-                                _ptr(dir_weight), _ptr(host_col0), append, factor_dtype, _stream(stream)))
+                   factor_dtype, stream=None, dir_seed_v=None):
+    _check(lib().zo_bank_update(C.byref(bank), m, n, r, n_dirs, _ptr(dir_seed), _ptr(dir_seed_v), tensor_id,
+                                _ptr(proj_grad), lr, _ptr(dir_weight), _ptr(host_col0), append, factor_dtype,
+                                _stream(stream)))
+
+
+def zo_schedule_step(sched, nu, n_blocks, n_dirs, base_u, base_v, dir_seed, dir_seed_v, stream=None):
+    _check(lib().zo_schedule_step(_ptr(sched), nu, n_blocks, n_dirs, base_u, base_v, _ptr(dir_seed),
+                                  _ptr(dir_seed_v), _stream(stream)))
+
+
+def zo_bank_update_scheduled(bank, m, n, r, n_dirs, dir_seed, dir_seed_v, tensor_id, proj_grad, lr, dir_weight,
+                             sched, n_blocks, factor_dtype, stream=None):
+    _check(lib().zo_bank_update_scheduled(C.byref(bank), m, n, r, n_dirs, _ptr(dir_seed), _ptr(dir_seed_v), tensor_id,
+                                          _ptr(proj_grad), lr, _ptr(dir_weight), _ptr(sched), n_blocks, factor_dtype,
+                                          _stream(stream)))

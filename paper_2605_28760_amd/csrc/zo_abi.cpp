@@ -83,6 +83,7 @@ zo::BatchDev to_dev(const zo_batch* b) {
   d.T = b->n_tokens; d.S = b->n_seqs; d.C = b->n_cands; d.K = b->n_dirs;
   d.cu = b->cu_seqlens; d.seq_cand = b->seq_cand; d.cand_dir = b->cand_dir; d.cand_sign = b->cand_sign;
   d.seed = b->dir_seed;
+  d.seed_v = b->dir_seed_v;
   return d;
 }
 
@@ -388,15 +389,23 @@ int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t*
   return ZO_OK;
 }
 
-int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, const uint64_t* dir_seed,
-                       uint32_t tensor_id, const float* proj_grad, float lr, const float* dir_weight,
-                       const int32_t* host_col0, int32_t append, zo_dtype factor_dtype, void* stream) {
+namespace {
+int32_t check_bank_update(const zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, zo_dtype factor_dtype) {
   if (!bank) return fail(ZO_ERR_NULL, "bank is NULL");
   if (m < 0 || n < 0 || n_dirs < 0) return fail(ZO_ERR_SHAPE, "m = %d, n = %d, n_dirs = %d", m, n, n_dirs);
   if (r < 1 || r > 64) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, 64]", r);
   if (bank->R_cap < 0 || bank->R_used < 0 || bank->R_used > bank->R_cap)
     return fail(ZO_ERR_SHAPE, "bank R_used = %d, R_cap = %d", bank->R_used, bank->R_cap);
   if (factor_dtype != ZO_F32 && factor_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "factor_dtype %d", (int)factor_dtype);
+  return ZO_OK;
+}
+}  // namespace
+
+int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, const uint64_t* dir_seed,
+                       const uint64_t* dir_seed_v, uint32_t tensor_id, const float* proj_grad, float lr,
+                       const float* dir_weight, const int32_t* host_col0, int32_t append, zo_dtype factor_dtype,
+                       void* stream) {
+  if (int32_t st = check_bank_update(bank, m, n, r, n_dirs, factor_dtype)) return st;
   if (append != 0 && append != 1) return fail(ZO_ERR_UNSUPPORTED, "append = %d", append);
   if (n_dirs == 0) return ZO_OK;
   if (!dir_seed || !proj_grad || !host_col0) return fail(ZO_ERR_NULL, "dir_seed, proj_grad or host_col0 is NULL");
@@ -415,10 +424,45 @@ int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n
   }
   zo::BankUpdateArgs a;
   a.P = bank->P; a.Vb = bank->Vb; a.R_cap = bank->R_cap; a.m = m; a.n = n; a.r = r;
-  a.seed = dir_seed; a.tensor_id = tensor_id; a.proj_grad = proj_grad; a.lr = lr; a.dir_weight = dir_weight;
+  a.seed = dir_seed; a.seed_v = dir_seed_v; a.tensor_id = tensor_id; a.proj_grad = proj_grad; a.lr = lr;
+  a.dir_weight = dir_weight; a.sched = nullptr; a.n_dirs = n_dirs;
   a.default_weight = 1.0f / (float)n_dirs; a.append = append; a.bf16 = factor_dtype == ZO_BF16;
   ZO_HIP(zo::launch_bank_update(a, n_dirs, host_col0, (hipStream_t)stream), "zo_bank_update");
   if (append) bank->R_used = new_used;
+  return ZO_OK;
+}
+
+int32_t zo_schedule_step(zo_sched* sched, int32_t nu, int32_t n_blocks, int32_t n_dirs, uint64_t base_u,
+                         uint64_t base_v, uint64_t* dir_seed, uint64_t* dir_seed_v, void* stream) {
+  static_assert(sizeof(zo_sched) == sizeof(zo::SchedDev), "schedule state layouts differ");
+  if (!sched) return fail(ZO_ERR_NULL, "sched is NULL");
+  if (nu < 1 || n_blocks < 1 || n_dirs < 0) return fail(ZO_ERR_SHAPE, "nu = %d, n_blocks = %d, n_dirs = %d", nu, n_blocks, n_dirs);
+  if (n_dirs > 0 && (!dir_seed || !dir_seed_v)) return fail(ZO_ERR_NULL, "dir_seed or dir_seed_v is NULL");
+  ZO_HIP(zo::launch_schedule_step((zo::SchedDev*)sched, nu, n_blocks, n_dirs, base_u, base_v, dir_seed, dir_seed_v,
+                                  (hipStream_t)stream), "zo_schedule_step");
+  return ZO_OK;
+}
+
+int32_t zo_bank_update_scheduled(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs,
+                                 const uint64_t* dir_seed, const uint64_t* dir_seed_v, uint32_t tensor_id,
+                                 const float* proj_grad, float lr, const float* dir_weight, const zo_sched* sched,
+                                 int32_t n_blocks, zo_dtype factor_dtype, void* stream) {
+  if (int32_t st = check_bank_update(bank, m, n, r, n_dirs, factor_dtype)) return st;
+  if (n_blocks < 1) return fail(ZO_ERR_SHAPE, "n_blocks = %d", n_blocks);
+  if (n_dirs == 0) return ZO_OK;
+  if (!dir_seed || !proj_grad || !sched) return fail(ZO_ERR_NULL, "dir_seed, proj_grad or sched is NULL");
+  if (!bank->P || !bank->Vb) return fail(ZO_ERR_NULL, "bank.P / bank.Vb is NULL");
+  const int64_t cols = (int64_t)n_blocks * n_dirs * r;
+  if (cols > bank->R_cap)
+    return fail(ZO_ERR_BANK_FULL, "%d blocks x %d directions x rank %d = %lld columns exceed R_cap = %d", n_blocks, n_dirs, r, (long long)cols, bank->R_cap);
+  if (cols > bank->R_used)
+    return fail(ZO_ERR_SHAPE, "scheduled updates need R_used >= %lld (all blocks in use from the start), R_used = %d", (long long)cols, bank->R_used);
+  zo::BankUpdateArgs a;
+  a.P = bank->P; a.Vb = bank->Vb; a.R_cap = bank->R_cap; a.m = m; a.n = n; a.r = r;
+  a.seed = dir_seed; a.seed_v = dir_seed_v; a.tensor_id = tensor_id; a.proj_grad = proj_grad; a.lr = lr;
+  a.dir_weight = dir_weight; a.sched = (const zo::SchedDev*)sched; a.n_dirs = n_dirs;
+  a.default_weight = 1.0f / (float)n_dirs; a.append = 0; a.bf16 = factor_dtype == ZO_BF16;
+  ZO_HIP(zo::launch_bank_update(a, n_dirs, nullptr, (hipStream_t)stream), "zo_bank_update_scheduled");
   return ZO_OK;
 }
 

@@ -22,6 +22,7 @@ struct BatchDev {
   const int32_t* cand_dir;
   const float* cand_sign;
   const uint64_t* seed;
+  const uint64_t* seed_v;   // null: V is drawn from `seed` too
 };
 
 // One side-down work item: rows [row0, row0 + nrows) of one sequence.
@@ -149,10 +150,19 @@ hipError_t launch_score_combine(const ScoreCombineArgs& a, hipStream_t st);
 hipError_t launch_active_rows(const int32_t* targets, int T, int32_t* rows, int32_t* pos, int32_t* n_rows, hipStream_t st);
 hipError_t launch_estimate(const BatchDev& b, const float* cand_sum, const int32_t* cand_cnt, float eps,
                            int reduction, float* cand_loss, float* proj_grad, hipStream_t st);
+// Device-resident schedule state (same layout as the zo_sched of the public header).
+struct SchedDev {
+  int64_t next_step, step;
+  int32_t interval, block, append, reserved;
+};
+hipError_t launch_schedule_step(SchedDev* s, int nu, int n_blocks, int K, uint64_t base_u, uint64_t base_v,
+                                uint64_t* seed_u, uint64_t* seed_v, hipStream_t st);
+
 struct BankUpdateArgs {
   float* P; float* Vb; int R_cap;
   int m, n, r;
-  const uint64_t* seed; uint32_t tensor_id;
+  const uint64_t* seed; const uint64_t* seed_v; uint32_t tensor_id;
+  const SchedDev* sched; int n_dirs;   // sched non-null: block and mode come from the device
   const float* proj_grad; float lr; const float* dir_weight; float default_weight;
   int append; int bf16;
 };

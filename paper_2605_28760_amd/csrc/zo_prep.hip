@@ -158,7 +158,7 @@ __global__ void k_image_Vt(BatchDev b, uint32_t tid_v, int n, int r, int RP, bf1
   const int64_t rem = idx - (int64_t)k * per_dir;
   const int j = (int)(rem / n), i = (int)(rem % n);
   float z = 0.0f;
-  if (j < r) z = factor_normal(b.seed[k], tid_v, (uint64_t)i * r + j);
+  if (j < r) z = factor_normal(b.seed_v ? b.seed_v[k] : b.seed[k], tid_v, (uint64_t)i * r + j);
   Vt[idx] = f32_to_bf16(z);
 }
 
@@ -211,7 +211,8 @@ __global__ void k_factors_f32(BatchDev b, uint32_t tid, int rows, int r, float* 
   const int64_t per_dir = (int64_t)rows * r;
   if (idx >= per_dir * b.K) return;
   const int k = (int)(idx / per_dir);
-  out[idx] = factor_normal(b.seed[k], tid, (uint64_t)(idx - (int64_t)k * per_dir));
+  const uint64_t seed = ((tid & 1u) && b.seed_v) ? b.seed_v[k] : b.seed[k];   // odd stream id: V
+  out[idx] = factor_normal(seed, tid, (uint64_t)(idx - (int64_t)k * per_dir));
 }
 
 hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int n, int r,
@@ -220,6 +221,32 @@ hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int 
   const int64_t nu = (int64_t)b.K * m * r, nv = (int64_t)b.K * n * r;
   hipLaunchKernelGGL(k_factors_f32, dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st, b, tensor_id & ~1u, m, r, Uf);
   hipLaunchKernelGGL(k_factors_f32, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st, b, tensor_id | 1u, n, r, Vf);
+  return hipGetLastError();
+}
+
+// ---- device-resident schedule of the multi-step loop (Sec. 3.2) ---------------------------
+__global__ __launch_bounds__(256) void k_schedule_step(SchedDev* s, int nu, int n_blocks, int K, uint64_t base_u,
+                                                       uint64_t base_v, uint64_t* seed_u, uint64_t* seed_v) {
+  const int64_t t = s->next_step;
+  __syncthreads();   // every thread has read the step number before thread 0 advances it
+  const int64_t interval = t / nu;
+  for (int j = threadIdx.x; j < K; j += blockDim.x) {
+    seed_u[j] = base_u + (uint64_t)t * (uint64_t)K + (uint64_t)j;
+    seed_v[j] = base_v + (uint64_t)interval * (uint64_t)K + (uint64_t)j;
+  }
+  if (threadIdx.x == 0) {
+    s->step = t;
+    s->interval = (int32_t)interval;
+    s->block = (int32_t)(interval % n_blocks);
+    s->append = (t % nu == 0) ? 1 : 0;
+    s->reserved = 0;
+    s->next_step = t + 1;
+  }
+}
+
+hipError_t launch_schedule_step(SchedDev* s, int nu, int n_blocks, int K, uint64_t base_u, uint64_t base_v,
+                                uint64_t* seed_u, uint64_t* seed_v, hipStream_t st) {
+  hipLaunchKernelGGL(k_schedule_step, dim3(1), dim3(256), 0, st, s, nu, n_blocks, K, base_u, base_v, seed_u, seed_v);
   return hipGetLastError();
 }
 

@@ -173,35 +173,37 @@ struct BankCols { int32_t first_dir; int32_t n; int32_t col0[kBankBatch]; };
 __global__ void k_bank_update(BankUpdateArgs a, BankCols cols) {
   const int kb = blockIdx.y;
   const int k = cols.first_dir + kb;
-  const int col0 = cols.col0[kb];
+  // block and mode: from the host (by value) or from the device-resident schedule
+  const int col0 = a.sched ? (a.sched->block * a.n_dirs + k) * a.r : cols.col0[kb];
+  const bool append = a.sched ? a.sched->append != 0 : a.append != 0;
+  if (col0 < 0 || col0 + a.r > a.R_cap) return;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const uint64_t seed = a.seed[k];
   if (idx < (int64_t)a.m * a.r) {
     const int i = (int)(idx / a.r), j = (int)(idx % a.r);
     const float w = a.dir_weight ? a.dir_weight[k] : a.default_weight;
     const float beta = -a.lr * a.proj_grad[k] * w;
-    float u = factor_normal(seed, a.tensor_id & ~1u, (uint64_t)idx);
+    float u = factor_normal(a.seed[k], a.tensor_id & ~1u, (uint64_t)idx);
     if (a.bf16) u = bf16_round(u);
     float* dst = a.P + (int64_t)i * a.R_cap + col0 + j;
-    *dst = a.append ? beta * u : fmaf(beta, u, *dst);
+    *dst = append ? beta * u : fmaf(beta, u, *dst);
   }
-  if (a.append && idx < (int64_t)a.n * a.r) {
+  if (append && idx < (int64_t)a.n * a.r) {
     const int i = (int)(idx / a.r), j = (int)(idx % a.r);
-    float v = factor_normal(seed, a.tensor_id | 1u, (uint64_t)idx);
+    float v = factor_normal(a.seed_v ? a.seed_v[k] : a.seed[k], a.tensor_id | 1u, (uint64_t)idx);
     if (a.bf16) v = bf16_round(v);
     a.Vb[(int64_t)i * a.R_cap + col0 + j] = v;
   }
 }
 
 hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st) {
-  const int rows = a.append ? (a.m > a.n ? a.m : a.n) : a.m;
+  const int rows = (a.append || a.sched) ? (a.m > a.n ? a.m : a.n) : a.m;
   const int64_t total = (int64_t)rows * a.r;
   if (total == 0) return hipSuccess;
   for (int first = 0; first < n_dirs; first += kBankBatch) {
     BankCols cols;
     cols.first_dir = first;
     cols.n = n_dirs - first < kBankBatch ? n_dirs - first : kBankBatch;
-    for (int i = 0; i < kBankBatch; ++i) cols.col0[i] = i < cols.n ? col0[first + i] : 0;
+    for (int i = 0; i < kBankBatch; ++i) cols.col0[i] = (col0 && i < cols.n) ? col0[first + i] : 0;
     hipLaunchKernelGGL(k_bank_update, dim3((unsigned)((total + 255) / 256), cols.n), dim3(256), 0, st, a, cols);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -23,7 +23,8 @@ def _tt(dtype):
 class DeviceBatch:
     """Batch arrays on the device plus the zo_batch struct that points at them."""
 
-    def __init__(self, cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed, device, host_mirrors=True):
+    def __init__(self, cu_seqlens, seq_cand, cand_dir, cand_sign, dir_seed, device, host_mirrors=True,
+                 dir_seed_v=None):
         self.host = dict(cu=np.ascontiguousarray(cu_seqlens, np.int32), seq_cand=np.ascontiguousarray(seq_cand, np.int32),
                          cand_dir=np.ascontiguousarray(cand_dir, np.int32))
         self.cu = torch.from_numpy(self.host["cu"]).to(device)
@@ -32,12 +33,14 @@ class DeviceBatch:
         self.cand_sign = torch.from_numpy(np.ascontiguousarray(cand_sign, np.float32)).to(device)
         # torch has no uint64 arithmetic; the seeds travel as the same 64 bits in an int64 tensor
         self.dir_seed = torch.from_numpy(np.ascontiguousarray(dir_seed, np.uint64).view(np.int64)).to(device)
+        self.dir_seed_v = None if dir_seed_v is None else \
+            torch.from_numpy(np.ascontiguousarray(dir_seed_v, np.uint64).view(np.int64)).to(device)
         self.T = int(self.host["cu"][-1])
         self.S, self.C, self.K = len(self.host["seq_cand"]), len(self.host["cand_dir"]), len(dir_seed)
         mir = self.host if host_mirrors else dict(cu=None, seq_cand=None, cand_dir=None)
         self.struct = zb.make_batch(self.T, self.cu, self.seq_cand, self.cand_dir, self.cand_sign, self.dir_seed,
                                     mir["cu"], mir["seq_cand"], mir["cand_dir"],
-                                    n_seqs=self.S, n_cands=self.C, n_dirs=self.K)
+                                    n_seqs=self.S, n_cands=self.C, n_dirs=self.K, dir_seed_v=self.dir_seed_v)
 
 
 class DeviceLayer:
@@ -121,3 +124,82 @@ class DeviceWorkload:
                     if l.bank is not None and l.bank.R_used >= self.w.r * self.batch.K:
                         col0 = np.arange(self.batch.K, dtype=np.int32) * self.w.r
                         self.bank_update(i, lr, col0, 0, stream=stream)
+
+
+class LoopDriver:
+    """The multi-step loop of Sec. 3.2 on one DeviceWorkload: per step, the device-resident schedule
+    draws the seeds (U fresh every step, V once per interval of `nu` steps) and names the bank block,
+    then probe linears, scoring, estimate and the scheduled bank update of every layer follow on one
+    stream.  Nothing in a step depends on the host, so one captured HIP graph replays every step.
+
+    The banks of all layers must hold n_blocks * K * r columns; reset() zeroes them."""
+
+    def __init__(self, d, nu, n_blocks, lr, base_u, base_v):
+        self.d, self.nu, self.n_blocks, self.lr = d, int(nu), int(n_blocks), float(lr)
+        self.base_u, self.base_v = int(base_u), int(base_v)
+        b = d.batch
+        dev = d.device
+        self.sched = torch.zeros(4, dtype=torch.int64, device=dev)          # one zo_sched (32 bytes)
+        self.seed_u = torch.zeros(max(b.K, 1), dtype=torch.int64, device=dev)
+        self.seed_v = torch.zeros(max(b.K, 1), dtype=torch.int64, device=dev)
+        self.batch = DeviceBatch(b.host["cu"], b.host["seq_cand"], b.host["cand_dir"], b.cand_sign.cpu().numpy(),
+                                 np.zeros(b.K, np.uint64), dev, dir_seed_v=np.zeros(b.K, np.uint64))
+        # the batch struct points at the schedule's seed buffers
+        self.batch.dir_seed, self.batch.dir_seed_v = self.seed_u, self.seed_v
+        self.batch.struct = zb.make_batch(b.T, self.batch.cu, self.batch.seq_cand, self.batch.cand_dir,
+                                          self.batch.cand_sign, self.seed_u, b.host["cu"], b.host["seq_cand"],
+                                          b.host["cand_dir"], n_seqs=b.S, n_cands=b.C, n_dirs=b.K,
+                                          dir_seed_v=self.seed_v)
+        need = self.n_blocks * b.K * d.w.r
+        for l in d.layers:
+            if l.bank is None or l.bank.R_cap < need:
+                raise ValueError("layer %s: the loop needs a bank of %d columns" % (l.name, need))
+            l.bank.R_used = l.bank.R_cap
+            need_ws = zb.zo_probe_linear_workspace_bytes(b.T, b.S, b.K, l.m, l.n, d.w.r, l.bank.R_used, _dt(d.dtype))
+            if need_ws > d.ws_bytes:
+                d.ws_bytes = need_ws
+                d.ws = torch.empty(need_ws, device=dev, dtype=torch.uint8)
+        self.graph = None
+
+    def reset(self, first_step=0):
+        """Zeroes every bank and restarts the schedule at step `first_step`."""
+        for l in self.d.layers:
+            l.P.zero_()
+            l.Vb.zero_()
+        self.sched.zero_()
+        self.sched[0] = int(first_step)
+
+    def step(self, stream=None):
+        d, b = self.d, self.batch
+        zb.zo_schedule_step(self.sched, self.nu, self.n_blocks, b.K, self.base_u, self.base_v, self.seed_u,
+                            self.seed_v, stream)
+        for i in range(len(d.layers)):
+            d.probe_linear(i, stream=stream, batch=b)
+        d.score(stream=stream, batch=b)
+        zb.zo_estimate(b.struct, d.cand_sum, d.cand_cnt, float(d.w.eps), d.w.reduction, d.cand_loss, d.proj_grad,
+                       stream)
+        for l in d.layers:
+            zb.zo_bank_update_scheduled(l.bank, l.m, l.n, d.w.r, b.K, self.seed_u, self.seed_v, l.tensor_id,
+                                        d.proj_grad, self.lr, None, self.sched, self.n_blocks, _dt(d.dtype), stream)
+
+    def capture(self):
+        """Captures one step into a HIP graph (after one eager warm-up step, which configures the
+        kernels; call reset() afterwards).  replay() then runs a step."""
+        side = torch.cuda.Stream(device=self.d.device)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step(stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.step(stream=torch.cuda.current_stream())
+        return self.graph
+
+    def replay(self):
+        self.graph.replay()
+
+    def read_sched(self):
+        raw = self.sched.cpu().numpy()
+        return zb.zo_sched.from_buffer_copy(raw.tobytes())
+

@@ -141,3 +141,20 @@ def test_bank_update_validation():
     assert _status(lambda: zb.zo_factor_fill(1, 0, 4, 0, zb.ZO_F32, FAKE)) == zb.ZO_ERR_SHAPE
     assert _status(lambda: zb.zo_philox_words(1, 0, 0, -1, FAKE)) == zb.ZO_ERR_SHAPE
     assert _status(lambda: zb.zo_philox_words(1, 0, 0, 4, None)) == zb.ZO_ERR_NULL
+
+
+def test_schedule_and_scheduled_update_validation():
+    step = lambda **k: zb.zo_schedule_step(k.get("sched", FAKE), k.get("nu", 2), k.get("B", 2), k.get("K", 2), 1, 2,
+                                           k.get("su", FAKE), k.get("sv", FAKE))
+    assert _status(step, sched=None) == zb.ZO_ERR_NULL
+    assert _status(step, nu=0) == zb.ZO_ERR_SHAPE
+    assert _status(step, B=0) == zb.ZO_ERR_SHAPE
+    assert _status(step, sv=None) == zb.ZO_ERR_NULL
+    upd = lambda bank, **k: zb.zo_bank_update_scheduled(bank, 64, 64, k.get("r", 4), k.get("K", 2), FAKE, FAKE, 0, FAKE,
+                                                        1e-3, None, k.get("sched", FAKE), k.get("B", 2), zb.ZO_BF16)
+    assert _status(upd, zb.make_bank(8, 8, FAKE, FAKE)) == zb.ZO_ERR_BANK_FULL        # 2 blocks x 2 dirs x 4 > 8
+    assert _status(upd, zb.make_bank(16, 8, FAKE, FAKE)) == zb.ZO_ERR_SHAPE          # blocks beyond R_used
+    assert _status(upd, zb.make_bank(16, 16, FAKE, FAKE), sched=None) == zb.ZO_ERR_NULL
+    assert _status(upd, zb.make_bank(16, 16, FAKE, None)) == zb.ZO_ERR_NULL
+    assert _status(upd, zb.make_bank(16, 16, FAKE, FAKE), B=0) == zb.ZO_ERR_SHAPE
+    assert C.sizeof(zb.zo_sched) == 32 and C.sizeof(zb.zo_batch) == 96

@@ -1,0 +1,148 @@
+"""GPU parity of the multi-step loop (Sec. 3.2): device-resident schedule, V reused over an
+interval, one bank block per interval, and replay of one captured step."""
+import copy
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import zo_loop
+from oracle import zo_oracle as zo
+from paper_2605_28760_amd import binding as zb
+from paper_2605_28760_amd import workloads as wl
+from paper_2605_28760_amd.runner import DeviceWorkload, LoopDriver
+from zo_testlib import assert_close, oracle_batch, to_np
+
+DEV = "cuda:0"
+BASE_U, BASE_V = 0x1234_5678_9ABC_DEF0, 0xFFFF_FFFF_FFFF_FFF0   # the V seeds wrap modulo 2^64
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def _assert_factor_close(got, want, what, dtype):
+    """Bank columns are (multiples of) factor entries.  In bf16 configurations an entry is a normal
+    rounded to bf16; the GPU evaluates the normal in fp32, the oracle in fp64, so an entry that lies
+    within 1e-5 of a rounding tie may land on the neighbouring bf16 value (2^-8 relative): allowed for
+    at most one entry in a thousand, everything else to 1e-5."""
+    got = np.asarray(got, np.float64); want = np.asarray(want, np.float64)
+    scale = np.maximum(np.abs(want), 1e-30)
+    rel = np.abs(got - want) / scale
+    if dtype != "bf16":
+        assert_close(got, want, 1e-5, what, atol=1e-9)
+        return
+    off = rel > 1e-5
+    assert off.mean() <= 1e-3 and (rel[off] < 2.0 ** -7).all(), (what, int(off.sum()), rel.max())
+
+
+def _banks(d):
+    return [zo.Bank(l.P.cpu().numpy().copy(), l.Vb.cpu().numpy().copy(), l.bank.R_used) for l in d.layers]
+
+
+def test_schedule_kernel_matches_the_oracle_schedule():
+    K, r, nu, B = 3, 8, 2, 3
+    sched = torch.zeros(4, dtype=torch.int64, device=DEV)
+    su = torch.zeros(K, dtype=torch.int64, device=DEV)
+    sv = torch.zeros(K, dtype=torch.int64, device=DEV)
+    sched[0] = 5                                        # start in the middle of an interval
+    for t in range(5, 5 + 2 * nu * B):
+        zb.zo_schedule_step(sched, nu, B, K, BASE_U, BASE_V, su, sv); _sync()
+        want = zo_loop.schedule(t, nu, B, K, r, BASE_U, BASE_V)
+        got = zb.zo_sched.from_buffer_copy(sched.cpu().numpy().tobytes())
+        assert (got.step, got.next_step, got.interval, got.block, got.append) == \
+            (t, t + 1, want.interval, want.block, int(want.append))
+        assert np.array_equal(su.cpu().numpy().view(np.uint64), want.seed_u)
+        assert np.array_equal(sv.cpu().numpy().view(np.uint64), want.seed_v)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_loop_step_by_step_against_the_oracle(dtype):
+    """Every step is checked against the one-step oracle evaluated on the state the GPU is in (its banks
+    before the step, the schedule's seeds), so tolerances do not compound; the banks after the step
+    must be the oracle's update of the banks before it."""
+    nu, B = 2, 2
+    if dtype == "bf16":
+        w = wl.ragged_packed(hidden=128, ffn=256, vocab=300, n_ex=6, n_dirs=2, r=8, R=2 * 2 * 8, len_lo=20, len_hi=90)
+    else:
+        w = wl.opt_scoring(hidden=64, ffn=128, vocab=200, n_ex=3, seq_len=40, r=4, R=2 * 1 * 4, dtype="f32")
+    K = len(w.dir_seed)
+    d = DeviceWorkload(w, DEV)
+    lr = 1e-3 if dtype == "bf16" else 1e-2      # (a step size that keeps the bf16 chain's logits moderate)
+    loop = LoopDriver(d, nu, B, lr=lr, base_u=BASE_U, base_v=BASE_V)
+    loop.reset()
+    ob = oracle_batch(w)
+    for t in range(nu * B + 1):                          # one step past the end: block 0 is reopened
+        before = _banks(d)
+        loop.step(); _sync()
+        sc = zo_loop.schedule(t, nu, B, K, w.r, BASE_U, BASE_V)
+        got = loop.read_sched()
+        assert (got.step, got.block, got.append) == (t, sc.block, int(sc.append))
+        b = zo.Batch(ob.cu_seqlens, ob.seq_cand, ob.cand_dir, ob.cand_sign, sc.seed_u, sc.seed_v)
+        cur = []
+        for l, bank in zip(w.layers, before):
+            c = copy.copy(l); c.P, c.Vb, c.R_used = bank.P, bank.Vb, bank.R_used
+            cur.append(c)
+        want = zo.run_chain(b, w.X, cur, w.head, w.targets, w.r, w.eps, w.dtype, w.reduction)
+        tol = 2e-2 if dtype == "bf16" else 1e-4
+        assert_close(to_np(d.Y[-1]), want["Y"][-1], tol, "step %d: last hidden" % t, atol=1e-5)
+        assert_close(to_np(d.cand_loss), want["cand_loss"], 1e-5, "step %d: cand_loss" % t,
+                     atol=1e-3 if w.reduction == 0 else 0.5)
+        grads = to_np(d.proj_grad)
+        for l, bank, dl in zip(w.layers, before, d.layers):
+            nb = zo.bank_update(bank, b, l.m, l.n, w.r, l.tensor_id, grads, lr, sc.col0, append=sc.append,
+                                factor_dtype=w.dtype)
+            _assert_factor_close(dl.P.cpu().numpy(), nb.P, "step %d: P of %s" % (t, l.name), dtype)
+            _assert_factor_close(dl.Vb.cpu().numpy(), nb.Vb, "step %d: Vb of %s" % (t, l.name), dtype)
+    # after nu * B + 1 steps block 0 holds only the last step's update; block 1 still holds interval 1
+    assert float(d.layers[0].P[:, K * w.r:].abs().max()) > 0
+
+
+def test_free_running_fp32_loop_tracks_the_oracle_loop():
+    """fp32 end to end: the GPU loop and the oracle loop, each feeding on its own gradients, stay together."""
+    w = wl.opt_scoring(hidden=64, ffn=128, vocab=200, n_ex=3, seq_len=40, r=4, R=3 * 1 * 4, dtype="f32")
+    d = DeviceWorkload(w, DEV)
+    loop = LoopDriver(d, 2, 3, lr=1e-5, base_u=7, base_v=11)     # summed NLL: gradients of order 100
+    loop.reset()
+    losses = []
+    for _ in range(6):
+        loop.step(); _sync()
+        losses.append(to_np(d.cand_loss).copy())
+    zero = [copy.copy(l) for l in w.layers]
+    for l in zero:
+        l.P, l.Vb = np.zeros_like(l.P), np.zeros_like(l.Vb)
+    outs, banks = zo_loop.run_loop(oracle_batch(w), w.X, zero, w.head, w.targets, w.r, w.eps, "f32", w.reduction,
+                                   steps=6, nu=2, n_blocks=3, lr=1e-5, base_u=7, base_v=11)
+    assert outs[-1]["cand_loss"][0] < outs[0]["cand_loss"][0] - 0.3      # the loop makes progress
+    for t in range(6):
+        assert_close(losses[t], outs[t]["cand_loss"], 2e-5, "step %d: cand_loss" % t)
+    for dl, bank in zip(d.layers, banks):
+        assert_close(dl.P.cpu().numpy(), bank.P, 2e-2, "final P", atol=1e-6)
+
+
+def test_graph_replay_equals_eager_steps():
+    """One captured step replayed six times (with unrelated eager work and synchronisation between the
+    replays) leaves the same bits as six eager steps: losses of every step, banks, schedule state."""
+    w = wl.ragged_packed(hidden=128, ffn=256, vocab=300, n_ex=6, n_dirs=2, r=8, R=3 * 2 * 8, len_lo=20, len_hi=90)
+    d = DeviceWorkload(w, DEV)
+    loop = LoopDriver(d, 2, 3, lr=1e-2, base_u=BASE_U, base_v=BASE_V)
+    loop.reset()
+    eager = []
+    for _ in range(6):
+        loop.step(); _sync()
+        eager.append((d.cand_loss.clone(), d.proj_grad.clone(), d.tok_nll.clone()))
+    eager_banks = [(l.P.clone(), l.Vb.clone()) for l in d.layers]
+    loop.capture()
+    loop.reset()
+    junk = torch.randn(1 << 16, device=DEV)
+    for t in range(6):
+        loop.replay()
+        junk = (junk * 1.0001).sum().expand(1 << 16).contiguous()     # the program's own eager work in between
+        _sync()
+        for a, b in zip(eager[t], (d.cand_loss, d.proj_grad, d.tok_nll)):
+            assert torch.equal(a, b), "replay %d" % t
+    for (P, Vb), l in zip(eager_banks, d.layers):
+        assert torch.equal(P, l.P) and torch.equal(Vb, l.Vb)
+    assert loop.read_sched().next_step == 6
