@@ -167,6 +167,29 @@ def main():
     d.targets.copy_(all_targets)
     torch.cuda.synchronize()
 
+    # Secondary: the multi-step loop (device-resident seed / bank-block schedule + the whole step), eager
+    # launches against replays of one captured HIP graph.  Run last: it zeroes the banks.
+    from paper_2605_28760_amd.runner import LoopDriver
+    loop_info = None
+    n_blocks = int(w.layers[0].R_used) // (w.r * d.batch.K) if w.layers[0].P is not None else 0
+    if n_blocks >= 1:
+        loop = LoopDriver(d, nu=4, n_blocks=n_blocks, lr=1e-7, base_u=1, base_v=2)
+
+        def time_loop(fn, n):
+            loop.reset()
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(n):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n
+        eager_ms = time_loop(lambda: loop.step(stream=stream), n_sec)
+        loop.capture()
+        graph_ms = time_loop(loop.replay, n_sec)
+        loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms}
+
     seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
     seg_ms = seg.mean(axis=0)
     breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
@@ -200,6 +223,10 @@ def main():
         "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "breakdown_ms": breakdown, "probe_linear_calls": calls, "input_setup_s": gen_s,
         # forward (probe linears + scoring) with candidates / the same rows all foreground
+        # whole step over the same forward with every sequence foreground: the analogue of the paper's
+        # native / matched-inference ratio
+        "native_over_matched": ms_per_step / plain_ms,
+        "loop": loop_info,
         "active_token_scoring": {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms},
         "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},
         # bytes the update step moves (P read + write per layer) against rewriting the dense weights
