@@ -50,20 +50,29 @@ def schedule(step, nu, n_blocks, K, r, base_u, base_v):
 
 
 def run_loop(batch, X, layers, head, targets, r, eps, dtype, reduction, steps, nu, n_blocks, lr,
-             base_u, base_v, first_step=0, allow_wrap=False):
+             base_u, base_v, first_step=0, allow_wrap=False, fold_at_wrap=False):
     """`steps` optimisation steps starting at step number `first_step`.
 
     layers: objects with W, tensor_id, act, P, Vb, R_used (the banks must have
     room for n_blocks * K * r columns; they are not modified: the final banks
     are returned).  Every step evaluates the candidates of `batch` with that
     step's seeds against the current banks, then updates every layer's bank.
-    Returns (per-step list of run_chain outputs, final list of Bank)."""
+    With fold_at_wrap, whenever the schedule is about to reopen block 0 over
+    intervals still in the bank, every bank is first folded into its layer's
+    base weights (rounded to `dtype`) and emptied: the run continues past
+    nu * n_blocks steps and nothing is discarded.
+    Returns (per-step list of run_chain outputs, final list of Bank); with
+    fold_at_wrap the final base weights are a third element."""
     K = len(batch.dir_seed)
+    layers = [copy.copy(l) for l in layers]
     banks = [zo.Bank(np.array(l.P, np.float32), np.array(l.Vb, np.float32), int(l.R_used)) for l in layers]
     outs = []
     for t in range(first_step, first_step + steps):
         sc = schedule(t, nu, n_blocks, K, r, base_u, base_v)
-        if sc.interval >= n_blocks and not allow_wrap:
+        if sc.interval >= n_blocks and sc.block == 0 and sc.append and fold_at_wrap:
+            for i, l in enumerate(layers):
+                l.W, banks[i] = zo.fold_bank(l.W, banks[i], dtype)
+        elif sc.interval >= n_blocks and not allow_wrap and not fold_at_wrap:
             raise ValueError("bank exhausted after %d steps: fold it or stop" % (nu * n_blocks))
         b = zo.Batch(batch.cu_seqlens, batch.seq_cand, batch.cand_dir, batch.cand_sign, sc.seed_u, sc.seed_v)
         cur = []
@@ -77,6 +86,8 @@ def run_loop(batch, X, layers, head, targets, r, eps, dtype, reduction, steps, n
         banks = [zo.bank_update(bank, b, l.W.shape[0], l.W.shape[1], r, l.tensor_id, out["proj_grad"], lr, sc.col0,
                                 append=sc.append, factor_dtype=dtype)
                  for l, bank in zip(layers, banks)]
+    if fold_at_wrap:
+        return outs, banks, [l.W for l in layers]
     return outs, banks
 
 

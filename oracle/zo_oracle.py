@@ -19,7 +19,8 @@ What the path computes, by definition:
     estimator of Sec. 2.1 (Eq. 2) turns them into one projected-gradient
     coefficient per direction;
   * the lazy update of Sec. 3.2 adds beta_k U_k to the direction's column
-    block of P (and, when a block is opened, stores V_k next to it).
+    block of P (and, when a block is opened, stores V_k next to it);
+  * folding writes W_0 + P Vb^T back into the base and empties the bank.
 
 The factorised evaluation the GPU performs is algebraically identical to this
 dense definition (Sec. 2.3), so the oracle *is* the definition: each W_c is
@@ -257,6 +258,19 @@ def bank_update(bank: Bank, batch: Batch, m, n, r, tensor_id, proj_grad, lr,
         else:
             P[:, c0:c0 + r] += beta * U
     return Bank(P.astype(np.float32), Vb.astype(np.float32), R_used)
+
+
+def fold_bank(W, bank: Bank, dtype):
+    """Fold the bank into the base (Sec. 3.2: standalone runs may fold the
+    external state; Eq. bank read right to left): W <- W_0 + P Vb^T over the
+    columns in use, evaluated exactly and rounded once to the storage type of W.
+    Returns the new W (fp32 array holding values of that type) and an emptied
+    bank of the same shape."""
+    R = int(bank.R_used)
+    Wn = np.asarray(W, np.float64) + np.asarray(bank.P, np.float64)[:, :R] @ np.asarray(bank.Vb, np.float64)[:, :R].T
+    Wn = _round_out(Wn, dtype)
+    empty = Bank(np.zeros_like(np.asarray(bank.P, np.float32)), np.zeros_like(np.asarray(bank.Vb, np.float32)), R)
+    return Wn, empty
 
 
 def run_chain(batch: Batch, X, layers, head, targets, r, eps, dtype, reduction):

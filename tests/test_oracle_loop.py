@@ -116,3 +116,38 @@ def test_separate_v_seed_changes_v_only():
     assert np.array_equal(U0, U1) and not np.array_equal(V0, V1)
     b.dir_seed_v = np.array([5], np.uint64)
     assert np.array_equal(V0, zo.direction_factors(b, 0, 12, 20, 4, 6, "f32")[1])
+
+
+def test_fold_moves_the_bank_into_the_base_without_changing_the_map():
+    """Eq. (bank) read right to left: W_0 + P Vb^T folded into the base and an empty bank give the same
+    centre forward.  Catches a transposed factor, columns beyond R_used leaking in, a bank left full."""
+    rng = np.random.default_rng(4)
+    m, n, R = 20, 28, 6
+    W = rng.standard_normal((m, n))
+    bank = zo.Bank(rng.standard_normal((m, R + 3)).astype(np.float32), rng.standard_normal((n, R + 3)).astype(np.float32), R)
+    b = zo.Batch(np.array([0, 5], np.int32), np.array([0], np.int32), np.array([-1], np.int32),
+                 np.array([0.0], np.float32), np.zeros(0, np.uint64))
+    X = rng.standard_normal((5, n))
+    Wn, empty = zo.fold_bank(W, bank, "f64")
+    np.testing.assert_allclose(zo.probe_linear(b, X, Wn, 4, 1e-3, 0, empty, out_dtype="f64"),
+                               zo.probe_linear(b, X, W, 4, 1e-3, 0, bank, out_dtype="f64"), rtol=1e-12)
+    assert not empty.P.any() and not empty.Vb.any() and empty.R_used == R
+    np.testing.assert_allclose(Wn - W, bank.P[:, :R].astype(np.float64) @ bank.Vb[:, :R].astype(np.float64).T, atol=1e-12)
+    # rounding happens once, to the storage type: within half a bf16 ulp of the exact sum
+    Wb = zo.fold_bank(W, bank, "bf16")[0]
+    exact = W + bank.P[:, :R].astype(np.float64) @ bank.Vb[:, :R].astype(np.float64).T
+    assert np.all(np.abs(Wb - exact) <= np.abs(exact) * 2.0 ** -8)
+    assert np.array_equal(zo.fold_bank(Wb, zo.Bank(bank.P, bank.Vb, 0), "bf16")[0], Wb)   # empty bank: no change
+
+
+def test_loop_with_fold_at_wrap_equals_dense_weight_loop():
+    """Past nu * B steps the loop folds and goes on; nothing is lost relative to dense updates."""
+    batch, X, layers, head, tg, r = _problem(n_blocks=2)
+    kw = dict(r=r, eps=1e-2, dtype="f32", reduction=0, steps=7, nu=1, lr=1e-2, base_u=5, base_v=6)
+    outs, banks, Ws = zo_loop.run_loop(batch, X, layers, head, tg, n_blocks=2, fold_at_wrap=True, **kw)
+    outs_d, Wd = zo_loop.run_loop_dense(batch, X, layers, head, tg, **kw)
+    for t, (a, b) in enumerate(zip(outs, outs_d)):
+        np.testing.assert_allclose(a["cand_loss"], b["cand_loss"], rtol=2e-6, err_msg="step %d" % t)
+    for W, bank, D in zip(Ws, banks, Wd):
+        np.testing.assert_allclose(W.astype(np.float64) + bank.P.astype(np.float64) @ bank.Vb.astype(np.float64).T, D,
+                                   atol=5e-6)
