@@ -188,7 +188,15 @@ def main():
         eager_ms = time_loop(lambda: loop.step(stream=stream), n_sec)
         loop.capture()
         graph_ms = time_loop(loop.replay, n_sec)
-        loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms}
+        # fold the (tiny) accumulated bank into the base weights: the price of going past nu * n_blocks steps
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        loop.fold(stream=stream)
+        e0.record(stream)
+        loop.fold(stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
+                     "fold_all_layers_ms": e0.elapsed_time(e1)}
 
     seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
     seg_ms = seg.mean(axis=0)

@@ -280,6 +280,18 @@ int32_t zo_bank_update_scheduled(zo_bank* bank, int32_t m, int32_t n, int32_t r,
                                  const float* dir_weight, const zo_sched* sched, int32_t n_blocks,
                                  zo_dtype factor_dtype, void* stream);
 
+/*
+ * Fold the bank into the base (Sec. 3.2: standalone runs may fold the external
+ * state; Eq. "bank" read right to left):
+ *   W <- W + P[:, :R_used] Vb[:, :R_used]^T      (fp32 arithmetic, one rounding to dtype)
+ * and then zeroes those columns of P and Vb on the device: the bank represents
+ * no update any more and its blocks can be reopened.  bank->R_used is left as
+ * it is.  This is the ONLY entry point that writes base weights; W [m x n] ld ldw
+ * of type dtype is read and written in place.
+ */
+int32_t zo_fold_bank(zo_bank* bank, void* W, int64_t ldw, int32_t m, int32_t n, zo_dtype dtype,
+                     void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -71,6 +71,7 @@ _PROTOS = {
                                    C.c_int, C.c_void_p]),
     "zo_schedule_step": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint64,
                                      C.c_void_p, C.c_void_p, C.c_void_p]),
+    "zo_fold_bank": (C.c_int32, [C.POINTER(zo_bank), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int, C.c_void_p]),
     "zo_bank_update_scheduled": (C.c_int32, [C.POINTER(zo_bank), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p,
                                              C.c_void_p, C.c_int32, C.c_int, C.c_void_p]),
@@ -213,3 +214,7 @@ def zo_bank_update_scheduled(bank, m, n, r, n_dirs, dir_seed, dir_seed_v, tensor
     _check(lib().zo_bank_update_scheduled(C.byref(bank), m, n, r, n_dirs, _ptr(dir_seed), _ptr(dir_seed_v), tensor_id,
                                           _ptr(proj_grad), lr, _ptr(dir_weight), _ptr(sched), n_blocks, factor_dtype,
                                           _stream(stream)))
+
+
+def zo_fold_bank(bank, W, ldw, m, n, dtype, stream=None):
+    _check(lib().zo_fold_bank(C.byref(bank), _ptr(W), ldw, m, n, dtype, _stream(stream)))

@@ -158,6 +158,8 @@ ScorePlan plan_score(int T, int S, int vocab, zo_dtype dt) {
   return p;
 }
 
+bool ld_too_small(int64_t ld, int cols) { return ld < cols || ld > kMaxLd; }
+
 int32_t check_matrix(const char* name, const void* p, int64_t ld, int cols, zo_dtype dt) {
   if (ld < cols || ld > kMaxLd) return fail(ZO_ERR_SHAPE, "%s: leading dimension %lld invalid for %d columns", name, (long long)ld, cols);
   if (dt == ZO_BF16) {
@@ -463,6 +465,23 @@ int32_t zo_bank_update_scheduled(zo_bank* bank, int32_t m, int32_t n, int32_t r,
   a.dir_weight = dir_weight; a.sched = (const zo::SchedDev*)sched; a.n_dirs = n_dirs;
   a.default_weight = 1.0f / (float)n_dirs; a.append = 0; a.bf16 = factor_dtype == ZO_BF16;
   ZO_HIP(zo::launch_bank_update(a, n_dirs, nullptr, (hipStream_t)stream), "zo_bank_update_scheduled");
+  return ZO_OK;
+}
+
+int32_t zo_fold_bank(zo_bank* bank, void* W, int64_t ldw, int32_t m, int32_t n, zo_dtype dtype, void* stream) {
+  if (!bank) return fail(ZO_ERR_NULL, "bank is NULL");
+  if (m < 0 || n < 0) return fail(ZO_ERR_SHAPE, "m = %d, n = %d", m, n);
+  if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
+  if (bank->R_cap < 0 || bank->R_used < 0 || bank->R_used > bank->R_cap)
+    return fail(ZO_ERR_SHAPE, "bank R_used = %d, R_cap = %d", bank->R_used, bank->R_cap);
+  if (m == 0 || n == 0 || bank->R_used == 0) return ZO_OK;
+  if (!W || !bank->P || !bank->Vb) return fail(ZO_ERR_NULL, "W, bank.P or bank.Vb is NULL");
+  if (ld_too_small(ldw, n)) return fail(ZO_ERR_SHAPE, "W: leading dimension %lld invalid for %d columns", (long long)ldw, n);
+  if (((uintptr_t)W & (dtype == ZO_BF16 ? 1u : 3u)) != 0) return fail(ZO_ERR_SHAPE, "W: pointer misaligned");
+  zo::FoldArgs a;
+  a.P = bank->P; a.Vb = bank->Vb; a.R_cap = bank->R_cap; a.R = bank->R_used;
+  a.W = W; a.ldw = ldw; a.m = m; a.n = n; a.bf16 = dtype == ZO_BF16;
+  ZO_HIP(zo::launch_fold_bank(a, (hipStream_t)stream), "zo_fold_bank");
   return ZO_OK;
 }
 

@@ -169,4 +169,11 @@ struct BankUpdateArgs {
 // col0: host array of n_dirs block offsets (passed to the kernel by value in batches)
 hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st);
 
+// W (fp32 or bf16, in place) += P[:, :R] Vb[:, :R]^T, then the R columns of P and Vb are zeroed.
+struct FoldArgs {
+  float* P; float* Vb; int R_cap, R;
+  void* W; int64_t ldw; int m, n; int bf16;
+};
+hipError_t launch_fold_bank(const FoldArgs& a, hipStream_t st);
+
 }  // namespace zo

@@ -182,6 +182,11 @@ class LoopDriver:
             zb.zo_bank_update_scheduled(l.bank, l.m, l.n, d.w.r, b.K, self.seed_u, self.seed_v, l.tensor_id,
                                         d.proj_grad, self.lr, None, self.sched, self.n_blocks, _dt(d.dtype), stream)
 
+    def fold(self, stream=None):
+        """Folds every layer's bank into its base weights and empties it (the one place the base is written)."""
+        for l in self.d.layers:
+            zb.zo_fold_bank(l.bank, l.W, l.W.stride(0), l.m, l.n, _dt(self.d.dtype), stream)
+
     def capture(self):
         """Captures one step into a HIP graph (after one eager warm-up step, which configures the
         kernels; call reset() afterwards).  replay() then runs a step."""

@@ -158,3 +158,16 @@ def test_schedule_and_scheduled_update_validation():
     assert _status(upd, zb.make_bank(16, 16, FAKE, None)) == zb.ZO_ERR_NULL
     assert _status(upd, zb.make_bank(16, 16, FAKE, FAKE), B=0) == zb.ZO_ERR_SHAPE
     assert C.sizeof(zb.zo_sched) == 32 and C.sizeof(zb.zo_batch) == 96
+
+
+def test_fold_bank_validation():
+    fold = lambda bank, **k: zb.zo_fold_bank(bank, k.get("W", FAKE), k.get("ld", 64), k.get("m", 64), k.get("n", 64),
+                                             k.get("dt", zb.ZO_BF16))
+    full = zb.make_bank(8, 8, FAKE, FAKE)
+    assert _status(fold, full, W=None) == zb.ZO_ERR_NULL
+    assert _status(fold, zb.make_bank(8, 8, FAKE, None)) == zb.ZO_ERR_NULL
+    assert _status(fold, full, ld=32) == zb.ZO_ERR_SHAPE
+    assert _status(fold, full, W=FAKE + 1) == zb.ZO_ERR_SHAPE
+    assert _status(fold, full, dt=5) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(fold, zb.make_bank(8, 9, FAKE, FAKE)) == zb.ZO_ERR_SHAPE
+    fold(zb.make_bank(8, 0, None, None), W=None)          # an empty bank folds to nothing, without device work

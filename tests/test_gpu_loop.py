@@ -146,3 +146,57 @@ def test_graph_replay_equals_eager_steps():
     for (P, Vb), l in zip(eager_banks, d.layers):
         assert torch.equal(P, l.P) and torch.equal(Vb, l.Vb)
     assert loop.read_sched().next_step == 6
+
+
+@pytest.mark.parametrize("dtype,m,n", [("f32", 200, 136), ("bf16", 264, 192)])
+def test_fold_bank_matches_the_oracle(dtype, m, n):
+    rng = np.random.default_rng(8)
+    R_cap, R = 24, 16
+    W = (rng.standard_normal((m, n)) / np.sqrt(n)).astype(np.float32)
+    if dtype == "bf16":
+        W = wl.as_bf16_values(W)
+    P = (rng.standard_normal((m, R_cap)) * 0.05).astype(np.float32)
+    Vb = (rng.standard_normal((n, R_cap)) * 0.05).astype(np.float32)
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Wd = torch.from_numpy(W).to(DEV).to(tt).contiguous()
+    Pd, Vd = torch.from_numpy(P).to(DEV), torch.from_numpy(Vb).to(DEV)
+    bank = zb.make_bank(R_cap, R, Pd, Vd)
+    zb.zo_fold_bank(bank, Wd, Wd.stride(0), m, n, zb.ZO_BF16 if dtype == "bf16" else zb.ZO_F32); _sync()
+    want, _ = zo.fold_bank(W, zo.Bank(P, Vb, R), dtype)
+    got = to_np(Wd)
+    if dtype == "f32":
+        assert_close(got, want, 1e-6, "folded W")
+    else:
+        off = got != want                 # the sum may sit within an fp32 rounding of a bf16 tie
+        assert off.mean() <= 1e-3 and np.all(np.abs(got - want)[off] <= np.abs(want[off]) * 2.0 ** -7), int(off.sum())
+        assert (got != W).mean() > 0.2    # the fold really changed the base
+    assert not Pd[:, :R].any() and not Vd[:, :R].any()                       # folded columns are empty now
+    assert np.array_equal(Pd[:, R:].cpu().numpy(), P[:, R:]) and np.array_equal(Vd[:, R:].cpu().numpy(), Vb[:, R:])
+    assert bank.R_used == R
+
+
+def test_loop_with_fold_runs_past_the_bank():
+    """nu = 1, two blocks, five steps: the host folds whenever the schedule is about to reopen block 0;
+    losses follow the oracle's loop with the same policy, and nothing is discarded."""
+    w = wl.opt_scoring(hidden=64, ffn=128, vocab=200, n_ex=3, seq_len=40, r=4, R=2 * 1 * 4, dtype="f32")
+    d = DeviceWorkload(w, DEV)
+    loop = LoopDriver(d, 1, 2, lr=1e-5, base_u=7, base_v=11)
+    loop.reset()
+    losses = []
+    for t in range(5):
+        if t >= 2 and t % 2 == 0:
+            loop.fold()
+        loop.step(); _sync()
+        losses.append(to_np(d.cand_loss).copy())
+    zero = [copy.copy(l) for l in w.layers]
+    for l in zero:
+        l.P, l.Vb = np.zeros_like(l.P), np.zeros_like(l.Vb)
+    outs, banks, Ws = zo_loop.run_loop(oracle_batch(w), w.X, zero, w.head, w.targets, w.r, w.eps, "f32", w.reduction,
+                                       steps=5, nu=1, n_blocks=2, lr=1e-5, base_u=7, base_v=11, fold_at_wrap=True)
+    for t in range(5):
+        assert_close(losses[t], outs[t]["cand_loss"], 2e-5, "step %d: cand_loss" % t)
+    for dl, W, l in zip(d.layers, Ws, w.layers):
+        # each loop feeds on its own gradients (equal to about 1e-3): compare what the folds added
+        assert_close(to_np(dl.W).astype(np.float64) - l.W, W.astype(np.float64) - l.W, 2e-2,
+                     "what two folds added to the base", atol=1e-7)
+        assert np.abs(to_np(dl.W) - l.W).max() > 1e-4
