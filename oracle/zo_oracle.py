@@ -230,6 +230,44 @@ def estimate(batch: Batch, cand_sum, cand_cnt, eps, reduction=0):
     return loss, grad
 
 
+def estimate_es(batch: Batch, cand_sum, cand_cnt, eps, reduction=0):
+    """Reward-normalised one-sided estimate (the evolution-strategies shape of
+    Sec. 4 and the taxonomy table: N candidate evaluations around one centre,
+    reward normalisation, a reward-weighted perturbation update).
+
+    Direction k is represented by its lowest-numbered candidate with positive
+    sign; its reward is minus that candidate's loss.  Over the N directions
+    that have such a candidate,
+        z_k = (R_k - mean R) / max(std R, 1e-8)      (population std)
+    and the coefficient handed to the bank update is c_k = -z_k / eps, so that
+    beta_k = -lr c_k / N = lr z_k / (N eps): the update lr / (N sigma) *
+    sum_k z_k eps_k of evolution strategies with sigma = eps and
+    eps_k = U_k V_k^T.  Directions without a positive candidate get 0.
+    [Reading: the paper names the ingredients, not the formula; this is the
+    standard normalised-reward form.]  Returns (cand_loss, coefficients)."""
+    cand_sum = np.asarray(cand_sum, dtype=np.float64)
+    cand_cnt = np.asarray(cand_cnt, dtype=np.int64)
+    if reduction == 0:
+        loss = cand_sum / np.maximum(cand_cnt, 1)
+    elif reduction == 1:
+        loss = cand_sum.copy()
+    else:
+        raise ValueError(reduction)
+    K = batch.n_dirs
+    rep = np.full(K, -1, dtype=np.int64)
+    for k in range(K):
+        plus = [c for c in range(batch.n_cands) if batch.cand_dir[c] == k and batch.cand_sign[c] > 0]
+        if plus:
+            rep[k] = plus[0]
+    have = rep >= 0
+    coef = np.zeros(K, dtype=np.float64)
+    if have.any():
+        R = -loss[rep[have]]
+        z = (R - R.mean()) / max(R.std(), 1e-8)
+        coef[have] = -z / float(eps)
+    return loss, coef
+
+
 def bank_update(bank: Bank, batch: Batch, m, n, r, tensor_id, proj_grad, lr,
                 col0, dir_weight=None, append=False, factor_dtype="f32"):
     """Lazy update (Sec. 3.2, Eq. layer-coupling): with beta_k = -lr c_k w_k,

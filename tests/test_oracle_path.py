@@ -294,3 +294,36 @@ def test_planted_mistakes_are_caught(monkeypatch):
     bb = _batch([1, 1], [0, 1], [0, 0], [-1, 1], 1)
     _, g = zo.estimate(bb, np.array([1.0, 3.0]), np.array([1, 1]), 0.5)
     assert g[0] == 2.0
+
+
+def test_es_estimate_is_a_normalised_reward_weighting():
+    """Pins for the reward-normalised one-sided estimate: z has mean 0 and unit
+    population variance, is unchanged by shifting or scaling the losses, skips
+    directions without a positive candidate, and on a linear objective the
+    weighted perturbation sum is a descent direction.  Catches a sign error
+    (reward = +loss), a sample-std normalisation and a wrong eps scaling."""
+    rng = np.random.default_rng(11)
+    m, n, r, K, eps = 10, 14, 3, 6, 1e-2
+    cand_dir = np.array(list(range(K - 1)) + [-1], np.int32)           # direction K-1 has no candidate; last = centre
+    cand_sign = np.array([1.0] * (K - 1) + [0.0], np.float32)
+    b = zo.Batch(np.array([0, 1], np.int32), np.array([0], np.int32), cand_dir, cand_sign,
+                 np.arange(K, dtype=np.uint64) + np.uint64(77))
+    G = rng.standard_normal((m, n))
+    dirs = [zo.direction_factors(b, k, m, n, r, 0, "f32") for k in range(K)]
+    # linear objective: L(W0 + eps U V^T) = L0 + eps <G, U V^T>
+    L = np.array([3.0 + eps * np.sum(G * (U @ V.T)) for U, V in dirs[:K - 1]] + [3.0])
+    cnt = np.ones(K, np.int64)
+    loss, c = zo.estimate_es(b, L, cnt, eps, reduction=1)
+    assert np.array_equal(loss, L) and c[K - 1] == 0.0
+    z = -c[:K - 1] * eps
+    assert abs(z.mean()) < 1e-12 and abs((z ** 2).mean() - 1.0) < 1e-12
+    c2 = zo.estimate_es(b, 5.0 * L - 2.0, cnt, eps, reduction=1)[1]
+    np.testing.assert_allclose(c2, c, rtol=1e-9)
+    # beta_k = -lr c_k / K; the summed update must decrease the linear objective
+    upd = sum((-1.0 * c[k] / K) * (dirs[k][0] @ dirs[k][1].T) for k in range(K - 1))
+    assert np.sum(G * upd) < 0
+    # mean reduction divides by the scored-token counts first
+    cnt2 = np.array([2, 4, 1, 5, 3, 1])
+    np.testing.assert_allclose(zo.estimate_es(b, L * cnt2, cnt2, eps, reduction=0)[1], c, rtol=1e-9)
+    # equal rewards: nothing to prefer
+    assert not zo.estimate_es(b, np.full(K, 2.0), cnt, eps, reduction=1)[1].any()
