@@ -214,6 +214,22 @@ int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t*
                     void* stream);
 
 /*
+ * Reward-normalised one-sided estimate (Sec. 4: N candidate evaluations around
+ * one centre, reward normalisation, reward-weighted update; the evolution-
+ * strategies shape).  Direction k is represented by its lowest-numbered
+ * candidate with positive sign, reward R_k = -cand_loss of that candidate;
+ * over the N directions that have one,
+ *   z_k = (R_k - mean R) / max(std R, 1e-8)    (population std, fixed-order sums)
+ *   proj_grad[k] = -z_k / eps                  (0 for directions without one)
+ * so that zo_bank_update's beta_k = -lr proj_grad[k] / N = lr z_k / (N eps).
+ * The formula is this library's reading: the paper names the ingredients only.
+ * Arguments as zo_estimate.
+ */
+int32_t zo_estimate_es(const zo_batch* batch, const float* cand_sum, const int32_t* cand_cnt,
+                       float eps, int32_t reduction, float* cand_loss, float* proj_grad,
+                       void* stream);
+
+/*
  * Lazy bank update (Sec. 3.2, Eq. "layer-coupling": sum_t beta_t U_t V_k^T =
  * P_k V_k^T, so only P_k is maintained).  For every direction k, with
  * beta_k = -lr * proj_grad[k] * dir_weight[k] read on the device:

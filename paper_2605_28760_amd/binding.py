@@ -71,6 +71,8 @@ _PROTOS = {
                                    C.c_int, C.c_void_p]),
     "zo_schedule_step": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_uint64, C.c_uint64,
                                      C.c_void_p, C.c_void_p, C.c_void_p]),
+    "zo_estimate_es": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]),
     "zo_fold_bank": (C.c_int32, [C.POINTER(zo_bank), C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int, C.c_void_p]),
     "zo_bank_update_scheduled": (C.c_int32, [C.POINTER(zo_bank), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p,
@@ -218,3 +220,8 @@ def zo_bank_update_scheduled(bank, m, n, r, n_dirs, dir_seed, dir_seed_v, tensor
 
 def zo_fold_bank(bank, W, ldw, m, n, dtype, stream=None):
     _check(lib().zo_fold_bank(C.byref(bank), _ptr(W), ldw, m, n, dtype, _stream(stream)))
+
+
+def zo_estimate_es(batch, cand_sum, cand_cnt, eps, reduction, cand_loss, proj_grad, stream=None):
+    _check(lib().zo_estimate_es(C.byref(batch), _ptr(cand_sum), _ptr(cand_cnt), eps, reduction, _ptr(cand_loss),
+                                _ptr(proj_grad), _stream(stream)))

@@ -391,6 +391,17 @@ int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t*
   return ZO_OK;
 }
 
+int32_t zo_estimate_es(const zo_batch* batch, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                       int32_t reduction, float* cand_loss, float* proj_grad, void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (reduction != 0 && reduction != 1) return fail(ZO_ERR_UNSUPPORTED, "reduction %d", reduction);
+  if (!(eps > 0.0f)) return fail(ZO_ERR_SHAPE, "eps = %g must be positive", (double)eps);
+  if (batch->n_cands > 0 && (!cand_sum || !cand_cnt || !cand_loss)) return fail(ZO_ERR_NULL, "cand_sum, cand_cnt or cand_loss is NULL");
+  if (batch->n_dirs > 0 && !proj_grad) return fail(ZO_ERR_NULL, "proj_grad is NULL");
+  ZO_HIP(zo::launch_estimate_es(to_dev(batch), cand_sum, cand_cnt, eps, reduction, cand_loss, proj_grad, (hipStream_t)stream), "zo_estimate_es");
+  return ZO_OK;
+}
+
 namespace {
 int32_t check_bank_update(const zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, zo_dtype factor_dtype) {
   if (!bank) return fail(ZO_ERR_NULL, "bank is NULL");

@@ -158,6 +158,8 @@ struct SchedDev {
 hipError_t launch_schedule_step(SchedDev* s, int nu, int n_blocks, int K, uint64_t base_u, uint64_t base_v,
                                 uint64_t* seed_u, uint64_t* seed_v, hipStream_t st);
 
+hipError_t launch_estimate_es(const BatchDev& b, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                              int reduction, float* cand_loss, float* proj_grad, hipStream_t st);
 struct BankUpdateArgs {
   float* P; float* Vb; int R_cap;
   int m, n, r;

@@ -165,6 +165,53 @@ hipError_t launch_estimate(const BatchDev& b, const float* cand_sum, const int32
   return hipGetLastError();
 }
 
+// Reward-normalised one-sided estimate: one workgroup; every direction finds its representative
+// candidate, thread 0 forms mean and variance of the rewards in direction order (fixed order, N is
+// small), then every direction gets -z / eps.
+__global__ __launch_bounds__(256) void k_estimate_es(BatchDev b, const float* cand_sum, const int32_t* cand_cnt,
+                                                     float eps, int reduction, float* cand_loss, float* proj_grad) {
+  __shared__ float s_mean, s_inv_std;
+  auto loss_of = [&](int c) {
+    return reduction == 0 ? cand_sum[c] / (float)max(cand_cnt[c], 1) : cand_sum[c];
+  };
+  auto rep_of = [&](int k) {
+    for (int c = 0; c < b.C; ++c)
+      if (b.cand_dir[c] == k && b.cand_sign[c] > 0.0f) return c;
+    return -1;
+  };
+  for (int c = threadIdx.x; c < b.C; c += blockDim.x) cand_loss[c] = loss_of(c);
+  if (threadIdx.x == 0) {
+    float sum = 0.0f;
+    int n = 0;
+    for (int k = 0; k < b.K; ++k) {
+      const int c = rep_of(k);
+      if (c >= 0) { sum += -loss_of(c); ++n; }
+    }
+    const float mean = n > 0 ? sum / (float)n : 0.0f;
+    float var = 0.0f;
+    for (int k = 0; k < b.K; ++k) {
+      const int c = rep_of(k);
+      if (c >= 0) { const float dlt = -loss_of(c) - mean; var = fmaf(dlt, dlt, var); }
+    }
+    var = n > 0 ? var / (float)n : 0.0f;
+    s_mean = mean;
+    s_inv_std = 1.0f / fmaxf(sqrtf(var), 1e-8f);
+  }
+  __syncthreads();
+  for (int k = threadIdx.x; k < b.K; k += blockDim.x) {
+    const int c = rep_of(k);
+    proj_grad[k] = c >= 0 ? -((-loss_of(c) - s_mean) * s_inv_std) / eps : 0.0f;
+  }
+}
+
+hipError_t launch_estimate_es(const BatchDev& b, const float* cand_sum, const int32_t* cand_cnt, float eps,
+                              int reduction, float* cand_loss, float* proj_grad, hipStream_t st) {
+  if (b.C == 0 && b.K == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_estimate_es, dim3(1), dim3(256), 0, st, b, cand_sum, cand_cnt, eps, reduction, cand_loss,
+                     proj_grad);
+  return hipGetLastError();
+}
+
 // ---- lazy bank update ---------------------------------------------------------------------
 constexpr int kBankBatch = 32;
 struct BankCols { int32_t first_dir; int32_t n; int32_t col0[kBankBatch]; };

@@ -355,3 +355,39 @@ def test_scoring_only_active_tokens():
         on = tg >= 0
         assert np.all(tok[~on] == 0)
         assert np.array_equal(tok[on], full_tok[on]), name   # same bits as when every token is scored
+
+
+def test_es_style_one_sided_candidates():
+    """N one-sided candidates around a centre (Sec. 4, the evolution-strategies shape): the probe path
+    evaluates them like any other candidate table; zo_estimate_es turns the losses into normalised-reward
+    coefficients.  Checked against the oracle on the GPU's own candidate sums and end to end."""
+    import copy
+    base = wl.opt_scoring(hidden=128, ffn=256, vocab=300, n_ex=9, seq_len=50, r=8, R=16)
+    N = 5
+    w = copy.copy(base)
+    S = len(base.seq_cand)
+    w.seq_cand = (np.arange(S) % (N + 1)).astype(np.int32)
+    w.cand_dir = np.array(list(range(N)) + [-1], np.int32)
+    w.cand_sign = np.array([1.0] * N + [0.0], np.float32)
+    w.dir_seed = (np.arange(N, dtype=np.uint64) + np.uint64(4242))
+    w.reduction = 0
+    d = DeviceWorkload(w, DEV)
+    for i in range(len(w.layers)):
+        d.probe_linear(i)
+    d.score()
+    zb.zo_estimate_es(d.batch.struct, d.cand_sum, d.cand_cnt, float(w.eps), 0, d.cand_loss, d.proj_grad); _sync()
+    _per_layer_parity(w, d)
+    ob = oracle_batch(w)
+    loss, coef = zo.estimate_es(ob, to_np(d.cand_sum), to_np(d.cand_cnt), w.eps, 0)
+    assert_close(to_np(d.cand_loss), loss, 1e-6, "cand_loss")
+    assert_close(to_np(d.proj_grad), coef, 1e-3, "normalised-reward coefficients", atol=1e-2)
+    z = -to_np(d.proj_grad) * w.eps
+    assert abs(z.mean()) < 1e-4 and abs((z ** 2).mean() - 1.0) < 1e-3
+    # the two-point estimate has nothing to difference here: no direction has a negative candidate
+    zb.zo_estimate(d.batch.struct, d.cand_sum, d.cand_cnt, float(w.eps), 0, d.cand_loss, d.proj_grad); _sync()
+    assert not to_np(d.proj_grad).any()
+    # end to end: the oracle chain's own candidate losses give the same preference order
+    out = oracle_chain(w)
+    _, coef_o = zo.estimate_es(ob, out["cand_sum"], out["cand_cnt"], w.eps, 0)
+    zb.zo_estimate_es(d.batch.struct, d.cand_sum, d.cand_cnt, float(w.eps), 0, d.cand_loss, d.proj_grad); _sync()
+    assert_close(to_np(d.cand_loss), out["cand_loss"], 1e-5, "cand_loss vs oracle chain", atol=1e-3)
