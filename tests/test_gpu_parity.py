@@ -391,3 +391,44 @@ def test_es_style_one_sided_candidates():
     _, coef_o = zo.estimate_es(ob, out["cand_sum"], out["cand_cnt"], w.eps, 0)
     zb.zo_estimate_es(d.batch.struct, d.cand_sum, d.cand_cnt, float(w.eps), 0, d.cand_loss, d.proj_grad); _sync()
     assert_close(to_np(d.cand_loss), out["cand_loss"], 1e-5, "cand_loss vs oracle chain", atol=1e-3)
+
+
+def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0):
+    """One bf16 probe linear with its own input on an arbitrary candidate table."""
+    rng = np.random.default_rng(seed)
+    cu = np.zeros(len(lens) + 1, np.int32); cu[1:] = np.cumsum(lens)
+    T = int(cu[-1])
+    K = (max(cand_dir) + 1) if len(cand_dir) and max(cand_dir) >= 0 else 0
+    X = wl.as_bf16_values(rng.standard_normal((T, n)).astype(np.float32))
+    W = wl.as_bf16_values((rng.standard_normal((m, n)) / np.sqrt(n)).astype(np.float32))
+    P = (rng.standard_normal((m, R)) * 1e-2).astype(np.float32) if R else None
+    Vb = (rng.standard_normal((n, R)) * 1e-2).astype(np.float32) if R else None
+    layer = wl.Layer("odd", m, n, 6, W, act, P, Vb, R, X)
+    return wl.Workload("odd-shapes", 9, "bf16", r, 1e-3, cu, np.array(seq_cand, np.int32),
+                       np.array(cand_dir, np.int32), np.array(cand_sign, np.float32),
+                       (np.arange(K, dtype=np.uint64) + np.uint64(991 + seed)), [layer], False)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_bf16_probe_linear_odd_shapes(case):
+    """Shapes that leave ragged tails in every tile dimension of the matrix-core kernel (out features
+    not a multiple of 16, 128 or 256; one token; token counts just past a tile; many short sequences of
+    different directions inside one token tile; ranks 1 and 64; a bank wider than one side-down pass)."""
+    cases = [
+        dict(lens=[1], seq_cand=[0], cand_dir=[0], cand_sign=[1], m=8, n=64, r=1, R=0),
+        dict(lens=[257, 3], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=200, n=128, r=5, R=16),
+        dict(lens=[5] * 60, seq_cand=[i % 7 - 1 for i in range(60)], cand_dir=[0, 0, 1, 1, 2, -1],
+             cand_sign=[1, -1, 1, -1, 1, 0], m=264, n=192, r=64, R=48, act=1),
+        dict(lens=[130, 0, 0, 126, 1], seq_cand=[1, 0, -1, -1, 0], cand_dir=[0, 0], cand_sign=[1, -1], m=24, n=320, r=16, R=144),
+        dict(lens=[300], seq_cand=[-1], cand_dir=[0], cand_sign=[1], m=136, n=64, r=8, R=32),
+        dict(lens=[64, 64, 64, 64, 1], seq_cand=[0, 1, 2, 3, 4], cand_dir=[0, 0, 1, 1, -1], cand_sign=[1, -1, 1, -1, 0],
+             m=520, n=256, r=17, R=0),
+        dict(lens=[511], seq_cand=[2], cand_dir=[1, 1, 0], cand_sign=[-1, 1, 1], m=256, n=1024, r=33, R=136),
+        dict(lens=[2, 254, 2], seq_cand=[0, -1, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=1032, n=64, r=2, R=8),
+    ]
+    w = _single_layer(case, **cases[case])
+    d = DeviceWorkload(w, DEV)
+    d.probe_linear(0); _sync()
+    _per_layer_parity(w, d)
+    y32 = to_np(DeviceWorkload(w, DEV, out_dtype="f32").probe_linear(0))
+    assert_close(y32, oracle_layer(w, 0, w.layers[0].X, out_dtype="f32"), 2e-2, "fp32 output")
