@@ -265,7 +265,7 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   tabs.max_items = plan.max_items;
   // a batch without candidates (or probes and bank both absent) is a plain GEMM
   const bool has_side = batch->n_cands > 0;
-  if (has_side) ZO_HIP(zo::launch_seq_tables(bd, eps, tabs, st), "batch tables");
+  if (has_side && in_dtype != ZO_BF16) ZO_HIP(zo::launch_seq_tables(bd, eps, tabs, st), "batch tables");
 
   if (in_dtype == ZO_BF16) {
     uint16_t* Uh = (uint16_t*)(ws + plan.Uh);
@@ -274,9 +274,9 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
     uint16_t* Vbt = (uint16_t*)(ws + plan.Vbt);
     uint16_t* Aside = (uint16_t*)(ws + plan.Aside);
     if (has_side) {
-      ZO_HIP(zo::launch_factor_images_bf16(bd, tensor_id, m, n, r, plan.RP, Uh, Vt, st), "factor images");
-      if (R > 0)
-        ZO_HIP(zo::launch_bank_images_bf16(bank->P, bank->Vb, bank->R_cap, R, plan.Rp, m, n, Ph, Vbt, st), "bank images");
+      ZO_HIP(zo::launch_probe_prep_bf16(bd, eps, tabs, tensor_id, m, n, r, plan.RP, plan.Rp, R > 0 ? bank->P : nullptr,
+                                        R > 0 ? bank->Vb : nullptr, R > 0 ? bank->R_cap : 0, R, Uh, Vt, Ph, Vbt, st),
+             "probe preparation");
       zo::SideDownArgs sd;
       sd.X = (const uint16_t*)X; sd.ldx = ldx; sd.Vt = Vt; sd.Vbt = Vbt;
       sd.n = n; sd.RP = plan.RP; sd.Rp = plan.Rp; sd.T = T;

@@ -51,10 +51,6 @@ hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_ca
 hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, hipStream_t st);
 // bf16 operand images: Uh [K][m][RP] (k-contiguous rows of U, zero padded to RP),
 // Vt [K][RP][n] (V transposed), Ph [m][Rp], Vbt [Rp][n].
-hipError_t launch_factor_images_bf16(const BatchDev& b, uint32_t tensor_id, int m, int n, int r, int RP,
-                                     uint16_t* Uh, uint16_t* Vt, hipStream_t st);
-hipError_t launch_bank_images_bf16(const float* P, const float* Vb, int R_cap, int R_used, int Rp,
-                                   int m, int n, uint16_t* Ph, uint16_t* Vbt, hipStream_t st);
 // fp32 factors: Uf [K][m][r], Vf [K][n][r]
 hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int n, int r,
                               float* Uf, float* Vf, hipStream_t st);
@@ -71,6 +67,11 @@ struct SideDownArgs {
   uint16_t* Aside;                  // bf16 [T][RP+Rp]: [s*eps*X V | X Vb]
   const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;  // for the split-K reduction
 };
+// sequence tables, token -> sequence map and the four operand images of a bf16 probe linear in one launch
+hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables& tabs, uint32_t tensor_id, int m,
+                                  int n, int r, int RP, int Rp, const float* P, const float* Vb, int R_cap,
+                                  int R_used, uint16_t* Uh, uint16_t* Vt, uint16_t* Ph, uint16_t* Vbt,
+                                  hipStream_t st);
 hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st);
 
 // ---- zo_gemm.hip ---------------------------------------------------------------

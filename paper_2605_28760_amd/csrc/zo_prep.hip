@@ -63,12 +63,15 @@ __device__ __forceinline__ int seq_of_row(const int32_t* cu, int S, int t) {
   return lo;
 }
 
-__global__ void k_tok_index(BatchDev b, int32_t* tok_seq, int32_t* tok_cand) {
-  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void tok_index_at(const BatchDev& b, int t, int32_t* tok_seq, int32_t* tok_cand) {
   if (t >= b.T) return;
   const int s = seq_of_row(b.cu, b.S, t);
   if (tok_seq) tok_seq[t] = s;
   if (tok_cand) tok_cand[t] = b.seq_cand[s];
+}
+
+__global__ void k_tok_index(BatchDev b, int32_t* tok_seq, int32_t* tok_cand) {
+  tok_index_at(b, blockIdx.x * blockDim.x + threadIdx.x, tok_seq, tok_cand);
 }
 
 hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_cand, hipStream_t st) {
@@ -80,7 +83,7 @@ hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_ca
 // Per-sequence kind / scale and the list of side-down work items (chunks of at
 // most kSideRows rows of one sequence).  One workgroup; sequences are scanned in
 // blocks of 1024 so the item order follows the row order.
-__global__ __launch_bounds__(1024) void k_seq_tables(BatchDev b, float eps, SeqTables t) {
+__device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, const SeqTables& t) {
   __shared__ int s_scan[1024];
   __shared__ int s_carry;
   const int tid = threadIdx.x;
@@ -130,6 +133,8 @@ __global__ __launch_bounds__(1024) void k_seq_tables(BatchDev b, float eps, SeqT
   if (tid == 0) *t.n_items = min(s_carry, t.max_items);
 }
 
+__global__ __launch_bounds__(1024) void k_seq_tables(BatchDev b, float eps, SeqTables t) { seq_tables_block(b, eps, t); }
+
 hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, hipStream_t st) {
   hipLaunchKernelGGL(k_seq_tables, dim3(1), dim3(1024), 0, st, b, eps, t);
   hipError_t e = hipGetLastError();
@@ -138,8 +143,7 @@ hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, h
 }
 
 // ---- operand images ----------------------------------------------------------------------
-__global__ void k_image_U(BatchDev b, uint32_t tid_u, int m, int r, int RP, bf16_t* Uh) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint32_t tid_u, int m, int r, int RP, bf16_t* Uh) {
   const int64_t per_dir = (int64_t)m * RP;
   if (idx >= per_dir * b.K) return;
   const int k = (int)(idx / per_dir);
@@ -150,8 +154,7 @@ __global__ void k_image_U(BatchDev b, uint32_t tid_u, int m, int r, int RP, bf16
   Uh[idx] = f32_to_bf16(z);
 }
 
-__global__ void k_image_Vt(BatchDev b, uint32_t tid_v, int n, int r, int RP, bf16_t* Vt) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void image_Vt_at(const BatchDev& b, int64_t idx, uint32_t tid_v, int n, int r, int RP, bf16_t* Vt) {
   const int64_t per_dir = (int64_t)n * RP;
   if (idx >= per_dir * b.K) return;
   const int k = (int)(idx / per_dir);
@@ -162,48 +165,10 @@ __global__ void k_image_Vt(BatchDev b, uint32_t tid_v, int n, int r, int RP, bf1
   Vt[idx] = f32_to_bf16(z);
 }
 
-hipError_t launch_factor_images_bf16(const BatchDev& b, uint32_t tensor_id, int m, int n, int r, int RP,
-                                     uint16_t* Uh, uint16_t* Vt, hipStream_t st) {
-  if (b.K == 0) return hipSuccess;
-  const int64_t nu = (int64_t)b.K * m * RP, nv = (int64_t)b.K * n * RP;
-  hipLaunchKernelGGL(k_image_U, dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st, b, tensor_id & ~1u, m, r,
-                     RP, Uh);
-  hipLaunchKernelGGL(k_image_Vt, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st, b, tensor_id | 1u, n, r,
-                     RP, Vt);
-  return hipGetLastError();
-}
-
-__global__ void k_image_P(const float* P, int R_cap, int R_used, int Rp, int m, bf16_t* Ph) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void image_P_at(int64_t idx, const float* P, int R_cap, int R_used, int Rp, int m, bf16_t* Ph) {
   if (idx >= (int64_t)m * Rp) return;
   const int i = (int)(idx / Rp), j = (int)(idx % Rp);
   Ph[idx] = f32_to_bf16(j < R_used ? P[(int64_t)i * R_cap + j] : 0.0f);
-}
-
-// Vbt[j][i] = Vb[i][j]: 32x32 tiles through LDS so both sides are coalesced.
-__global__ void k_image_Vbt(const float* Vb, int R_cap, int R_used, int Rp, int n, bf16_t* Vbt) {
-  __shared__ float tile[32][33];
-  const int i0 = blockIdx.x * 32, j0 = blockIdx.y * 32;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 256 threads: ty 0..7
-  for (int rr = ty; rr < 32; rr += 8) {
-    const int i = i0 + rr, j = j0 + tx;
-    tile[rr][tx] = (i < n && j < R_used) ? Vb[(int64_t)i * R_cap + j] : 0.0f;
-  }
-  __syncthreads();
-  for (int rr = ty; rr < 32; rr += 8) {
-    const int j = j0 + rr, i = i0 + tx;
-    if (j < Rp && i < n) Vbt[(int64_t)j * n + i] = f32_to_bf16(tile[tx][rr]);
-  }
-}
-
-hipError_t launch_bank_images_bf16(const float* P, const float* Vb, int R_cap, int R_used, int Rp,
-                                   int m, int n, uint16_t* Ph, uint16_t* Vbt, hipStream_t st) {
-  if (Rp == 0) return hipSuccess;
-  const int64_t np = (int64_t)m * Rp;
-  hipLaunchKernelGGL(k_image_P, dim3((unsigned)((np + 255) / 256)), dim3(256), 0, st, P, R_cap, R_used, Rp, m, Ph);
-  hipLaunchKernelGGL(k_image_Vbt, dim3((n + 31) / 32, (Rp + 31) / 32), dim3(256), 0, st, Vb, R_cap, R_used, Rp,
-                     n, Vbt);
-  return hipGetLastError();
 }
 
 __global__ void k_factors_f32(BatchDev b, uint32_t tid, int rows, int r, float* out) {
@@ -221,6 +186,63 @@ hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int 
   const int64_t nu = (int64_t)b.K * m * r, nv = (int64_t)b.K * n * r;
   hipLaunchKernelGGL(k_factors_f32, dim3((unsigned)((nu + 255) / 256)), dim3(256), 0, st, b, tensor_id & ~1u, m, r, Uf);
   hipLaunchKernelGGL(k_factors_f32, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st, b, tensor_id | 1u, n, r, Vf);
+  return hipGetLastError();
+}
+
+// ---- everything a bf16 probe linear prepares before its side-down pass, in one launch ------
+// Block roles, in order: [sequence tables: 1] [token -> sequence map] [U image] [V^T image]
+// [P image] [Vb^T image: 32x32 transposing tiles].  The pieces do not depend on one another.
+struct ProbePrepArgs {
+  BatchDev b; float eps; SeqTables tabs;
+  uint32_t tensor_id; int m, n, r, RP, Rp;
+  const float* P; const float* Vb; int R_cap, R_used;
+  bf16_t* Uh; bf16_t* Vt; bf16_t* Ph; bf16_t* Vbt;
+  int nb_tok, nb_U, nb_Vt, nb_P, nb_Vbt, vbt_tiles_n;
+};
+
+__global__ __launch_bounds__(1024) void k_probe_prep(ProbePrepArgs a) {
+  int blk = blockIdx.x;
+  if (blk == 0) { seq_tables_block(a.b, a.eps, a.tabs); return; }
+  blk -= 1;
+  if (blk < a.nb_tok) { tok_index_at(a.b, blk * 1024 + threadIdx.x, a.tabs.tok_seq, nullptr); return; }
+  blk -= a.nb_tok;
+  if (blk < a.nb_U) { image_U_at(a.b, (int64_t)blk * 1024 + threadIdx.x, a.tensor_id & ~1u, a.m, a.r, a.RP, a.Uh); return; }
+  blk -= a.nb_U;
+  if (blk < a.nb_Vt) { image_Vt_at(a.b, (int64_t)blk * 1024 + threadIdx.x, a.tensor_id | 1u, a.n, a.r, a.RP, a.Vt); return; }
+  blk -= a.nb_Vt;
+  if (blk < a.nb_P) { image_P_at((int64_t)blk * 1024 + threadIdx.x, a.P, a.R_cap, a.R_used, a.Rp, a.m, a.Ph); return; }
+  blk -= a.nb_P;
+  // Vbt[j][i] = Vb[i][j], one 32x32 tile per block, coalesced on both sides
+  __shared__ float tile[32][33];
+  const int i0 = (blk % a.vbt_tiles_n) * 32, j0 = (blk / a.vbt_tiles_n) * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  {
+    const int i = i0 + ty, j = j0 + tx;
+    tile[ty][tx] = (i < a.n && j < a.R_used) ? a.Vb[(int64_t)i * a.R_cap + j] : 0.0f;
+  }
+  __syncthreads();
+  {
+    const int j = j0 + ty, i = i0 + tx;
+    if (j < a.Rp && i < a.n) a.Vbt[(int64_t)j * a.n + i] = f32_to_bf16(tile[tx][ty]);
+  }
+}
+
+hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables& tabs, uint32_t tensor_id, int m,
+                                  int n, int r, int RP, int Rp, const float* P, const float* Vb, int R_cap,
+                                  int R_used, uint16_t* Uh, uint16_t* Vt, uint16_t* Ph, uint16_t* Vbt,
+                                  hipStream_t st) {
+  ProbePrepArgs a;
+  a.b = b; a.eps = eps; a.tabs = tabs; a.tensor_id = tensor_id; a.m = m; a.n = n; a.r = r; a.RP = RP; a.Rp = Rp;
+  a.P = P; a.Vb = Vb; a.R_cap = R_cap; a.R_used = R_used; a.Uh = Uh; a.Vt = Vt; a.Ph = Ph; a.Vbt = Vbt;
+  auto blocks = [](int64_t n_elems) { return (int)((n_elems + 1023) / 1024); };
+  a.nb_tok = blocks(b.T);
+  a.nb_U = blocks((int64_t)b.K * m * RP);
+  a.nb_Vt = blocks((int64_t)b.K * n * RP);
+  a.nb_P = Rp > 0 ? blocks((int64_t)m * Rp) : 0;
+  a.vbt_tiles_n = (n + 31) / 32;
+  a.nb_Vbt = Rp > 0 ? a.vbt_tiles_n * ((Rp + 31) / 32) : 0;
+  const int64_t total = 1 + (int64_t)a.nb_tok + a.nb_U + a.nb_Vt + a.nb_P + a.nb_Vbt;
+  hipLaunchKernelGGL(k_probe_prep, dim3((unsigned)total), dim3(1024), 0, st, a);
   return hipGetLastError();
 }
 
