@@ -10,7 +10,7 @@
 // item share one direction.  One wave per (item, k-split); the four waves of a
 // workgroup walk the same K range, so the bank operand Vb is staged once per
 // workgroup in LDS (direct-to-LDS loads, double buffered) while each wave keeps
-// its own rows of X and its own direction's V in registers, double buffered.
+// its own rows of X and its own direction's V in registers.
 #include <type_traits>
 
 #include "zo_device.hpp"
@@ -26,12 +26,11 @@ typedef __attribute__((address_space(3))) void lds_void;
 // NBB = number of 16-column bank blocks this pass accumulates; kDir = whether the pass
 // also carries the (single) 16-column direction block.  cb0 = first bank block of the pass.
 //
-// Pipeline.  A wave keeps two K steps of its rows in registers: while step s is multiplied,
-// the loads of step s+1 (issued before the wait for step s) are in flight, so every wave
-// always has 8 KiB of X outstanding.  The bank operand of step s+1 goes to the other LDS
-// stage right after the workgroup barrier of step s, when every wave has finished the
-// MFMAs of step s-1, the last readers of that stage.  Every wave issues the same loads in
-// the same order, so the waits are compile-time constants.
+// One K step of 64: a wave issues the loads of its 64 rows (8 KiB) and of its direction's V, the
+// workgroup's Vb slice goes to one of two alternating LDS stages, everybody waits, one barrier,
+// multiply.  Measured alternatives on this part: keeping a second step of X in flight in registers
+// is slower (3.0 against 4.3 TB/s: the loads of a step already fill the memory pipeline), as are
+// steps of 32 or 128, items of 16 or 32 rows, and a third workgroup per CU (register spills).
 template <int NBB, bool kDir>
 __global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownArgs a, int cb0) {
   // Vb stage: [half h of the K step][16-col block][col][4 chunks of 16 B], chunk index XOR (col>>2)&3
@@ -52,18 +51,14 @@ __global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownA
   constexpr int kstride = 64;
   const int nsteps = kchunk / kstride;
   const bool has_dir = kDir && it.kind >= 0;
-  const bool work = live && it.kind != kKindForeground;   // wave-uniform
+  const bool work = live && it.kind != kKindForeground;   // wave-uniform; foreground rows are not read at all
 
-  // per-lane addresses: 16 B at (row, k + h*32 + lg*8).  A wave without work (no item, or a
-  // foreground item, whose rows are not read at all) issues the same loads as the others, so
-  // that the waits below are the same constants for every wave, but always of one 16-byte
-  // piece of X that stays in cache.
-  const int xstride = work ? 64 : 0;
+  // per-lane addresses: 16 B at (row, k + h*32 + lg*8)
   const bf16_t* pa[4];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
     const int row = it.row0 + min(rb * 16 + lr, it.nrows - 1);
-    pa[rb] = work ? a.X + (int64_t)row * a.ldx + k_begin + lg * 8 : a.X;
+    pa[rb] = a.X + (int64_t)row * a.ldx + k_begin + lg * 8;
   }
   // a centre item has no direction: read a valid address (its own X rows), discard the result
   const bf16_t* pv = has_dir ? a.Vt + ((int64_t)it.kind * a.RP + lr) * a.n + k_begin + lg * 8 : pa[0];
@@ -77,13 +72,10 @@ __global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownA
       (void*)(a.Vbt + (int64_t)cb0 * 16 * a.n), 0, (int)((int64_t)(NBB > 0 ? NBB : 1) * 16 * a.n * 2), 0x00020000);
   const uint32_t rd_off = lr * 64 + ((lg ^ ((lr >> 2) & 3)) << 4);
 
-  // every wave issues the same number of Vb loads (the last ones may repeat a block another
-  // wave also loads: same data, same place)
-  constexpr int kVbPerWave = (2 * NBB + 3) / 4;
   auto issue_vb = [&](int stage, int step) {
 #pragma unroll
-    for (int i = 0; i < kVbPerWave; ++i) {
-      const int j = min(wave + 4 * i, 2 * NBB - 1);
+    for (int j = 0; j < 2 * NBB; ++j) {
+      if ((j & 3) != wave) continue;
       const int h = j & 1, b = j >> 1;
       __builtin_amdgcn_raw_ptr_buffer_load_lds(vb_rsrc, (lds_void*)(&s_vb[stage][0] + (h * NBB + b) * 1024), 16,
                                                (int)vb_off, (b * 16 * a.n + step * kstride + h * 32) * 2, 0, 0);
@@ -96,62 +88,42 @@ __global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownA
 #pragma unroll
     for (int cb = 0; cb < NBB + 1; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  bf16x8 fa[2][2][4], fv[2][2];   // [buffer][half][row block], [buffer][half]
-  constexpr int kRegLoads = 8 + (kDir ? 2 : 0);   // register loads of one step
-  auto load_x = [&](auto bufc, int step) {
-    constexpr int q = decltype(bufc)::value;
+  // Refilling stage (step+1)&1 is safe once a wave is past barrier `step`: every wave has then
+  // finished the MFMAs of step-1, the last reader of that stage.
+  for (int step = 0; step < nsteps; ++step) {
+    bf16x8 fa[2][4], fv[2];   // [half][row block], [half]
+    if (work) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) fa[h][rb] = load_frag(pa[rb] + step * kstride + h * 32);
+        if (kDir) fv[h] = load_frag(pv + step * kstride + h * 32);
+      }
+    } else {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int rb = 0; rb < 4; ++rb) fa[h][rb] = zero_frag();
+        fv[h] = zero_frag();
+      }
+    }
+    if (NBB > 0) issue_vb(step & 1, step);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const char* stage = &s_vb[step & 1][0];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
+      bf16x8 fb[NBB > 0 ? NBB : 1];
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) fa[q][h][rb] = load_frag(pa[rb] + step * xstride + h * 32 * (xstride != 0));
-      if (kDir) fv[q][h] = load_frag(pv + step * xstride + h * 32 * (xstride != 0));
-    }
-  };
-  auto body = [&](auto bufc, auto morec, int step) {
-    constexpr int q = decltype(bufc)::value;
-    constexpr bool more = decltype(morec)::value;
-    if (more) {
-      load_x(std::integral_constant<int, q ^ 1>{}, step + 1);
-      // everything but the loads just issued has landed: this step's rows, direction and Vb stage
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kRegLoads) : "memory");
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-    const char* stage = &s_vb[q][0];
-    bf16x8 fb[2][NBB > 0 ? NBB : 1];
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int b = 0; b < NBB; ++b) fb[h][b] = *(const bf16x8*)(stage + (h * NBB + b) * 1024 + rd_off);
-    if (more && NBB > 0) issue_vb(q ^ 1, step + 1);
-#pragma unroll
-    for (int h = 0; h < 2; ++h)
+      for (int b = 0; b < NBB; ++b) fb[b] = *(const bf16x8*)(stage + (h * NBB + b) * 1024 + rd_off);
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb) {
-        if (kDir) acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[q][h][rb], fv[q][h], acc[rb][0], 0, 0, 0);
+        if (kDir) acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[h][rb], fv[h], acc[rb][0], 0, 0, 0);
 #pragma unroll
         for (int b = 0; b < NBB; ++b)
-          acc[rb][b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[q][h][rb], fb[h][b], acc[rb][b + 1], 0, 0, 0);
+          acc[rb][b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[h][rb], fb[b], acc[rb][b + 1], 0, 0, 0);
       }
-  };
-  using B0 = std::integral_constant<int, 0>;
-  using B1 = std::integral_constant<int, 1>;
-
-  load_x(B0{}, 0);
-  if (NBB > 0) issue_vb(0, 0);
-  int step = 0;
-  for (; step + 2 < nsteps; step += 2) {
-    body(B0{}, std::true_type{}, step);
-    body(B1{}, std::true_type{}, step + 1);
-  }
-  if (step + 2 == nsteps) {   // one or two steps are left; the last one prefetches nothing
-    body(B0{}, std::true_type{}, step);
-    body(B1{}, std::false_type{}, step + 1);
-  } else {
-    body(B0{}, std::false_type{}, step);
+    }
   }
   if (!live) return;
 
