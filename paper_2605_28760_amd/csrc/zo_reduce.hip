@@ -97,13 +97,20 @@ __global__ __launch_bounds__(64) void k_cand_sum(ScoreCombineArgs a) {
 __global__ __launch_bounds__(1024) void k_active_rows(const int32_t* targets, int T, int32_t* rows, int32_t* pos,
                                                       int32_t* n_rows) {
   __shared__ int s_tot[16];
+  constexpr int U = 8;   // 64-token pieces loaded together (independent loads: one round trip per 512 tokens)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int per_wave = ((T + 15) / 16 + 63) / 64 * 64;
   const int lo = min(wave * per_wave, T), hi = min(lo + per_wave, T);
   int cnt = 0;
-  for (int t0 = lo; t0 < hi; t0 += 64) {
-    const int t = t0 + lane;
-    cnt += __popcll(__ballot(t < hi && targets[t] >= 0));
+  for (int t0 = lo; t0 < hi; t0 += 64 * U) {
+    bool on[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * 64 + lane;
+      on[u] = t < hi && targets[t] >= 0;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) cnt += __popcll(__ballot(on[u]));
   }
   if (lane == 0) s_tot[wave] = cnt;
   __syncthreads();
@@ -112,14 +119,22 @@ __global__ __launch_bounds__(1024) void k_active_rows(const int32_t* targets, in
     if (w < wave) base += s_tot[w];
     total += s_tot[w];
   }
-  for (int t0 = lo; t0 < hi; t0 += 64) {
-    const int t = t0 + lane;
-    const bool on = t < hi && targets[t] >= 0;
-    const uint64_t m = __ballot(on);
-    const int before = __popcll(m & ((1ull << lane) - 1ull));
-    if (t < hi) pos[t] = base + before;
-    if (on) rows[base + before] = t;
-    base += __popcll(m);
+  for (int t0 = lo; t0 < hi; t0 += 64 * U) {
+    bool on[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * 64 + lane;
+      on[u] = t < hi && targets[t] >= 0;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * 64 + lane;
+      const uint64_t m = __ballot(on[u]);
+      const int before = __popcll(m & ((1ull << lane) - 1ull));
+      if (t < hi) pos[t] = base + before;
+      if (on[u]) rows[base + before] = t;
+      base += __popcll(m);
+    }
   }
   if (threadIdx.x == 0) *n_rows = total;
 }
