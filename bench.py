@@ -63,7 +63,7 @@ def main():
                     help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by sequences; see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (the path shards by sequences, one replica per GPU); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
 

@@ -45,10 +45,9 @@ constexpr int kThreads = kWaves * 64;
 constexpr int RB = 8;                             // 16-row blocks per wave: 128 weight rows
 constexpr int CB = 4;                             // 16-token blocks per wave: 64 tokens
 constexpr int kLPW = 32 / kWaves;                 // direct-to-LDS loads per wave per operand tile
-#ifndef ZO_LOADS_AFTER_BARRIER
-#define ZO_LOADS_AFTER_BARRIER 8
-#endif
-constexpr int kLoadsLate = ZO_LOADS_AFTER_BARRIER;   // loads of a K tile issued in the k-step after the barrier
+// All 8 loads of a K tile are issued in the k-step right after the barrier, which gives them a whole
+// K-tile period to land (issuing half of them half a period later measured 3-9 % slower).
+constexpr int kLoadsLate = 2 * kLPW;                 // loads of a K tile issued in the k-step after the barrier
 constexpr int kLoadsEarly = 2 * kLPW - kLoadsLate;   // ... and in the k-step before the next barrier
 
 typedef __attribute__((address_space(3))) void lds_void;
