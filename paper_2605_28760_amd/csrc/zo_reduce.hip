@@ -19,12 +19,23 @@ __global__ __launch_bounds__(256) void k_tok_nll(ScoreCombineArgs a) {
   float M = -INFINITY, S = 0.0f;
   const int at = (t < a.T && a.pos) ? a.pos[t] : t;   // where this token's partials are
   if (t < a.T && a.targets[t] >= 0) {
-    for (int j = j0; j < a.n_vt; j += 8) {
-      const float m = a.part_max[(int64_t)j * a.T + at];
-      const float s = a.part_sum[(int64_t)j * a.T + at];
-      const float Mn = fmaxf(M, m);
-      if (Mn > -INFINITY) S = S * expf(M - Mn) + s * expf(m - Mn);
-      M = Mn;
+    // four tiles per trip so that their loads are in flight together; merged in the same order as one by one
+    for (int j = j0; j < a.n_vt; j += 32) {
+      float m[4], s[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int jj = j + 8 * u;
+        const bool in = jj < a.n_vt;
+        m[u] = in ? a.part_max[(int64_t)jj * a.T + at] : -INFINITY;
+        s[u] = in ? a.part_sum[(int64_t)jj * a.T + at] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j + 8 * u >= a.n_vt) break;
+        const float Mn = fmaxf(M, m[u]);
+        if (Mn > -INFINITY) S = S * expf(M - Mn) + s[u] * expf(m[u] - Mn);
+        M = Mn;
+      }
     }
   }
   s_m[j0][tl] = M;
@@ -97,18 +108,18 @@ __global__ __launch_bounds__(64) void k_cand_sum(ScoreCombineArgs a) {
 __global__ __launch_bounds__(1024) void k_active_rows(const int32_t* targets, int T, int32_t* rows, int32_t* pos,
                                                       int32_t* n_rows) {
   __shared__ int s_tot[16];
-  constexpr int U = 8;   // 64-token pieces loaded together (independent loads: one round trip per 512 tokens)
+  constexpr int U = 16;  // 64-token pieces loaded together (independent loads: one round trip per 1024 tokens)
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int per_wave = ((T + 15) / 16 + 63) / 64 * 64;
   const int lo = min(wave * per_wave, T), hi = min(lo + per_wave, T);
   int cnt = 0;
   for (int t0 = lo; t0 < hi; t0 += 64 * U) {
+    int32_t tg[U];
     bool on[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int t = t0 + u * 64 + lane;
-      on[u] = t < hi && targets[t] >= 0;
-    }
+    for (int u = 0; u < U; ++u) tg[u] = targets[min(t0 + u * 64 + lane, T - 1)];   // unconditional: the loads go out together
+#pragma unroll
+    for (int u = 0; u < U; ++u) on[u] = t0 + u * 64 + lane < hi && tg[u] >= 0;
 #pragma unroll
     for (int u = 0; u < U; ++u) cnt += __popcll(__ballot(on[u]));
   }
@@ -120,12 +131,12 @@ __global__ __launch_bounds__(1024) void k_active_rows(const int32_t* targets, in
     total += s_tot[w];
   }
   for (int t0 = lo; t0 < hi; t0 += 64 * U) {
+    int32_t tg[U];
     bool on[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int t = t0 + u * 64 + lane;
-      on[u] = t < hi && targets[t] >= 0;
-    }
+    for (int u = 0; u < U; ++u) tg[u] = targets[min(t0 + u * 64 + lane, T - 1)];   // unconditional: the loads go out together
+#pragma unroll
+    for (int u = 0; u < U; ++u) on[u] = t0 + u * 64 + lane < hi && tg[u] >= 0;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int t = t0 + u * 64 + lane;
