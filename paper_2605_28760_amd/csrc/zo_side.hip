@@ -49,9 +49,12 @@ __global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownA
   const int kchunk = a.n / a.ksplit;
   const int k_begin = split * kchunk;
   constexpr int kstride = 64;
-  const int nsteps = kchunk / kstride;
+  const int nsteps_all = kchunk / kstride;
   const bool has_dir = kDir && it.kind >= 0;
   const bool work = live && it.kind != kKindForeground;   // wave-uniform; foreground rows are not read at all
+  // a workgroup whose four items are all foreground (or absent) has nothing to multiply: it skips the
+  // K loop and only writes its zeros
+  const bool wg_work = __syncthreads_or(work) != 0;
 
   // per-lane addresses: 16 B at (row, k + h*32 + lg*8)
   const bf16_t* pa[4];
@@ -90,6 +93,7 @@ __global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownA
 
   // Refilling stage (step+1)&1 is safe once a wave is past barrier `step`: every wave has then
   // finished the MFMAs of step-1, the last reader of that stage.
+  const int nsteps = wg_work ? nsteps_all : 0;
   for (int step = 0; step < nsteps; ++step) {
     bf16x8 fa[2][4], fv[2];   // [half][row block], [half]
     if (work) {
