@@ -32,7 +32,7 @@ typedef __attribute__((address_space(3))) void lds_void;
 // is slower (3.0 against 4.3 TB/s: the loads of a step already fill the memory pipeline), as are
 // steps of 32 or 128, items of 16 or 32 rows, and a third workgroup per CU (register spills).
 template <int NBB, bool kDir>
-__global__ __launch_bounds__(256, (NBB <= 4 ? 2 : 1)) void k_side_down(SideDownArgs a, int cb0) {
+__global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   // Vb stage: [half h of the K step][16-col block][col][4 chunks of 16 B], chunk index XOR (col>>2)&3
   __shared__ __attribute__((aligned(1024))) char s_vb[2][NBB > 0 ? NBB * 2048 : 16];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
