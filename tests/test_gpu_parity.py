@@ -432,3 +432,33 @@ def test_bf16_probe_linear_odd_shapes(case):
     _per_layer_parity(w, d)
     y32 = to_np(DeviceWorkload(w, DEV, out_dtype="f32").probe_linear(0))
     assert_close(y32, oracle_layer(w, 0, w.layers[0].X, out_dtype="f32"), 2e-2, "fp32 output")
+
+
+def test_scoring_with_an_input_pitch_beyond_the_gather_window():
+    """H spanning 2 GiB or more (here through a large row pitch) cannot be addressed through the
+    scored-token list; the head then multiplies every row.  Same results, same rules for unscored rows."""
+    T, d, V, ld = 4200, 128, 333, 1 << 18                  # 4200 rows x 512 KiB pitch = 2.05 GiB
+    rng = np.random.default_rng(21)
+    Hh = wl.as_bf16_values(rng.standard_normal((T, d)).astype(np.float32))
+    Wh = wl.as_bf16_values((rng.standard_normal((V, d)) / np.sqrt(d)).astype(np.float32))
+    tg = rng.integers(0, V, T).astype(np.int32)
+    tg[::5] = -1
+    big = torch.empty((T, ld), dtype=torch.bfloat16, device=DEV)
+    big[:, :d] = torch.from_numpy(Hh).to(DEV).to(torch.bfloat16)
+    W = torch.from_numpy(Wh).to(DEV).to(torch.bfloat16)
+    lens = [1000, 1200, 0, 2000]
+    cu = np.zeros(5, np.int32); cu[1:] = np.cumsum(lens)
+    b = DeviceBatch(cu, np.array([0, 1, 0, -1], np.int32), np.array([0, 0], np.int32), np.array([1.0, -1.0], np.float32),
+                    np.array([7], np.uint64), DEV)
+    wsb = zb.zo_score_workspace_bytes(T, 4, V, d, zb.ZO_BF16)
+    ws = torch.empty(wsb, dtype=torch.uint8, device=DEV)
+    tok = torch.empty(T, device=DEV); seq = torch.empty(4, device=DEV)
+    cs = torch.empty(2, device=DEV); cc = torch.empty(2, dtype=torch.int32, device=DEV)
+    zb.zo_score(b.struct, big, ld, W, d, V, d, zb.ZO_BF16, torch.from_numpy(tg).to(DEV), tok, seq, cs, cc, ws, wsb); _sync()
+    ob = zo.Batch(cu, np.array([0, 1, 0, -1], np.int32), np.array([0, 0], np.int32), np.array([1.0, -1.0], np.float32),
+                  np.array([7], np.uint64))
+    otok, oseq, ocs, occ = zo.score(ob, Hh, Wh, tg)
+    assert_close(to_np(tok), otok, 1e-4, "tok_nll", atol=1e-4)
+    assert_close(to_np(seq), oseq, 1e-4, "seq_nll", atol=1e-3)
+    assert_close(to_np(cs), ocs, 1e-4, "cand_sum", atol=1e-3)
+    assert np.array_equal(to_np(cc), occ) and np.all(to_np(tok)[::5] == 0)
