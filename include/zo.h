@@ -308,6 +308,52 @@ int32_t zo_bank_update_scheduled(zo_bank* bank, int32_t m, int32_t n, int32_t r,
 int32_t zo_fold_bank(zo_bank* bank, void* W, int64_t ldw, int32_t m, int32_t n, zo_dtype dtype,
                      void* stream);
 
+/*
+ * ---- What joins the probe linears of a decoder block ------------------------
+ * A candidate's scoring pass (Sec. 2.2: a query is a teacher-forced scoring
+ * pass of the model under the candidate's weights) runs whole decoder blocks.
+ * The probed tensors are the block's linear layers (Sec. 3.2); normalisation,
+ * causal self-attention inside each packed sequence (Sec. 3.1) and the residual
+ * sums carry no perturbed parameters, are the same for every candidate and so
+ * take no candidate table.  The paper does not spell these operations out;
+ * they follow the standard definitions of the model families it evaluates.
+ */
+typedef enum zo_norm { ZO_LAYER_NORM = 0, ZO_RMS_NORM = 1 } zo_norm;
+
+/*
+ * Residual sum and normalisation of packed rows:
+ *   h = X + R                      (R NULL: h = X)
+ *   ZO_LAYER_NORM  Y = (h - mean(h)) / sqrt(var(h) + norm_eps) * gamma + beta   (biased variance)
+ *   ZO_RMS_NORM    Y = h / sqrt(mean(h^2) + norm_eps) * gamma                   (beta ignored)
+ * X, R, Hsum, Y: [n_tokens x d] of type dtype with leading dimensions ldx,
+ * ldr, ldh, ldy; gamma, beta: fp32 [d] (beta may be NULL).  Hsum (optional,
+ * needs R) receives h rounded to dtype, and it is that rounded h which is
+ * normalised; Hsum may alias X or R.  Y is optional (NULL: only the sum is
+ * written); Hsum and Y may not both be NULL.  fp32 arithmetic, moments by the
+ * two-pass formula.  No workspace.
+ */
+int32_t zo_add_norm(const void* X, int64_t ldx, const void* R, int64_t ldr,
+                    const float* gamma, const float* beta, int32_t kind, float norm_eps,
+                    int32_t n_tokens, int32_t d, zo_dtype dtype,
+                    void* Hsum, int64_t ldh, void* Y, int64_t ldy, void* stream);
+
+/*
+ * Causal self-attention over the packed sequences of `batch` (only n_tokens,
+ * n_seqs and cu_seqlens are read): for row t of sequence i and query head h,
+ *   O[t, h] = sum_j softmax_j(scale * <Q[t, h], K[j, g]>) V[j, g],
+ *   j over rows cu[i] .. t of the same sequence,  g = h / (n_heads / n_kv_heads).
+ * Q, O: [n_tokens x n_heads*head_dim]; K, V: [n_tokens x n_kv_heads*head_dim];
+ * each with its own leading dimension, so the three may be column ranges of
+ * one fused projection output.  O must not overlap Q, K or V.
+ * ZO_BF16: head_dim must be 128; products on bf16 MFMA with fp32 accumulation,
+ * softmax in fp32, weights rounded to bf16 before the second product.
+ * ZO_F32: head_dim <= 256, fp32 throughout.  No workspace.
+ */
+int32_t zo_attention(const zo_batch* batch, const void* Q, int64_t ldq, const void* K, int64_t ldk,
+                     const void* V, int64_t ldv, int32_t n_heads, int32_t n_kv_heads,
+                     int32_t head_dim, float scale, zo_dtype dtype, void* O, int64_t ldo,
+                     void* stream);
+
 #ifdef __cplusplus
 }
 #endif

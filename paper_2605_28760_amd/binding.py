@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libzo.so")
 
 ZO_F32, ZO_BF16 = 0, 1
 ZO_OK = 0
+ZO_LAYER_NORM, ZO_RMS_NORM = 0, 1
 ZO_ERR_NULL, ZO_ERR_SHAPE, ZO_ERR_INDEX, ZO_ERR_BANK_FULL = -1, -2, -3, -4
 ZO_ERR_WORKSPACE, ZO_ERR_UNSUPPORTED, ZO_ERR_HIP = -5, -6, -7
 
@@ -77,6 +78,12 @@ _PROTOS = {
     "zo_bank_update_scheduled": (C.c_int32, [C.POINTER(zo_bank), C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                                              C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_float, C.c_void_p,
                                              C.c_void_p, C.c_int32, C.c_int, C.c_void_p]),
+    "zo_add_norm": (C.c_int32, [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
+                                C.c_float, C.c_int32, C.c_int32, C.c_int, C.c_void_p, C.c_int64, C.c_void_p,
+                                C.c_int64, C.c_void_p]),
+    "zo_attention": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
+                                 C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int, C.c_void_p,
+                                 C.c_int64, C.c_void_p]),
 }
 EXPORTS = tuple(_PROTOS)
 
@@ -225,3 +232,13 @@ def zo_fold_bank(bank, W, ldw, m, n, dtype, stream=None):
 def zo_estimate_es(batch, cand_sum, cand_cnt, eps, reduction, cand_loss, proj_grad, stream=None):
     _check(lib().zo_estimate_es(C.byref(batch), _ptr(cand_sum), _ptr(cand_cnt), eps, reduction, _ptr(cand_loss),
                                 _ptr(proj_grad), _stream(stream)))
+
+
+def zo_add_norm(X, ldx, R, ldr, gamma, beta, kind, norm_eps, n_tokens, d, dtype, Hsum, ldh, Y, ldy, stream=None):
+    _check(lib().zo_add_norm(_ptr(X), ldx, _ptr(R), ldr, _ptr(gamma), _ptr(beta), kind, norm_eps, n_tokens, d,
+                             dtype, _ptr(Hsum), ldh, _ptr(Y), ldy, _stream(stream)))
+
+
+def zo_attention(batch, Q, ldq, K, ldk, V, ldv, n_heads, n_kv_heads, head_dim, scale, dtype, O, ldo, stream=None):
+    _check(lib().zo_attention(C.byref(batch), _ptr(Q), ldq, _ptr(K), ldk, _ptr(V), ldv, n_heads, n_kv_heads,
+                              head_dim, scale, dtype, _ptr(O), ldo, _stream(stream)))

@@ -496,4 +496,62 @@ int32_t zo_fold_bank(zo_bank* bank, void* W, int64_t ldw, int32_t m, int32_t n, 
   return ZO_OK;
 }
 
+int32_t zo_add_norm(const void* X, int64_t ldx, const void* R, int64_t ldr, const float* gamma, const float* beta,
+                    int32_t kind, float norm_eps, int32_t n_tokens, int32_t d, zo_dtype dtype, void* Hsum,
+                    int64_t ldh, void* Y, int64_t ldy, void* stream) {
+  if (n_tokens < 0 || d < 0) return fail(ZO_ERR_SHAPE, "n_tokens = %d, d = %d", n_tokens, d);
+  if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
+  if (kind != ZO_LAYER_NORM && kind != ZO_RMS_NORM) return fail(ZO_ERR_UNSUPPORTED, "normalisation kind %d", kind);
+  if (!(norm_eps >= 0.0f)) return fail(ZO_ERR_SHAPE, "norm_eps = %g", (double)norm_eps);
+  if (!Hsum && !Y) return fail(ZO_ERR_NULL, "Hsum and Y are both NULL: nothing to compute");
+  if (Hsum && !R) return fail(ZO_ERR_NULL, "Hsum given without a residual R");
+  if (n_tokens == 0 || d == 0) return ZO_OK;
+  if (!X) return fail(ZO_ERR_NULL, "X is NULL");
+  if (Y && !gamma) return fail(ZO_ERR_NULL, "gamma is NULL");
+  const uintptr_t elem_mask = dtype == ZO_BF16 ? 1u : 3u;
+  struct { const char* name; const void* p; int64_t ld; } mats[] = {
+      {"X", X, ldx}, {"R", R, ldr}, {"Hsum", Hsum, ldh}, {"Y", Y, ldy}};
+  for (const auto& mt : mats) {
+    if (!mt.p) continue;
+    if (ld_too_small(mt.ld, d))
+      return fail(ZO_ERR_SHAPE, "%s: leading dimension %lld invalid for %d columns", mt.name, (long long)mt.ld, d);
+    if (((uintptr_t)mt.p & elem_mask) != 0) return fail(ZO_ERR_SHAPE, "%s: pointer misaligned", mt.name);
+  }
+  zo::NormArgs a;
+  a.X = X; a.ldx = ldx; a.R = R; a.ldr = ldr; a.gamma = gamma; a.beta = beta; a.kind = kind; a.eps = norm_eps;
+  a.T = n_tokens; a.d = d; a.bf16 = dtype == ZO_BF16; a.Hsum = Hsum; a.ldh = ldh; a.Y = Y; a.ldy = ldy;
+  ZO_HIP(zo::launch_add_norm(a, (hipStream_t)stream), "zo_add_norm");
+  return ZO_OK;
+}
+
+int32_t zo_attention(const zo_batch* batch, const void* Q, int64_t ldq, const void* K, int64_t ldk, const void* V,
+                     int64_t ldv, int32_t n_heads, int32_t n_kv_heads, int32_t head_dim, float scale,
+                     zo_dtype dtype, void* O, int64_t ldo, void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
+  if (n_heads < 1 || n_kv_heads < 1 || head_dim < 1 || n_heads > 65535)
+    return fail(ZO_ERR_SHAPE, "n_heads = %d, n_kv_heads = %d, head_dim = %d", n_heads, n_kv_heads, head_dim);
+  if (n_heads % n_kv_heads != 0)
+    return fail(ZO_ERR_SHAPE, "n_heads = %d is not a multiple of n_kv_heads = %d", n_heads, n_kv_heads);
+  if (dtype == ZO_BF16 && head_dim != zo::attention_bf16_head_dim())
+    return fail(ZO_ERR_UNSUPPORTED, "the bf16 kernel covers head_dim %d only (head_dim = %d)",
+                zo::attention_bf16_head_dim(), head_dim);
+  if (dtype == ZO_F32 && head_dim > zo::attention_f32_max_head_dim())
+    return fail(ZO_ERR_UNSUPPORTED, "the fp32 kernel covers head_dim <= %d (head_dim = %d)",
+                zo::attention_f32_max_head_dim(), head_dim);
+  if ((int64_t)n_heads * head_dim > kMaxLd) return fail(ZO_ERR_SHAPE, "n_heads * head_dim too large");
+  if (batch->n_tokens == 0) return ZO_OK;
+  if (!Q || !K || !V || !O) return fail(ZO_ERR_NULL, "Q, K, V or O is NULL");
+  if (int32_t st = check_matrix("Q", Q, ldq, n_heads * head_dim, dtype)) return st;
+  if (int32_t st = check_matrix("K", K, ldk, n_kv_heads * head_dim, dtype)) return st;
+  if (int32_t st = check_matrix("V", V, ldv, n_kv_heads * head_dim, dtype)) return st;
+  if (int32_t st = check_matrix("O", O, ldo, n_heads * head_dim, dtype)) return st;
+  zo::AttnArgs a;
+  a.Q = Q; a.ldq = ldq; a.K = K; a.ldk = ldk; a.V = V; a.ldv = ldv; a.O = O; a.ldo = ldo;
+  a.cu = batch->cu_seqlens; a.S = batch->n_seqs; a.T = batch->n_tokens;
+  a.n_heads = n_heads; a.group = n_heads / n_kv_heads; a.dh = head_dim; a.scale = scale; a.bf16 = dtype == ZO_BF16;
+  ZO_HIP(zo::launch_attention(a, (hipStream_t)stream), "zo_attention");
+  return ZO_OK;
+}
+
 }  // extern "C"

@@ -179,4 +179,31 @@ struct FoldArgs {
 };
 hipError_t launch_fold_bank(const FoldArgs& a, hipStream_t st);
 
+// ---- zo_block.hip (what joins the probe linears of a decoder block) --------------------
+struct NormArgs {
+  const void* X; int64_t ldx;       // [T][d]
+  const void* R; int64_t ldr;       // optional residual added to X first
+  const float* gamma; const float* beta;   // beta may be null
+  int kind;                         // 0 layer norm, 1 RMS norm
+  float eps;
+  int T, d, bf16;
+  void* Hsum; int64_t ldh;          // optional: X + R (may alias X)
+  void* Y; int64_t ldy;             // optional: the normalised rows
+};
+hipError_t launch_add_norm(const NormArgs& a, hipStream_t st);
+
+struct AttnArgs {
+  const void* Q; int64_t ldq;       // [T][n_heads * dh]
+  const void* K; int64_t ldk;       // [T][n_kv_heads * dh]
+  const void* V; int64_t ldv;
+  void* O; int64_t ldo;             // [T][n_heads * dh]
+  const int32_t* cu; int S, T;
+  int n_heads, group, dh;           // group = n_heads / n_kv_heads
+  float scale;
+  int bf16;
+};
+int attention_f32_max_head_dim();
+int attention_bf16_head_dim();
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+
 }  // namespace zo

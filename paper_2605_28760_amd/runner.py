@@ -48,6 +48,8 @@ class DeviceLayer:
         self.name, self.m, self.n, self.tensor_id, self.act = layer.name, layer.m, layer.n, layer.tensor_id, layer.act
         self.W = torch.from_numpy(layer.W).to(device=device, dtype=_tt(dtype)).contiguous()
         self.X = None if layer.X is None else torch.from_numpy(layer.X).to(device=device, dtype=_tt(dtype)).contiguous()
+        bias = getattr(layer, "bias", None)
+        self.bias = None if bias is None else torch.from_numpy(np.ascontiguousarray(bias, np.float32)).to(device)
         self.bank = None
         self.P = self.Vb = None
         if layer.P is not None:
@@ -90,7 +92,7 @@ class DeviceWorkload:
         l = self.layers[i]
         x = X if X is not None else (l.X if l.X is not None else (self.X if i == 0 else self.Y[i - 1]))
         y = self.Y[i]
-        zb.zo_probe_linear((batch or self.batch).struct, x, x.stride(0), l.W, l.W.stride(0), None, l.m, l.n,
+        zb.zo_probe_linear((batch or self.batch).struct, x, x.stride(0), l.W, l.W.stride(0), l.bias, l.m, l.n,
                            _dt(self.dtype), self.w.r, float(self.w.eps), l.tensor_id, l.bank, l.act,
                            y, y.stride(0), _dt(self.out_dtype), self.ws, self.ws_bytes, stream)
         return y
@@ -124,6 +126,50 @@ class DeviceWorkload:
                     if l.bank is not None and l.bank.R_used >= self.w.r * self.batch.K:
                         col0 = np.arange(self.batch.K, dtype=np.int32) * self.w.r
                         self.bank_update(i, lr, col0, 0, stream=stream)
+
+
+class DeviceBlock:
+    """One pre-norm decoder block on a DeviceWorkload built from workloads.decoder_block: sequences
+    zo_add_norm -> zo_probe_linear(qkv) -> zo_attention -> zo_probe_linear(o) -> zo_add_norm ->
+    zo_probe_linear(fc1) -> zo_probe_linear(fc2) -> zo_add_norm (sum only)."""
+
+    def __init__(self, d):
+        self.d = d
+        blk = d.w.meta["block"]
+        self.blk = blk
+        dev, tt = d.device, _tt(d.dtype)
+        up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
+        self.g1, self.b1, self.g2, self.b2 = up(blk.g1), up(blk.b1), up(blk.g2), up(blk.b2)
+        T, hidden = d.batch.T, d.layers[0].n
+        self.hidden = hidden
+        self.a1, self.h1, self.a2, self.h2 = (torch.empty((T, hidden), device=dev, dtype=tt) for _ in range(4))
+        self.att = torch.empty((T, blk.n_heads * blk.head_dim), device=dev, dtype=tt)
+
+    def add_norm(self, x, res, gamma, beta, hsum, y, stream=None):
+        ld = lambda t: 0 if t is None else t.stride(0)
+        zb.zo_add_norm(x, ld(x), res, ld(res), gamma, beta, self.blk.norm_kind, float(self.blk.norm_eps),
+                       x.shape[0], x.shape[1], _dt(self.d.dtype), hsum, ld(hsum), y, ld(y), stream)
+
+    def attention(self, qkv, out, stream=None, batch=None):
+        b = self.blk
+        nq, nkv = b.n_heads * b.head_dim, b.n_kv_heads * b.head_dim
+        q, k, v = qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:]
+        zb.zo_attention((batch or self.d.batch).struct, q, qkv.stride(0), k, qkv.stride(0), v, qkv.stride(0),
+                        b.n_heads, b.n_kv_heads, b.head_dim, float(b.scale), _dt(self.d.dtype), out,
+                        out.stride(0), stream)
+
+    def forward(self, X=None, stream=None):
+        d = self.d
+        x = d.X if X is None else X
+        self.add_norm(x, None, self.g1, self.b1, None, self.a1, stream)
+        qkv = d.probe_linear(0, self.a1, stream)
+        self.attention(qkv, self.att, stream)
+        o = d.probe_linear(1, self.att, stream)
+        self.add_norm(x, o, self.g2, self.b2, self.h1, self.a2, stream)
+        d.probe_linear(2, self.a2, stream)
+        f2 = d.probe_linear(3, d.Y[2], stream)
+        self.add_norm(self.h1, f2, None, None, self.h2, None, stream)
+        return self.h2
 
 
 class LoopDriver:

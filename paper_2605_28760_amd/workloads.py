@@ -20,7 +20,7 @@ from typing import Dict, List, Optional
 import numpy as np
 
 # tags of the independent random streams
-_TAG_X, _TAG_W, _TAG_HEAD, _TAG_TGT, _TAG_P, _TAG_VB, _TAG_LEN, _TAG_PERM = range(8)
+_TAG_X, _TAG_W, _TAG_HEAD, _TAG_TGT, _TAG_P, _TAG_VB, _TAG_LEN, _TAG_PERM, _TAG_BIAS, _TAG_NORM = range(10)
 
 
 def _rng(cfg, tag, sub=0):
@@ -52,6 +52,7 @@ class Layer:
     Vb: Optional[np.ndarray] = None   # [n, R_cap] fp32
     R_used: int = 0
     X: Optional[np.ndarray] = None    # own input [T, n] when layers are timed separately
+    bias: Optional[np.ndarray] = None  # fp32 [m]
 
 
 @dataclass
@@ -261,5 +262,68 @@ def subset_sequences(w: Workload, seq_ids):
     return out
 
 
+@dataclass
+class Block:
+    """Parameters of one pre-norm decoder block whose four linears (fused q/k/v
+    projection, output projection, fc1, fc2) are probed.  The layers are also
+    workload.layers[0..3], in that order."""
+    norm_kind: int              # 0 layer norm, 1 RMS norm
+    norm_eps: float
+    g1: np.ndarray              # fp32 [hidden]
+    b1: Optional[np.ndarray]
+    g2: np.ndarray
+    b2: Optional[np.ndarray]
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    scale: float
+    qkv: Layer
+    o: Layer
+    fc1: Layer
+    fc2: Layer
+
+
+def decoder_block(name, cfg, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, r, eps, R,
+                  batch):
+    """A decoder block on the given batch (the tuple _pair_batch returns): unit-variance input rows,
+    weights N(0, 1/fan_in), norm gains around 1, small biases, banks as in the chain workloads."""
+    cu, seq_cand, cand_dir, cand_sign, seq_ex, seq_len_a = batch
+    K = int(cand_dir.max()) + 1
+    X = _replicated_rows(cfg, _TAG_X, seq_ex, seq_len_a, hidden, 1.0, dtype)
+    shapes = [("qkv", (n_heads + 2 * n_kv_heads) * head_dim, hidden, 0), ("o", hidden, n_heads * head_dim, 0),
+              ("fc1", ffn, hidden, 1), ("fc2", hidden, ffn, 0)]
+    layers = []
+    for i, (nm, m, n, act) in enumerate(shapes):
+        W = _normal(cfg, _TAG_W, i, (m, n), n ** -0.5, dtype)
+        P, Vb = _bank(cfg, i, m, n, R)
+        bias = _normal(cfg, _TAG_BIAS, i, (m,), 0.1, "f32") if with_bias else None
+        layers.append(Layer(nm, m, n, 2 * i, W, act, P, Vb, R, None, bias))
+    gains = [np.float32(1) + _normal(cfg, _TAG_NORM, j, (hidden,), 0.1, "f32") for j in range(2)]
+    shifts = [_normal(cfg, _TAG_NORM, 2 + j, (hidden,), 0.1, "f32") if norm_kind == 0 else None for j in range(2)]
+    blk = Block(norm_kind, 1e-5 if norm_kind == 0 else 1e-6, gains[0], shifts[0], gains[1], shifts[1],
+                n_heads, n_kv_heads, head_dim, float(head_dim) ** -0.5, *layers)
+    return Workload(name, cfg, dtype, r, eps, cu, seq_cand, cand_dir, cand_sign, _seeds(cfg, K), layers, False, X,
+                    None, None, 1, {"block": blk})
+
+
+def opt_block(hidden=5120, n_heads=40, head_dim=128, ffn=20480, n_ex=64, seq_len=128, r=8, eps=1e-3, R=64, cfg=5,
+              dtype="bf16"):
+    """One OPT-13B-shaped decoder block (layer norm, biases, 40 heads of 128) on the batch of config 3."""
+    batch = _pair_batch([seq_len] * n_ex, [0] * n_ex)
+    return decoder_block("b3-opt13b-block-b64", cfg, dtype, hidden, n_heads, n_heads, head_dim, ffn, 0, True, r, eps,
+                         R, batch)
+
+
+def qwen_block(hidden=4096, n_heads=32, n_kv_heads=8, head_dim=128, ffn=12288, n_ex=32, n_dirs=16, len_lo=16,
+               len_hi=512, r=16, eps=1e-3, R=128, cfg=6, dtype="bf16"):
+    """One Qwen3-8B-shaped decoder block (RMS norm, no biases, 32 query heads over 8 key/value heads)
+    on the ragged batch of config 4.  The MLP is the two-matrix fc1 -> ReLU -> fc2 of the chain
+    workloads, at the same shapes."""
+    lengths = _rng(cfg, _TAG_LEN).integers(len_lo, len_hi + 1, size=n_ex)
+    batch = _pair_batch(lengths, np.arange(n_ex) % n_dirs)
+    return decoder_block("b4-qwen3-block-ragged", cfg, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn, 1, False,
+                         r, eps, R, batch)
+
+
 BUILDERS = {"c1": tiny_fp32, "c2": opt_layer_set, "c3": opt_scoring, "c4": ragged_packed,
-            "c5": mixed_foreground}
+            "c5": mixed_foreground, "b3": opt_block, "b4": qwen_block}

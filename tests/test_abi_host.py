@@ -171,3 +171,46 @@ def test_fold_bank_validation():
     assert _status(fold, full, dt=5) == zb.ZO_ERR_UNSUPPORTED
     assert _status(fold, zb.make_bank(8, 9, FAKE, FAKE)) == zb.ZO_ERR_SHAPE
     fold(zb.make_bank(8, 0, None, None), W=None)          # an empty bank folds to nothing, without device work
+
+
+def test_add_norm_validation():
+    def norm(**k):
+        zb.zo_add_norm(k.get("X", FAKE), k.get("ldx", 64), k.get("R", FAKE), k.get("ldr", 64), k.get("gamma", FAKE),
+                       k.get("beta", None), k.get("kind", zb.ZO_RMS_NORM), k.get("eps", 1e-6), k.get("T", 4),
+                       k.get("d", 64), k.get("dt", zb.ZO_BF16), k.get("H", FAKE), k.get("ldh", 64), k.get("Y", FAKE),
+                       k.get("ldy", 64))
+    assert _status(norm, X=None) == zb.ZO_ERR_NULL
+    assert _status(norm, H=None, Y=None) == zb.ZO_ERR_NULL          # nothing to compute
+    assert _status(norm, R=None) == zb.ZO_ERR_NULL                  # a sum output without a residual
+    assert _status(norm, gamma=None) == zb.ZO_ERR_NULL
+    assert _status(norm, kind=2) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(norm, dt=4) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(norm, ldy=63) == zb.ZO_ERR_SHAPE
+    assert _status(norm, ldr=8) == zb.ZO_ERR_SHAPE
+    assert _status(norm, X=FAKE + 1) == zb.ZO_ERR_SHAPE
+    assert _status(norm, Y=FAKE + 2, dt=zb.ZO_F32) == zb.ZO_ERR_SHAPE
+    assert _status(norm, T=-1) == zb.ZO_ERR_SHAPE
+    assert _status(norm, eps=-1.0) == zb.ZO_ERR_SHAPE
+    norm(T=0, X=None)                                               # no rows: nothing is touched
+    norm(d=0, X=None)
+
+
+def test_attention_validation():
+    def att(batch=None, **k):
+        zb.zo_attention(batch or _host_batch(), k.get("Q", FAKE), k.get("ldq", 512), k.get("K", FAKE),
+                        k.get("ldk", 512), k.get("V", FAKE), k.get("ldv", 512), k.get("H", 4), k.get("Hkv", 2),
+                        k.get("dh", 128), 0.1, k.get("dt", zb.ZO_BF16), k.get("O", FAKE), k.get("ldo", 512))
+    assert _status(att, Q=None) == zb.ZO_ERR_NULL
+    assert _status(att, O=None) == zb.ZO_ERR_NULL
+    assert _status(att, H=3) == zb.ZO_ERR_SHAPE                     # not a multiple of the key/value heads
+    assert _status(att, H=0) == zb.ZO_ERR_SHAPE
+    assert _status(att, dh=64) == zb.ZO_ERR_UNSUPPORTED             # the bf16 kernel is built for 128
+    assert "head_dim" in zb.last_error()
+    assert _status(att, dh=512, dt=zb.ZO_F32, ldq=4096, ldk=4096, ldv=4096, ldo=4096) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(att, ldq=256) == zb.ZO_ERR_SHAPE
+    assert _status(att, ldk=128) == zb.ZO_ERR_SHAPE
+    assert _status(att, ldo=516) == zb.ZO_ERR_SHAPE                 # rows would lose 16-byte alignment
+    assert _status(att, V=FAKE + 2) == zb.ZO_ERR_SHAPE
+    assert _status(att, dt=7) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(att, _host_batch(lens=(3, 2), T=6)) == zb.ZO_ERR_INDEX
+    att(_host_batch(lens=(0, 0)), Q=None, O=None)                   # an empty batch needs no buffers

@@ -1,0 +1,291 @@
+"""GPU parity of what joins the probe linears of a decoder block (residual sum +
+normalisation, packed causal attention) and of a whole block, against the CPU
+oracle.  Tolerances as for the rest of the path: fp32 rel 1e-5, bf16 storage
+with fp32 accumulation rel 2e-2 (rel means |got - want| <= rtol * max(|want|,
+rms(want))); sums of two stored values are exact up to the storage rounding and
+are compared bit for bit."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import zo_block as ob
+from oracle import zo_oracle as zo
+from paper_2605_28760_amd import binding as zb
+from paper_2605_28760_amd import workloads as wl
+from paper_2605_28760_amd.runner import DeviceBatch, DeviceBlock, DeviceWorkload
+from zo_testlib import assert_close, oracle_batch, to_np
+
+DEV = "cuda:0"
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _dev(a, dtype):
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    return torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(DEV).to(tt)
+
+
+def _vals(a, dtype):
+    """The values the device holds for host array a."""
+    return wl.as_bf16_values(a).astype(np.float64) if dtype == "bf16" else np.asarray(a, np.float32).astype(np.float64)
+
+
+def _plain_batch(lens):
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    S = len(lens)
+    return DeviceBatch(cu, np.full(S, -1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32),
+                       np.zeros(0, np.uint64), DEV), cu
+
+
+# ------------------------------------------------------------------ add + norm
+
+def _run_add_norm(x, res, gamma, beta, kind, eps, dtype, want_sum=True, want_y=True, in_place=False, pad=0):
+    T, d = x.shape
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float32
+
+    def padded(a):
+        buf = torch.zeros((T, d + pad), device=DEV, dtype=tt)
+        buf[:, :d] = _dev(a, dtype)
+        return buf
+    X = padded(x)
+    R = None if res is None else padded(res)
+    H = (X if in_place else torch.full((T, d + pad), 7.0, device=DEV, dtype=tt)) if (want_sum and res is not None) else None
+    Y = torch.full((T, d + pad), 7.0, device=DEV, dtype=tt) if want_y else None
+    g = None if gamma is None else torch.from_numpy(np.asarray(gamma, np.float32)).to(DEV)
+    b = None if beta is None else torch.from_numpy(np.asarray(beta, np.float32)).to(DEV)
+    ld = lambda t: 0 if t is None else t.stride(0)
+    zb.zo_add_norm(X, ld(X), R, ld(R), g, b, kind, eps, T, d, zb.ZO_BF16 if dtype == "bf16" else zb.ZO_F32,
+                   H, ld(H), Y, ld(Y))
+    torch.cuda.synchronize()
+    if pad:
+        for t in (H, Y):       # columns past d are never written
+            if t is not None and not (in_place and t is H):
+                assert (to_np(t[:, d:]) == 7.0).all()
+    return (None if H is None else to_np(H[:, :d])), (None if Y is None else to_np(Y[:, :d]))
+
+
+@pytest.mark.parametrize("dtype,d,pad", [("f32", 77, 3), ("f32", 1024, 0), ("bf16", 256, 0), ("bf16", 4096, 8),
+                                         ("bf16", 5120, 0), ("bf16", 6144, 0), ("bf16", 8192, 0), ("bf16", 100, 2),
+                                         ("bf16", 8200, 0)])
+@pytest.mark.parametrize("kind", [ob.LAYER_NORM, ob.RMS_NORM])
+def test_add_norm_matches_oracle(dtype, d, pad, kind):
+    g = _rng(d * 10 + kind)
+    T = 37
+    x = g.normal(size=(T, d)) * 2 + 0.3
+    res = g.normal(size=(T, d))
+    gamma = 1 + 0.2 * g.normal(size=d)
+    beta = 0.1 * g.normal(size=d) if kind == ob.LAYER_NORM else None
+    eps = 1e-5
+    rtol = 1e-5 if dtype == "f32" else 2e-2
+    xv, rv = _vals(x, dtype), _vals(res, dtype)
+    gv = np.asarray(gamma, np.float32).astype(np.float64)
+    bv = None if beta is None else np.asarray(beta, np.float32).astype(np.float64)
+    # with a residual
+    want_h, want_y = ob.add_norm(xv, rv, gv, bv, kind, eps, dtype)
+    got_h, got_y = _run_add_norm(x, res, gamma, beta, kind, eps, dtype, pad=pad)
+    np.testing.assert_array_equal(got_h, want_h)
+    assert_close(got_y, want_y, rtol, "y")
+    # without one
+    _, want_y0 = ob.add_norm(xv, None, gv, bv, kind, eps, dtype)
+    _, got_y0 = _run_add_norm(x, None, gamma, beta, kind, eps, dtype, pad=pad)
+    assert_close(got_y0, want_y0, rtol, "y (no residual)")
+    # sum written over X itself; and the sum alone
+    got_h2, got_y2 = _run_add_norm(x, res, gamma, beta, kind, eps, dtype, in_place=True, pad=pad)
+    np.testing.assert_array_equal(got_h2, want_h)
+    np.testing.assert_array_equal(got_y2, got_y)
+    got_h3, none_y = _run_add_norm(x, res, None, None, kind, eps, dtype, want_y=False, pad=pad)
+    assert none_y is None
+    np.testing.assert_array_equal(got_h3, want_h)
+    # normalised rows without storing the sum
+    _, got_y4 = _run_add_norm(x, res, gamma, beta, kind, eps, dtype, want_sum=False, pad=pad)
+    np.testing.assert_array_equal(got_y4, got_y)
+
+
+def test_add_norm_moments_of_a_shifted_row():
+    """A common offset of 30 standard deviations must not spoil the variance: the one-pass formula
+    E[x^2] - E[x]^2 loses about 900 * 2^-24 of it in fp32, the two-pass moments do not."""
+    g = _rng(5)
+    d = 2048
+    x = (g.normal(size=(8, d)) + 30.0).astype(np.float32)
+    _, got = _run_add_norm(x, None, np.ones(d), np.zeros(d), ob.LAYER_NORM, 1e-5, "f32")
+    _, want = ob.add_norm(x.astype(np.float64), None, np.ones(d), np.zeros(d), ob.LAYER_NORM, 1e-5, "f32")
+    assert_close(got, want, 1e-5, "shifted rows")
+
+
+# ------------------------------------------------------------------ attention
+
+def _run_attention(q, k, v, lens, H, Hkv, dh, scale, dtype, fused=True):
+    batch, cu = _plain_batch(lens)
+    T = int(cu[-1])
+    nq, nkv = H * dh, Hkv * dh
+    tt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    zdt = zb.ZO_BF16 if dtype == "bf16" else zb.ZO_F32
+    out = torch.full((T, nq + 8), 3.0, device=DEV, dtype=tt)
+    if fused:    # q, k, v as column ranges of one projection output
+        qkv = torch.cat([_dev(q, dtype), _dev(k, dtype), _dev(v, dtype)], dim=1).contiguous()
+        Q, K, V = qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:]
+        lq = lk = lv = qkv.stride(0)
+    else:
+        Q, K, V = _dev(q, dtype), _dev(k, dtype), _dev(v, dtype)
+        lq, lk, lv = nq, nkv, nkv
+    zb.zo_attention(batch.struct, Q, lq, K, lk, V, lv, H, Hkv, dh, scale, zdt, out, out.stride(0))
+    torch.cuda.synchronize()
+    assert (to_np(out[:, nq:]) == 3.0).all()
+    return to_np(out[:, :nq]), cu
+
+
+ATT_CASES = [
+    # lens, heads, kv heads
+    ([1, 0, 130, 64, 257, 300, 128, 5], 2, 2),
+    ([129, 63, 65, 1, 1, 512], 4, 1),
+    ([700], 8, 2),
+    ([33] * 9, 3, 3),
+]
+
+
+@pytest.mark.parametrize("lens,H,Hkv", ATT_CASES)
+def test_attention_bf16_matches_oracle(lens, H, Hkv):
+    dh = 128
+    g = _rng(sum(lens) + H)
+    T = sum(lens)
+    q, k, v = g.normal(size=(T, H * dh)), g.normal(size=(T, Hkv * dh)), g.normal(size=(T, Hkv * dh))
+    scale = dh ** -0.5
+    got, cu = _run_attention(q, k, v, lens, H, Hkv, dh, scale, "bf16")
+    want = ob.attention(_vals(q, "bf16"), _vals(k, "bf16"), _vals(v, "bf16"), cu, H, Hkv, dh, scale, "bf16")
+    assert_close(got, want, 2e-2, "attention bf16")
+    # peaked scores (larger scale): the weights concentrate on few keys
+    got2, _ = _run_attention(q, k, v, lens, H, Hkv, dh, 0.5, "bf16", fused=False)
+    want2 = ob.attention(_vals(q, "bf16"), _vals(k, "bf16"), _vals(v, "bf16"), cu, H, Hkv, dh, 0.5, "bf16")
+    assert_close(got2, want2, 2e-2, "attention bf16, peaked")
+
+
+@pytest.mark.parametrize("lens,H,Hkv,dh", [([1, 0, 70, 64, 130, 5], 2, 2, 64), ([50, 3, 200], 4, 2, 80),
+                                            ([40, 41], 6, 1, 128), ([17], 1, 1, 256), ([9, 9], 2, 1, 24)])
+def test_attention_fp32_matches_oracle(lens, H, Hkv, dh):
+    g = _rng(sum(lens) + dh)
+    T = sum(lens)
+    q, k, v = g.normal(size=(T, H * dh)), g.normal(size=(T, Hkv * dh)), g.normal(size=(T, Hkv * dh))
+    got, cu = _run_attention(q, k, v, lens, H, Hkv, dh, dh ** -0.5, "f32")
+    want = ob.attention(_vals(q, "f32"), _vals(k, "f32"), _vals(v, "f32"), cu, H, Hkv, dh, dh ** -0.5, "f32")
+    assert_close(got, want, 1e-5, "attention fp32")
+
+
+def test_attention_bf16_closed_forms():
+    """Equal keys => causal prefix mean of the values; first row of a sequence => its own value."""
+    dh, H = 128, 2
+    lens = [200, 1, 77]
+    T = sum(lens)
+    g = _rng(3)
+    q = g.normal(size=(T, H * dh))
+    k = np.tile(g.normal(size=(1, H * dh)), (T, 1))
+    v = g.normal(size=(T, H * dh))
+    got, cu = _run_attention(q, k, v, lens, H, H, dh, 1.0, "bf16")
+    vv = _vals(v, "bf16")
+    for a, b in zip(cu[:-1], cu[1:]):
+        want = np.cumsum(vv[a:b], axis=0) / np.arange(1, b - a + 1)[:, None]
+        assert_close(got[a:b], want, 2e-2, "prefix mean")
+        np.testing.assert_array_equal(got[a], vv[a])
+
+
+def test_attention_rows_do_not_depend_on_the_rest_of_the_batch():
+    dh, H, Hkv = 128, 4, 2
+    lens = [150, 3, 260, 64]
+    T = sum(lens)
+    g = _rng(4)
+    q, k, v = g.normal(size=(T, H * dh)), g.normal(size=(T, Hkv * dh)), g.normal(size=(T, Hkv * dh))
+    packed, cu = _run_attention(q, k, v, lens, H, Hkv, dh, dh ** -0.5, "bf16")
+    again, _ = _run_attention(q, k, v, lens, H, Hkv, dh, dh ** -0.5, "bf16")
+    np.testing.assert_array_equal(packed, again)
+    for i in (0, 2, 3):
+        a, b = cu[i], cu[i + 1]
+        alone, _ = _run_attention(q[a:b], k[a:b], v[a:b], [b - a], H, Hkv, dh, dh ** -0.5, "bf16")
+        np.testing.assert_array_equal(alone, packed[a:b])
+
+
+def test_attention_empty_batches():
+    batch, _ = _plain_batch([0, 0])
+    dummy = torch.zeros((1, 128), device=DEV, dtype=torch.bfloat16)
+    zb.zo_attention(batch.struct, dummy, 128, dummy, 128, dummy, 128, 1, 1, 128, 1.0, zb.ZO_BF16, dummy, 128)
+    torch.cuda.synchronize()
+    assert (to_np(dummy) == 0).all()
+
+
+# ------------------------------------------------------------------ whole block
+
+def _stagewise_block_parity(w, rtol):
+    d = DeviceWorkload(w, DEV)
+    blk = DeviceBlock(d)
+    h2 = blk.forward()
+    torch.cuda.synchronize()
+    b = w.meta["block"]
+    ob_batch = oracle_batch(w)
+    nq, nkv = b.n_heads * b.head_dim, b.n_kv_heads * b.head_dim
+
+    def lin(l, x):
+        bank = None if l.P is None else zo.Bank(l.P, l.Vb, l.R_used)
+        return zo.probe_linear(ob_batch, x, l.W, w.r, w.eps, l.tensor_id, bank, bias=l.bias, act=l.act,
+                               factor_dtype=w.dtype, out_dtype=w.dtype)
+    # every stage of the oracle is fed the device's own input of that stage
+    got = dict(a1=to_np(blk.a1), qkv=to_np(d.Y[0]), att=to_np(blk.att), o=to_np(d.Y[1]), h1=to_np(blk.h1),
+               a2=to_np(blk.a2), f1=to_np(d.Y[2]), f2=to_np(d.Y[3]), h2=to_np(h2))
+    x = np.asarray(w.X, np.float64)
+    _, a1 = ob.add_norm(x, None, b.g1, b.b1, b.norm_kind, b.norm_eps, w.dtype)
+    assert_close(got["a1"], a1, rtol, "a1")
+    assert_close(got["qkv"], lin(b.qkv, got["a1"]), rtol, "qkv")
+    qkv = got["qkv"]
+    att = ob.attention(qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:], w.cu_seqlens, b.n_heads, b.n_kv_heads,
+                       b.head_dim, b.scale, w.dtype)
+    assert_close(got["att"], att, rtol, "att")
+    assert_close(got["o"], lin(b.o, got["att"]), rtol, "o")
+    h1, a2 = ob.add_norm(x, got["o"], b.g2, b.b2, b.norm_kind, b.norm_eps, w.dtype)
+    np.testing.assert_array_equal(got["h1"], h1)
+    assert_close(got["a2"], a2, rtol, "a2")
+    assert_close(got["f1"], lin(b.fc1, got["a2"]), rtol, "f1")
+    assert_close(got["f2"], lin(b.fc2, got["f1"]), rtol, "f2")
+    np.testing.assert_array_equal(got["h2"], zo._round_out(got["h1"].astype(np.float64) + got["f2"], w.dtype))
+    return got
+
+
+def _small_batch(lens, n_dirs, n_fg):
+    ex_dir = np.arange(len(lens) - n_fg) % n_dirs
+    return wl._pair_batch(lens[:len(lens) - n_fg], ex_dir, n_fg, lens[len(lens) - n_fg:])
+
+
+@pytest.mark.parametrize("norm_kind,bias,Hkv", [(0, True, 2), (1, False, 1)])
+def test_block_bf16_stage_by_stage_and_end_to_end(norm_kind, bias, Hkv):
+    batch = _small_batch([70, 131, 9, 200, 40], 2, 1)
+    w = wl.decoder_block("blk-small", 40 + norm_kind, "bf16", 256, 2, Hkv, 128, 512, norm_kind, bias, 8, 1e-3, 32, batch)
+    got = _stagewise_block_parity(w, 2e-2)
+    # end to end: the oracle's own chain of rounded intermediates.  Eight stages of bf16 storage
+    # each contribute up to one rounding of their output, so the bound is a small multiple of 2e-2.
+    want = ob.block_forward(oracle_batch(w), w.X, w.meta["block"], w.r, w.eps, "bf16")
+    assert_close(got["h2"], want["h2"], 4e-2, "h2 end to end")
+    assert_close(got["att"], want["att"], 4e-2, "att end to end")
+
+
+def test_block_fp32_stage_by_stage_and_end_to_end():
+    batch = _small_batch([33, 64, 5, 90], 1, 1)
+    w = wl.decoder_block("blk-small-f32", 50, "f32", 96, 3, 1, 32, 160, 0, True, 4, 1e-3, 8, batch)
+    got = _stagewise_block_parity(w, 1e-5)
+    want = ob.block_forward(oracle_batch(w), w.X, w.meta["block"], w.r, w.eps, "f32")
+    assert_close(got["h2"], want["h2"], 5e-5, "h2 end to end")     # eight chained fp32 stages
+
+
+def test_block_foreground_rows_bit_identical():
+    """Foreground sequences of a mixed batch must come out of the block exactly as from a batch
+    in which every sequence is foreground (Sec. 4, mixed-batch experiment)."""
+    batch = _small_batch([70, 131, 9, 200, 140], 2, 2)
+    w = wl.decoder_block("blk-mixed", 60, "bf16", 256, 2, 2, 128, 512, 0, True, 8, 1e-3, 32, batch)
+    d = DeviceWorkload(w, DEV)
+    mixed = to_np(DeviceBlock(d).forward())
+    wf = wl.foreground_only(w)
+    plain = to_np(DeviceBlock(DeviceWorkload(wf, DEV)).forward())
+    torch.cuda.synchronize()
+    fg_rows = np.concatenate([np.arange(w.cu_seqlens[s], w.cu_seqlens[s + 1]) for s in np.nonzero(w.seq_cand < 0)[0]])
+    np.testing.assert_array_equal(mixed[fg_rows], plain[fg_rows])
+    probe_rows = np.setdiff1d(np.arange(w.T), fg_rows)
+    assert np.abs(mixed[probe_rows] - plain[probe_rows]).max() > 0
