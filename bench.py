@@ -52,6 +52,63 @@ def _cpu_baseline(w, budget_hint_s=20.0):
                       % (n_seq, sub.T, w.T, dt)}, out, sub
 
 
+def _block_section(name, n_rep):
+    """Secondary: one decoder block (norm -> fused q/k/v probe linear -> packed causal attention -> output
+    probe linear -> residual + norm -> fc1 -> fc2 -> residual) at the model shapes of the main workload,
+    timed per stage with events on the launch stream."""
+    import numpy as np
+    import torch
+    from paper_2605_28760_amd import workloads as wl
+    from paper_2605_28760_amd.runner import DeviceBlock, DeviceWorkload
+    w = wl.BUILDERS[name]()
+    d = DeviceWorkload(w, "cuda:0")
+    blk = DeviceBlock(d)
+    b = w.meta["block"]
+    st = torch.cuda.current_stream()
+    x = d.X
+    stages = [
+        ("norm1", lambda: blk.add_norm(x, None, blk.g1, blk.b1, None, blk.a1, st)),
+        ("qkv", lambda: d.probe_linear(0, blk.a1, st)),
+        ("attention", lambda: blk.attention(d.Y[0], blk.att, st)),
+        ("o", lambda: d.probe_linear(1, blk.att, st)),
+        ("add_norm2", lambda: blk.add_norm(x, d.Y[1], blk.g2, blk.b2, blk.h1, blk.a2, st)),
+        ("fc1", lambda: d.probe_linear(2, blk.a2, st)),
+        ("fc2", lambda: d.probe_linear(3, d.Y[2], st)),
+        ("residual", lambda: blk.add_norm(blk.h1, d.Y[3], None, None, blk.h2, None, st)),
+    ]
+
+    def timed(fn):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(n_rep):
+            fn()
+        e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_rep
+    blk.forward(stream=st)
+    torch.cuda.synchronize()
+    ms = {nm: timed(fn) for nm, fn in stages}
+    block_ms = timed(lambda: blk.forward(stream=st))
+    T, hid = w.T, blk.hidden
+    lens = np.diff(w.cu_seqlens).astype(np.float64)
+    att_flops = 4.0 * b.n_heads * b.head_dim * float((lens * (lens + 1) / 2).sum())   # causal half only
+    att_bytes = 2.0 * T * (2 * b.n_heads + 2 * b.n_kv_heads) * b.head_dim              # q, k, v read, o written
+    gemm_flops = sum(2.0 * T * l.m * l.n for l in w.layers)
+    gemm_ms = ms["qkv"] + ms["o"] + ms["fc1"] + ms["fc2"]
+    return {"workload": w.name, "rows": T, "hidden": hid, "heads": [b.n_heads, b.n_kv_heads, b.head_dim],
+            "norm": "layer" if b.norm_kind == 0 else "rms", "block_ms": block_ms, "stage_ms": ms,
+            "tokens_per_s": T / (block_ms * 1e-3),
+            "attention": {"tflops_causal": att_flops / (ms["attention"] * 1e-3) / 1e12,
+                          "gbs": att_bytes / (ms["attention"] * 1e-3) / 1e9,
+                          "frac_hbm_peak": att_bytes / (ms["attention"] * 1e-3) / 1e9 / PEAK_HBM_GBS},
+            "norm_gbs": {"norm1": 2 * 2.0 * T * hid / (ms["norm1"] * 1e-3) / 1e9,
+                         "add_norm2": 4 * 2.0 * T * hid / (ms["add_norm2"] * 1e-3) / 1e9,
+                         "residual": 3 * 2.0 * T * hid / (ms["residual"] * 1e-3) / 1e9},
+            "probe_linears_tflops": gemm_flops / (gemm_ms * 1e-3) / 1e12,
+            "share_outside_probe_linears": 1.0 - gemm_ms / sum(ms.values())}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +116,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-block", action="store_true", help="skip the decoder-block secondary measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -198,6 +256,10 @@ def main():
         loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
                      "fold_all_layers_ms": e0.elapsed_time(e1)}
 
+    block_info = None
+    if not args.no_block:
+        block_info = _block_section({"c3": "b3"}.get(args.workload, "b4"), n_sec)
+
     seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
     seg_ms = seg.mean(axis=0)
     breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
@@ -235,6 +297,7 @@ def main():
         # native / matched-inference ratio
         "native_over_matched": ms_per_step / plain_ms,
         "loop": loop_info,
+        "block": block_info,
         "active_token_scoring": {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms},
         "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},
         # bytes the update step moves (P read + write per layer) against rewriting the dense weights

@@ -9,9 +9,10 @@ import pytest
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
+from oracle import zo_block as ob
 from oracle import zo_oracle as zo
 from paper_2605_28760_amd import workloads as wl
-from paper_2605_28760_amd.runner import DeviceWorkload
+from paper_2605_28760_amd.runner import DeviceBlock, DeviceWorkload
 from zo_testlib import assert_close, oracle_batch, oracle_layer, to_np
 
 DEV = "cuda:0"
@@ -152,3 +153,47 @@ def test_config3_active_token_scoring_full_size():
     tok = to_np(d.tok_nll)
     assert np.all(tok[tg < 0] == 0) and np.all(tok[on] > 0)
     assert np.array_equal(to_np(d.cand_cnt), np.array([1024, 1024]))
+
+
+def _check_block_full_size(w, seqs):
+    """One decoder block at full size: sampled rows of every stage against the oracle fed with the
+    device's own input of that stage; attention on whole sampled sequences, all heads."""
+    d = DeviceWorkload(w, DEV)
+    blk = DeviceBlock(d)
+    h2 = blk.forward()
+    torch.cuda.synchronize()
+    b = w.meta["block"]
+    rows = _sample_rows(w, n_cands=2, per_cand=6)
+    rows_t = torch.from_numpy(rows).to(DEV)
+    at = lambda t: to_np(t[rows_t])
+    x = np.asarray(w.X[rows], np.float64)
+    _, a1 = ob.add_norm(x, None, b.g1, b.b1, b.norm_kind, b.norm_eps, w.dtype)
+    assert_close(at(blk.a1), a1, 2e-2, "a1 sampled rows")
+    for i, inp in enumerate([blk.a1, blk.att, blk.a2, d.Y[2]]):
+        x_in = np.zeros((w.T, w.layers[i].n), dtype=np.float32)
+        x_in[rows] = at(inp)
+        assert_close(at(d.Y[i]), oracle_layer(w, i, x_in, rows=rows), 2e-2, "Y[%s] sampled rows" % w.layers[i].name)
+    h1, a2 = ob.add_norm(x, at(d.Y[1]), b.g2, b.b2, b.norm_kind, b.norm_eps, w.dtype)
+    np.testing.assert_array_equal(at(blk.h1), h1)
+    assert_close(at(blk.a2), a2, 2e-2, "a2 sampled rows")
+    np.testing.assert_array_equal(at(h2), zo._round_out(at(blk.h1).astype(np.float64) + at(d.Y[3]), w.dtype))
+    nq, nkv = b.n_heads * b.head_dim, b.n_kv_heads * b.head_dim
+    cu = w.cu_seqlens
+    for s_ in seqs:
+        lo, hi = int(cu[s_]), int(cu[s_ + 1])
+        qkv = to_np(d.Y[0][lo:hi])
+        want = ob.attention(qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:], [0, hi - lo], b.n_heads,
+                            b.n_kv_heads, b.head_dim, b.scale, w.dtype)
+        assert_close(to_np(blk.att[lo:hi]), want, 2e-2, "attention, sequence %d" % s_)
+    assert np.isfinite(to_np(h2)).all()
+
+
+def test_opt13b_block_full_size():
+    w = wl.opt_block()
+    _check_block_full_size(w, [0, 77, len(w.seq_cand) - 1])
+
+
+def test_qwen3_block_ragged_full_size():
+    w = wl.qwen_block()
+    lens = np.diff(w.cu_seqlens)
+    _check_block_full_size(w, [int(np.argmax(lens)), int(np.argmin(lens)), len(lens) // 2])

@@ -32,7 +32,7 @@ def oracle_bank(layer):
 
 def oracle_layer(w, i, X, rows=None, out_dtype=None):
     l = w.layers[i]
-    return zo.probe_linear(oracle_batch(w), X, l.W, w.r, w.eps, l.tensor_id, oracle_bank(l), act=l.act,
+    return zo.probe_linear(oracle_batch(w), X, l.W, w.r, w.eps, l.tensor_id, oracle_bank(l), bias=getattr(l, "bias", None), act=l.act,
                            factor_dtype=w.dtype, out_dtype=out_dtype or w.dtype, rows=rows)
 
 
