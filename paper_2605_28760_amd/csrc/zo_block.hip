@@ -34,83 +34,98 @@ __device__ __forceinline__ void block_barrier() {
 
 // ------------------------------------------------------------------ add + norm
 
-constexpr int kNormWaves = 4;   // rows per workgroup
+constexpr int kNormWaves = 4;   // waves per workgroup, one row each at a time
 
 // bf16 rows with d % 8 == 0 and d <= kChunks * 512: lane l owns the 8 elements starting at
 // (c*64 + l)*8 of chunk c.  Exact two-pass moments in fp32 on the register copy of the row.
+// A workgroup covers rows_per_wave * 4 consecutive rows; gamma and beta are staged once per
+// workgroup in LDS (re-reading them per row from L2 would move four times the bytes of the
+// row itself), in the order the lanes read them: the two 16-byte halves of a lane's 8 values
+// sit in separate planes so that consecutive lanes read consecutive 16-byte words.
 template <int kChunks>
-__global__ __launch_bounds__(kNormWaves* kWave) void k_add_norm_bf16(NormArgs a) {
+__global__ __launch_bounds__(kNormWaves* kWave) void k_add_norm_bf16(NormArgs a, int rows_per_wave) {
+  __shared__ __attribute__((aligned(16))) float s_gamma[kChunks * 512];
+  __shared__ __attribute__((aligned(16))) float s_beta[kChunks * 512];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row = blockIdx.x * kNormWaves + wave;
-  if (row >= a.T) return;
-  const bf16_t* x = (const bf16_t*)a.X + (int64_t)row * a.ldx;
-  const bf16_t* res = a.R ? (const bf16_t*)a.R + (int64_t)row * a.ldr : nullptr;
-  bf16_t* hs = a.Hsum ? (bf16_t*)a.Hsum + (int64_t)row * a.ldh : nullptr;
-  float v[kChunks][8];
-  float sum = 0.f, sumsq = 0.f;
-#pragma unroll
-  for (int c = 0; c < kChunks; ++c) {
-    const int e0 = (c * kWave + lane) * 8;
-    if (e0 < a.d) {
-      const u32x4 xv = *reinterpret_cast<const u32x4*>(x + e0);
-      u32x4 rv = {0u, 0u, 0u, 0u};
-      if (res) rv = *reinterpret_cast<const u32x4*>(res + e0);
-      u32x4 hv;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float lo = __uint_as_float(xv[i] << 16), hi = __uint_as_float(xv[i] & 0xFFFF0000u);
-        if (res) {
-          // the sum is stored as bf16, and it is that stored value which is normalised
-          const uint32_t p = pack_bf16x2(lo + __uint_as_float(rv[i] << 16), hi + __uint_as_float(rv[i] & 0xFFFF0000u));
-          hv[i] = p;
-          lo = __uint_as_float(p << 16);
-          hi = __uint_as_float(p & 0xFFFF0000u);
-        }
-        v[c][2 * i] = lo;
-        v[c][2 * i + 1] = hi;
-        sum += lo + hi;
-        sumsq += lo * lo + hi * hi;
-      }
-      if (res && hs) *reinterpret_cast<u32x4*>(hs + e0) = hv;
-    } else {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[c][i] = 0.f;
+  if (a.Y) {
+    for (int e = threadIdx.x * 4; e < a.d; e += kNormWaves * kWave * 4) {
+      const int at = (e >> 9) * 512 + ((e >> 2) & 1) * 256 + ((e & 511) >> 3) * 4;
+      *reinterpret_cast<float4*>(&s_gamma[at]) = *reinterpret_cast<const float4*>(a.gamma + e);
+      *reinterpret_cast<float4*>(&s_beta[at]) =
+          a.beta ? *reinterpret_cast<const float4*>(a.beta + e) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    __syncthreads();
   }
-  if (!a.Y) return;
   const float inv_d = 1.0f / (float)a.d;
-  float mean = 0.f, rstd;
-  if (a.kind == 0) {
-    mean = wave_sum(sum) * inv_d;
-    float dev = 0.f;
+  for (int it = 0; it < rows_per_wave; ++it) {
+    const int row = (blockIdx.x * rows_per_wave + it) * kNormWaves + wave;
+    if (row >= a.T) return;
+    const bf16_t* x = (const bf16_t*)a.X + (int64_t)row * a.ldx;
+    const bf16_t* res = a.R ? (const bf16_t*)a.R + (int64_t)row * a.ldr : nullptr;
+    bf16_t* hs = a.Hsum ? (bf16_t*)a.Hsum + (int64_t)row * a.ldh : nullptr;
+    float v[kChunks][8];
+    float sum = 0.f, sumsq = 0.f;
 #pragma unroll
-    for (int c = 0; c < kChunks; ++c)
-      if ((c * kWave + lane) * 8 < a.d) {
+    for (int c = 0; c < kChunks; ++c) {
+      const int e0 = (c * kWave + lane) * 8;
+      if (e0 < a.d) {
+        const u32x4 xv = *reinterpret_cast<const u32x4*>(x + e0);
+        u32x4 rv = {0u, 0u, 0u, 0u};
+        if (res) rv = *reinterpret_cast<const u32x4*>(res + e0);
+        u32x4 hv;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) dev += (v[c][i] - mean) * (v[c][i] - mean);
+        for (int i = 0; i < 4; ++i) {
+          float lo = __uint_as_float(xv[i] << 16), hi = __uint_as_float(xv[i] & 0xFFFF0000u);
+          if (res) {
+            // the sum is stored as bf16, and it is that stored value which is normalised
+            const uint32_t p =
+                pack_bf16x2(lo + __uint_as_float(rv[i] << 16), hi + __uint_as_float(rv[i] & 0xFFFF0000u));
+            hv[i] = p;
+            lo = __uint_as_float(p << 16);
+            hi = __uint_as_float(p & 0xFFFF0000u);
+          }
+          v[c][2 * i] = lo;
+          v[c][2 * i + 1] = hi;
+          sum += lo + hi;
+          sumsq += lo * lo + hi * hi;
+        }
+        if (res && hs) *reinterpret_cast<u32x4*>(hs + e0) = hv;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[c][i] = 0.f;
       }
-    rstd = 1.0f / sqrtf(wave_sum(dev) * inv_d + a.eps);
-  } else {
-    rstd = 1.0f / sqrtf(wave_sum(sumsq) * inv_d + a.eps);
-  }
-  bf16_t* y = (bf16_t*)a.Y + (int64_t)row * a.ldy;
+    }
+    if (!a.Y) continue;
+    float mean = 0.f, rstd;
+    if (a.kind == 0) {
+      mean = wave_sum(sum) * inv_d;
+      float dev = 0.f;
 #pragma unroll
-  for (int c = 0; c < kChunks; ++c) {
-    const int e0 = (c * kWave + lane) * 8;
-    if (e0 < a.d) {
-      const float4 g0 = *reinterpret_cast<const float4*>(a.gamma + e0);
-      const float4 g1 = *reinterpret_cast<const float4*>(a.gamma + e0 + 4);
-      float4 b0 = make_float4(0.f, 0.f, 0.f, 0.f), b1 = b0;
-      if (a.beta) {
-        b0 = *reinterpret_cast<const float4*>(a.beta + e0);
-        b1 = *reinterpret_cast<const float4*>(a.beta + e0 + 4);
+      for (int c = 0; c < kChunks; ++c)
+        if ((c * kWave + lane) * 8 < a.d) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) dev += (v[c][i] - mean) * (v[c][i] - mean);
+        }
+      rstd = 1.0f / sqrtf(wave_sum(dev) * inv_d + a.eps);
+    } else {
+      rstd = 1.0f / sqrtf(wave_sum(sumsq) * inv_d + a.eps);
+    }
+    bf16_t* y = (bf16_t*)a.Y + (int64_t)row * a.ldy;
+#pragma unroll
+    for (int c = 0; c < kChunks; ++c) {
+      const int e0 = (c * kWave + lane) * 8;
+      if (e0 < a.d) {
+        const float4 g0 = *reinterpret_cast<const float4*>(&s_gamma[c * 512 + lane * 4]);
+        const float4 g1 = *reinterpret_cast<const float4*>(&s_gamma[c * 512 + 256 + lane * 4]);
+        const float4 b0 = *reinterpret_cast<const float4*>(&s_beta[c * 512 + lane * 4]);
+        const float4 b1 = *reinterpret_cast<const float4*>(&s_beta[c * 512 + 256 + lane * 4]);
+        u32x4 o;
+        o[0] = pack_bf16x2((v[c][0] - mean) * rstd * g0.x + b0.x, (v[c][1] - mean) * rstd * g0.y + b0.y);
+        o[1] = pack_bf16x2((v[c][2] - mean) * rstd * g0.z + b0.z, (v[c][3] - mean) * rstd * g0.w + b0.w);
+        o[2] = pack_bf16x2((v[c][4] - mean) * rstd * g1.x + b1.x, (v[c][5] - mean) * rstd * g1.y + b1.y);
+        o[3] = pack_bf16x2((v[c][6] - mean) * rstd * g1.z + b1.z, (v[c][7] - mean) * rstd * g1.w + b1.w);
+        *reinterpret_cast<u32x4*>(y + e0) = o;
       }
-      u32x4 o;
-      o[0] = pack_bf16x2((v[c][0] - mean) * rstd * g0.x + b0.x, (v[c][1] - mean) * rstd * g0.y + b0.y);
-      o[1] = pack_bf16x2((v[c][2] - mean) * rstd * g0.z + b0.z, (v[c][3] - mean) * rstd * g0.w + b0.w);
-      o[2] = pack_bf16x2((v[c][4] - mean) * rstd * g1.x + b1.x, (v[c][5] - mean) * rstd * g1.y + b1.y);
-      o[3] = pack_bf16x2((v[c][6] - mean) * rstd * g1.z + b1.z, (v[c][7] - mean) * rstd * g1.w + b1.w);
-      *reinterpret_cast<u32x4*>(y + e0) = o;
     }
   }
 }
@@ -502,20 +517,37 @@ __global__ __launch_bounds__(kAttnWaves* kWave, 2) void k_attention_bf16(AttnArg
 
 hipError_t launch_add_norm(const NormArgs& a, hipStream_t st) {
   if (a.T == 0 || a.d == 0) return hipSuccess;
-  const dim3 grid((a.T + kNormWaves - 1) / kNormWaves), block(kNormWaves * kWave);
-  if (!a.bf16) {
-    k_add_norm_any<float><<<grid, block, 0, st>>>(a);
-    return hipGetLastError();
-  }
+  const dim3 block(kNormWaves * kWave);
   auto aligned = [](const void* p, int64_t ld) { return p == nullptr || (((uintptr_t)p & 15u) == 0 && ld % 8 == 0); };
-  const bool fast = a.d % 8 == 0 && a.d <= 8192 && aligned(a.X, a.ldx) && aligned(a.R, a.ldr) &&
+  const bool fast = a.bf16 && a.d % 8 == 0 && a.d <= 8192 && aligned(a.X, a.ldx) && aligned(a.R, a.ldr) &&
                     aligned(a.Hsum, a.ldh) && aligned(a.Y, a.ldy) && ((uintptr_t)a.gamma & 15u) == 0 &&
                     ((uintptr_t)a.beta & 15u) == 0;
-  if (!fast) k_add_norm_any<bf16_t><<<grid, block, 0, st>>>(a);
-  else if (a.d <= 2048) k_add_norm_bf16<4><<<grid, block, 0, st>>>(a);
-  else if (a.d <= 4096) k_add_norm_bf16<8><<<grid, block, 0, st>>>(a);
-  else if (a.d <= 6144) k_add_norm_bf16<12><<<grid, block, 0, st>>>(a);
-  else k_add_norm_bf16<16><<<grid, block, 0, st>>>(a);
+  if (!fast) {
+    const dim3 grid((a.T + kNormWaves - 1) / kNormWaves);
+    if (a.bf16) k_add_norm_any<bf16_t><<<grid, block, 0, st>>>(a);
+    else k_add_norm_any<float><<<grid, block, 0, st>>>(a);
+    return hipGetLastError();
+  }
+  // One round of workgroups: as many as are resident at once (registers and the LDS copy of gamma and
+  // beta allow wgs_per_cu per CU), each wave walking through its share of the rows.  More, smaller
+  // workgroups re-stage gamma and beta more often and leave a partial last round.
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      n = 256;
+    cus = n;
+  }
+  const int wgs_per_cu = a.d <= 2048 ? 7 : a.d <= 4096 ? 4 : a.d <= 6144 ? 3 : 2;
+  const int per_round = cus * wgs_per_cu * kNormWaves;
+  const int rows_per_wave = (a.T + per_round - 1) / per_round;
+  const int rows_per_wg = rows_per_wave * kNormWaves;
+  const dim3 grid((a.T + rows_per_wg - 1) / rows_per_wg);
+  if (a.d <= 2048) k_add_norm_bf16<4><<<grid, block, 0, st>>>(a, rows_per_wave);
+  else if (a.d <= 4096) k_add_norm_bf16<8><<<grid, block, 0, st>>>(a, rows_per_wave);
+  else if (a.d <= 6144) k_add_norm_bf16<12><<<grid, block, 0, st>>>(a, rows_per_wave);
+  else k_add_norm_bf16<16><<<grid, block, 0, st>>>(a, rows_per_wave);
   return hipGetLastError();
 }
 
