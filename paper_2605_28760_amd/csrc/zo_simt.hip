@@ -154,50 +154,4 @@ hipError_t launch_head_score_f32(const HeadScoreF32Args& a, hipStream_t st) {
   return hipGetLastError();
 }
 
-// ---- fold the bank into the base (Sec. 3.2) -------------------------------------------------
-// W[i][j] += sum_k P[i][k] Vb[j][k] over the R columns in use; fp32 on the vector ALU so that the
-// only rounding that matters is the one into W's storage type.  Rare (once per nu * B steps), so the
-// simple 64x64 tile is enough: it reads and writes W once.
-__global__ __launch_bounds__(256) void k_fold_bank(FoldArgs p) {
-  const int m0 = blockIdx.y * ST, n0 = blockIdx.x * ST;
-  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-  float acc[4][4] = {};
-  simt_mainloop(p.P, p.R_cap, p.m, m0, p.Vb, p.R_cap, p.n, n0, p.R, acc);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = m0 + ty * 4 + i;
-    if (row >= p.m) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int col = n0 + tx * 4 + j;
-      if (col >= p.n) continue;
-      const int64_t at = (int64_t)row * p.ldw + col;
-      if (p.bf16) {
-        bf16_t* W = (bf16_t*)p.W;
-        W[at] = f32_to_bf16(bf16_to_f32(W[at]) + acc[i][j]);
-      } else {
-        float* W = (float*)p.W;
-        W[at] += acc[i][j];
-      }
-    }
-  }
-}
-
-// zeroes columns [0, R) of a [rows x R_cap] fp32 matrix (a fill kernel, so that the call can be captured)
-__global__ void k_zero_columns(float* A, int rows, int R_cap, int R) {
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)rows * R) return;
-  A[(idx / R) * R_cap + idx % R] = 0.0f;
-}
-
-hipError_t launch_fold_bank(const FoldArgs& a, hipStream_t st) {
-  if (a.m == 0 || a.n == 0 || a.R == 0) return hipSuccess;
-  dim3 grid((a.n + ST - 1) / ST, (a.m + ST - 1) / ST);
-  hipLaunchKernelGGL(k_fold_bank, grid, dim3(256), 0, st, a);
-  const int64_t np_ = (int64_t)a.m * a.R, nv = (int64_t)a.n * a.R;
-  hipLaunchKernelGGL(k_zero_columns, dim3((unsigned)((np_ + 255) / 256)), dim3(256), 0, st, a.P, a.m, a.R_cap, a.R);
-  hipLaunchKernelGGL(k_zero_columns, dim3((unsigned)((nv + 255) / 256)), dim3(256), 0, st, a.Vb, a.n, a.R_cap, a.R);
-  return hipGetLastError();
-}
-
 }  // namespace zo
