@@ -89,19 +89,26 @@ zo::BatchDev to_dev(const zo_batch* b) {
 
 // ---- workspace plans --------------------------------------------------------------------
 struct ProbePlan {
-  int RP = 0, Rp = 0, max_items = 0, ksplit = 1;
+  int RP = 0, Rp = 0, max_items = 0, ks_cap = 1;
   size_t seq_kind, seq_scale, tok_seq, n_items, items;
   size_t Uh, Vt, Ph, Vbt, Aside, partial;   // bf16 path
   size_t Uf, Vf, Tside;                      // fp32 path
   size_t total = 0;
 };
 
-int side_ksplit(int T, int n) {
-  // about two workgroups (of four 64-row items each) per CU; k-chunks are multiples of 64 and >= 512
-  const int groups = ((T + zo::kSideRows - 1) / zo::kSideRows + 3) / 4;
-  int ks = 1;
-  while (groups * ks < 512 && ks < 16 && n % (ks * 2 * 64) == 0 && n / (ks * 2) >= 512) ks *= 2;
-  return ks;
+// Rows reserved for the k-split partial sums of the side-down pass: a bound that only grows with T, so
+// a workspace sized for a large batch also serves every smaller one.
+size_t side_partial_rows(int T) { return (size_t)T * 16 < 262144 ? (size_t)T * 16 : 262144; }
+
+// Upper bound of the side-down k-split (the device picks the split once it knows the work items):
+// at most 16, k ranges of at least 512 columns, and split * T rows of partial sums must fit.
+int side_ks_cap(int T, int n) {
+  if (T <= 0) return 1;
+  int cap = n / 512;
+  if (cap > 16) cap = 16;
+  const int fit = (int)(side_partial_rows(T) / (size_t)T);
+  if (cap > fit) cap = fit;
+  return cap < 1 ? 1 : cap;
 }
 
 ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype dt) {
@@ -117,16 +124,13 @@ ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype d
     p.RP = round16(r);
     p.Rp = round16(R);
     const size_t NC = (size_t)p.RP + p.Rp;
-    p.ksplit = side_ksplit(T, n);
+    p.ks_cap = side_ks_cap(T, n);
     p.Uh = c.take((size_t)K * m * p.RP * 2);
     p.Vt = c.take((size_t)K * p.RP * n * 2);
     p.Ph = c.take((size_t)m * p.Rp * 2);
     p.Vbt = c.take((size_t)p.Rp * n * 2);
     p.Aside = c.take((size_t)T * NC * 2);
-    // k-split partial sums: ksplit * T rows are needed, which shrinks again once T alone fills the
-    // chip; reserve a bound that only grows with T (ksplit <= 16 and ksplit * T < 1024 * 256), so a
-    // workspace sized for a large batch also serves every smaller one
-    const size_t partial_rows = (size_t)T * 16 < 262144 ? (size_t)T * 16 : 262144;
+    const size_t partial_rows = side_partial_rows(T);
     p.partial = c.take(partial_rows * NC * 4);
   } else {
     p.Uf = c.take((size_t)K * m * r * 4);
@@ -263,6 +267,8 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   tabs.items = (zo::SideItem*)(ws + plan.items);
   tabs.n_items = (int32_t*)(ws + plan.n_items);
   tabs.max_items = plan.max_items;
+  tabs.side_slots = 2 * zo::compute_units();   // the side-down pass keeps two workgroups per CU
+  tabs.side_ks_cap = plan.ks_cap;
   // a batch without candidates (or probes and bank both absent) is a plain GEMM
   const bool has_side = batch->n_cands > 0;
   if (has_side && in_dtype != ZO_BF16) ZO_HIP(zo::launch_seq_tables(bd, eps, tabs, st), "batch tables");
@@ -281,7 +287,7 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
       sd.X = (const uint16_t*)X; sd.ldx = ldx; sd.Vt = Vt; sd.Vbt = Vbt;
       sd.n = n; sd.RP = plan.RP; sd.Rp = plan.Rp; sd.T = T;
       sd.items = tabs.items; sd.n_items = tabs.n_items; sd.max_items = plan.max_items;
-      sd.ksplit = plan.ksplit; sd.partial = (float*)(ws + plan.partial); sd.Aside = Aside;
+      sd.ks_cap = plan.ks_cap; sd.partial = (float*)(ws + plan.partial); sd.Aside = Aside;
       sd.tok_seq = tabs.tok_seq; sd.seq_kind = tabs.seq_kind; sd.seq_scale = tabs.seq_scale;
       ZO_HIP(zo::launch_side_down_bf16(sd, st), "side-down");
     }

@@ -531,14 +531,7 @@ hipError_t launch_add_norm(const NormArgs& a, hipStream_t st) {
   // One round of workgroups: as many as are resident at once (registers and the LDS copy of gamma and
   // beta allow wgs_per_cu per CU), each wave walking through its share of the rows.  More, smaller
   // workgroups re-stage gamma and beta more often and leave a partial last round.
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
-      n = 256;
-    cus = n;
-  }
+  const int cus = compute_units();
   const int wgs_per_cu = a.d <= 2048 ? 7 : a.d <= 4096 ? 4 : a.d <= 6144 ? 3 : 2;
   const int per_round = cus * wgs_per_cu * kNormWaves;
   const int rows_per_wave = (a.T + per_round - 1) / per_round;

@@ -298,7 +298,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads before the workgroup ends
 }
 
-static int gemm_grid(int total_tiles) {
+int compute_units() {
   static int cus = 0;
   if (cus == 0) {
     int dev = 0, n = 0;
@@ -306,6 +306,11 @@ static int gemm_grid(int total_tiles) {
       n = 256;
     cus = n;
   }
+  return cus;
+}
+
+static int gemm_grid(int total_tiles) {
+  const int cus = compute_units();
   const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
   const int slots = per_xcd < cus / kXcds ? per_xcd : cus / kXcds;
   return slots * kXcds;

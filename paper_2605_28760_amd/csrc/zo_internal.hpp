@@ -38,9 +38,16 @@ struct SeqTables {
   float* seq_scale;    // [S]
   int32_t* tok_seq;    // [T]
   SideItem* items;     // [max_items]
-  int32_t* n_items;    // [1]
+  int32_t* n_items;    // [2]: number of items, then the k-split the side-down pass uses for them
   int32_t max_items;
+  // how the k-split is chosen on the device once the items are known: as many splits as keep
+  // ceil(n_items / 4) * splits workgroups within `side_slots` (one resident round), at most side_ks_cap
+  int32_t side_slots;
+  int32_t side_ks_cap;
 };
+
+// number of compute units of the current device (256 on MI355X; cached)
+int compute_units();
 
 // ---- zo_prep.hip ------------------------------------------------------------
 hipError_t launch_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block,
@@ -62,8 +69,8 @@ struct SideDownArgs {
   const uint16_t* Vbt;              // [Rp][n]
   int n, RP, Rp, T;
   const SideItem* items; const int32_t* n_items; int max_items;
-  int ksplit;                       // >= 1
-  float* partial;                   // [ksplit][T][RP+Rp] when ksplit > 1
+  int ks_cap;                       // >= 1: upper bound of the k-split, which the device picks (n_items[1])
+  float* partial;                   // [k-split][T][RP+Rp] when the k-split is > 1
   uint16_t* Aside;                  // bf16 [T][RP+Rp]: [s*eps*X V | X Vb]
   const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;  // for the split-K reduction
 };

@@ -130,7 +130,12 @@ __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, c
     if (tid == 1023) s_carry += s_scan[1023];
     __syncthreads();
   }
-  if (tid == 0) *t.n_items = min(s_carry, t.max_items);
+  if (tid == 0) {
+    const int n_items = min(s_carry, t.max_items);
+    const int groups = max((n_items + 3) / 4, 1);
+    t.n_items[0] = n_items;
+    t.n_items[1] = max(1, min(t.side_ks_cap, t.side_slots / groups));
+  }
 }
 
 __global__ __launch_bounds__(1024) void k_seq_tables(BatchDev b, float eps, SeqTables t) { seq_tables_block(b, eps, t); }

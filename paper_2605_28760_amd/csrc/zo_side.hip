@@ -43,13 +43,17 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   // waves without an item still take part in the workgroup's Vb loads and barriers
   const SideItem it = a.items[live ? item_raw : (n_items > 0 ? n_items - 1 : 0)];
   const int split = blockIdx.x;
+  const int ksplit = a.n_items[1];   // chosen on the device for the number of items; the grid covers the cap
+  if (split >= ksplit) return;
   const int NC = a.RP + a.Rp;
   const int lr = lane & 15, lg = lane >> 4;
-  // each split walks its own contiguous K range in steps of 64
-  const int kchunk = a.n / a.ksplit;
-  const int k_begin = split * kchunk;
+  // each split walks its own contiguous K range in steps of 64; the first (steps mod k-split) splits
+  // take one step more
   constexpr int kstride = 64;
-  const int nsteps_all = kchunk / kstride;
+  const int steps_total = a.n / kstride;
+  const int q = steps_total / ksplit, rem = steps_total - q * ksplit;
+  const int k_begin = (split * q + min(split, rem)) * kstride;
+  const int nsteps_all = q + (split < rem ? 1 : 0);
   const bool has_dir = kDir && it.kind >= 0;
   const bool work = live && it.kind != kKindForeground;   // wave-uniform; foreground rows are not read at all
   // a workgroup whose four items are all foreground (or absent) has nothing to multiply: it skips the
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
         if (cb == 0 && !kDir) continue;
         const int col = cb == 0 ? lr : ndir_cols + (cb0 + cb - 1) * 16 + lr;
         const float x = acc[rb][cb][v];
-        if (a.ksplit == 1) {
+        if (ksplit == 1) {
           float y = x;
           if (cb == 0) y = has_dir ? it.scale * x : 0.0f;
           if (fg) y = 0.0f;
@@ -167,9 +171,13 @@ __global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int 
   if (item >= *a.n_items) return;
   const SideItem it = a.items[item];
   const int split = blockIdx.y;
+  const int ksplit = a.n_items[1];
+  if (split >= ksplit) return;
   const int NC = a.RP + a.Rp;
   const int lr = lane & 15, lg = lane >> 4;
-  const int kchunk = a.n / a.ksplit, k_begin = split * kchunk;
+  const int steps_total = a.n / 64;
+  const int q = steps_total / ksplit, rem = steps_total - q * ksplit;
+  const int k_begin = (split * q + min(split, rem)) * 64, kchunk = (q + (split < rem ? 1 : 0)) * 64;
   const bool has_dir = it.kind >= 0;
   f32x4 acc[4];
 #pragma unroll
@@ -195,13 +203,16 @@ __global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int 
       if (lrow >= it.nrows) continue;
       const int64_t row = it.row0 + lrow;
       const int col = cbd * 16 + lr;
-      if (a.ksplit == 1) a.Aside[row * NC + col] = f32_to_bf16(has_dir ? it.scale * acc[rb][v] : 0.0f);
+      if (ksplit == 1) a.Aside[row * NC + col] = f32_to_bf16(has_dir ? it.scale * acc[rb][v] : 0.0f);
       else a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][v];
     }
 }
 
-// Fixed-order sum of the k-split partials, scaling and rounding to bf16.
+// Fixed-order sum of the k-split partials, scaling and rounding to bf16.  Without a split the
+// side-down pass has written Aside itself.
 __global__ void k_side_reduce(SideDownArgs a) {
+  const int ksplit = a.n_items[1];
+  if (ksplit == 1) return;
   const int NC = a.RP + a.Rp;
   const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx >= (int64_t)a.T * NC) return;
@@ -211,7 +222,7 @@ __global__ void k_side_reduce(SideDownArgs a) {
   float y = 0.0f;
   const bool live = (col < a.RP) ? (kind >= 0) : (kind >= kKindCentre);
   if (live) {
-    for (int sp = 0; sp < a.ksplit; ++sp) y += a.partial[((int64_t)sp * a.T + row) * NC + col];
+    for (int sp = 0; sp < ksplit; ++sp) y += a.partial[((int64_t)sp * a.T + row) * NC + col];
     if (col < a.RP) y *= a.seq_scale[s];
   }
   a.Aside[idx] = f32_to_bf16(y);
@@ -219,7 +230,7 @@ __global__ void k_side_reduce(SideDownArgs a) {
 
 template <int NBB, bool kDir>
 static void launch_pass(const SideDownArgs& a, int cb0, hipStream_t st) {
-  dim3 grid(a.ksplit, (a.max_items + 3) / 4);
+  dim3 grid(a.ks_cap, (a.max_items + 3) / 4);
   hipLaunchKernelGGL((k_side_down<NBB, kDir>), grid, dim3(256), 0, st, a, cb0);
 }
 
@@ -250,12 +261,12 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
     done += nb;
   }
   for (int cbd = 1; cbd < a.RP / 16; ++cbd) {   // ranks above 16
-    dim3 grid((a.max_items + 3) / 4, a.ksplit);
+    dim3 grid((a.max_items + 3) / 4, a.ks_cap);
     hipLaunchKernelGGL(k_side_down_dirblock, grid, dim3(256), 0, st, a, cbd);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.ksplit > 1) {
+  if (a.ks_cap > 1) {
     const int64_t total = (int64_t)a.T * (a.RP + a.Rp);
     hipLaunchKernelGGL(k_side_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
   }

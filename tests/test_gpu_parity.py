@@ -409,11 +409,12 @@ def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0):
                        (np.arange(K, dtype=np.uint64) + np.uint64(991 + seed)), [layer], False)
 
 
-@pytest.mark.parametrize("case", range(8))
+@pytest.mark.parametrize("case", range(10))
 def test_bf16_probe_linear_odd_shapes(case):
     """Shapes that leave ragged tails in every tile dimension of the matrix-core kernel (out features
     not a multiple of 16, 128 or 256; one token; token counts just past a tile; many short sequences of
-    different directions inside one token tile; ranks 1 and 64; a bank wider than one side-down pass)."""
+    different directions inside one token tile; ranks 1 and 64; a bank wider than one side-down pass;
+    input widths whose 64-column steps do not divide evenly among the side-down pass's k ranges)."""
     cases = [
         dict(lens=[1], seq_cand=[0], cand_dir=[0], cand_sign=[1], m=8, n=64, r=1, R=0),
         dict(lens=[257, 3], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=200, n=128, r=5, R=16),
@@ -425,6 +426,8 @@ def test_bf16_probe_linear_odd_shapes(case):
              m=520, n=256, r=17, R=0),
         dict(lens=[511], seq_cand=[2], cand_dir=[1, 1, 0], cand_sign=[-1, 1, 1], m=256, n=1024, r=33, R=136),
         dict(lens=[2, 254, 2], seq_cand=[0, -1, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=1032, n=64, r=2, R=8),
+        dict(lens=[70, 9], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=64, n=1344, r=33, R=136),
+        dict(lens=[40, 0, 100, 65], seq_cand=[1, 0, -1, 2], cand_dir=[0, 1, -1], cand_sign=[1, -1, 0], m=48, n=1600, r=8, R=16),
     ]
     w = _single_layer(case, **cases[case])
     d = DeviceWorkload(w, DEV)
