@@ -148,26 +148,59 @@ hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, h
 }
 
 // ---- operand images ----------------------------------------------------------------------
-__device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint32_t tid_u, int m, int r, int RP, bf16_t* Uh) {
-  const int64_t per_dir = (int64_t)m * RP;
-  if (idx >= per_dir * b.K) return;
-  const int k = (int)(idx / per_dir);
-  const int64_t rem = idx - (int64_t)k * per_dir;
-  const int i = (int)(rem / RP), j = (int)(rem % RP);
-  float z = 0.0f;
-  if (j < r) z = factor_normal(b.seed[k], tid_u, (uint64_t)i * r + j);
-  Uh[idx] = f32_to_bf16(z);
+// Four consecutive columns c0 .. c0+3 of row i of a [rows x r] factor: entries c >= r are zero.
+// Entry (i, c) is element e = i*r + c of the stream, i.e. lane e%4 of block e/4; the four entries
+// come out of one block when r is a multiple of 4 and out of two neighbouring blocks otherwise.
+__device__ __forceinline__ void factor_quad(uint64_t seed, uint32_t tid, int64_t i, int r, int c0, float (&z)[4]) {
+  const uint64_t e0 = (uint64_t)i * r + c0;
+  float v[8];
+  {
+    const uint4 w = factor_block(seed, tid, e0 >> 2);
+    box_muller(w.x, w.y, v[0], v[1]);
+    box_muller(w.z, w.w, v[2], v[3]);
+  }
+  const int lane0 = (int)(e0 & 3);
+  if (lane0 != 0) {
+    const uint4 w = factor_block(seed, tid, (e0 >> 2) + 1);
+    box_muller(w.x, w.y, v[4], v[5]);
+    box_muller(w.z, w.w, v[6], v[7]);
+  } else {
+    v[4] = v[5] = v[6] = v[7] = 0.0f;
+  }
+#pragma unroll
+  for (int l = 0; l < 4; ++l) {
+    float x = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) x = (t == lane0 + l) ? v[t] : x;   // register select, no indexing
+    z[l] = c0 + l < r ? x : 0.0f;
+  }
 }
 
-__device__ __forceinline__ void image_Vt_at(const BatchDev& b, int64_t idx, uint32_t tid_v, int n, int r, int RP, bf16_t* Vt) {
-  const int64_t per_dir = (int64_t)n * RP;
+// idx runs over [K][m][RP/4]: one thread writes four neighbouring entries of a row of U (8 bytes)
+__device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint32_t tid_u, int m, int r, int RP, bf16_t* Uh) {
+  const int quads = RP >> 2;
+  const int64_t per_dir = (int64_t)m * quads;
   if (idx >= per_dir * b.K) return;
   const int k = (int)(idx / per_dir);
   const int64_t rem = idx - (int64_t)k * per_dir;
-  const int j = (int)(rem / n), i = (int)(rem % n);
-  float z = 0.0f;
-  if (j < r) z = factor_normal(b.seed_v ? b.seed_v[k] : b.seed[k], tid_v, (uint64_t)i * r + j);
-  Vt[idx] = f32_to_bf16(z);
+  const int i = (int)(rem / quads), c0 = (int)(rem % quads) * 4;
+  float z[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c0 < r) factor_quad(b.seed[k], tid_u, i, r, c0, z);
+  *reinterpret_cast<uint2*>(Uh + ((int64_t)k * m + i) * RP + c0) = make_uint2(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]));
+}
+
+// idx runs over [K][RP/4][n]: one thread writes entry i of four neighbouring rows of V^T
+__device__ __forceinline__ void image_Vt_at(const BatchDev& b, int64_t idx, uint32_t tid_v, int n, int r, int RP, bf16_t* Vt) {
+  const int quads = RP >> 2;
+  const int64_t per_dir = (int64_t)n * quads;
+  if (idx >= per_dir * b.K) return;
+  const int k = (int)(idx / per_dir);
+  const int64_t rem = idx - (int64_t)k * per_dir;
+  const int c0 = (int)(rem / n) * 4, i = (int)(rem % n);
+  float z[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c0 < r) factor_quad(b.seed_v ? b.seed_v[k] : b.seed[k], tid_v, i, r, c0, z);
+#pragma unroll
+  for (int l = 0; l < 4; ++l) Vt[((int64_t)k * RP + c0 + l) * n + i] = f32_to_bf16(z[l]);
 }
 
 __device__ __forceinline__ void image_P_at(int64_t idx, const float* P, int R_cap, int R_used, int Rp, int m, bf16_t* Ph) {
@@ -241,8 +274,8 @@ hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables&
   a.P = P; a.Vb = Vb; a.R_cap = R_cap; a.R_used = R_used; a.Uh = Uh; a.Vt = Vt; a.Ph = Ph; a.Vbt = Vbt;
   auto blocks = [](int64_t n_elems) { return (int)((n_elems + 1023) / 1024); };
   a.nb_tok = blocks(b.T);
-  a.nb_U = blocks((int64_t)b.K * m * RP);
-  a.nb_Vt = blocks((int64_t)b.K * n * RP);
+  a.nb_U = blocks((int64_t)b.K * m * (RP / 4));
+  a.nb_Vt = blocks((int64_t)b.K * n * (RP / 4));
   a.nb_P = Rp > 0 ? blocks((int64_t)m * Rp) : 0;
   a.vbt_tiles_n = (n + 31) / 32;
   a.nb_Vbt = Rp > 0 ? a.vbt_tiles_n * ((Rp + 31) / 32) : 0;
