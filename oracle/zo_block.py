@@ -127,3 +127,22 @@ def block_forward(batch, x, blk, r, eps, dtype, store=None):
     f2 = lin(blk.fc2, f1)
     h2 = _zo._round_out(np.asarray(h1, np.float64) + f2, store)
     return dict(a1=a1, qkv=qkv, att=att, o=o, h1=h1, a2=a2, f1=f1, f2=f2, h2=h2)
+
+
+def model_forward(batch, x, blocks, final_norm, head, targets, r, eps, dtype, reduction, store=None):
+    """Scoring pass of a whole model: the blocks in sequence, a final norm, LM-head scoring of
+    every row under its candidate (the head itself is not perturbed) and the two-point estimate.
+    final_norm = (gain, shift or None), of the same kind as the blocks' norms."""
+    store = store or dtype
+    h = x
+    per_block = []
+    for blk in blocks:
+        out = block_forward(batch, h, blk, r, eps, dtype, store)
+        per_block.append(out)
+        h = out["h2"]
+    last = blocks[-1]
+    _, hn = add_norm(h, None, final_norm[0], final_norm[1], last.norm_kind, last.norm_eps, store)
+    tok, seq, cs, cc = _zo.score(batch, hn, head, targets)
+    loss, grad = _zo.estimate(batch, cs, cc, eps, reduction)
+    return dict(blocks=per_block, final=hn, tok_nll=tok, seq_nll=seq, cand_sum=cs, cand_cnt=cc, cand_loss=loss,
+                proj_grad=grad)

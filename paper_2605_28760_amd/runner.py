@@ -129,21 +129,23 @@ class DeviceWorkload:
 
 
 class DeviceBlock:
-    """One pre-norm decoder block on a DeviceWorkload built from workloads.decoder_block: sequences
+    """One pre-norm decoder block on a DeviceWorkload whose layers base .. base+3 are its fused q/k/v
+    projection, output projection, fc1 and fc2: sequences
     zo_add_norm -> zo_probe_linear(qkv) -> zo_attention -> zo_probe_linear(o) -> zo_add_norm ->
     zo_probe_linear(fc1) -> zo_probe_linear(fc2) -> zo_add_norm (sum only)."""
 
-    def __init__(self, d):
-        self.d = d
-        blk = d.w.meta["block"]
+    def __init__(self, d, blk=None, base=0):
+        self.d, self.base = d, base
+        blk = blk if blk is not None else d.w.meta["block"]
         self.blk = blk
         dev, tt = d.device, _tt(d.dtype)
         up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(dev)
         self.g1, self.b1, self.g2, self.b2 = up(blk.g1), up(blk.b1), up(blk.g2), up(blk.b2)
-        T, hidden = d.batch.T, d.layers[0].n
+        T, hidden = d.batch.T, d.layers[base].n
         self.hidden = hidden
         self.a1, self.h1, self.a2, self.h2 = (torch.empty((T, hidden), device=dev, dtype=tt) for _ in range(4))
         self.att = torch.empty((T, blk.n_heads * blk.head_dim), device=dev, dtype=tt)
+        self.h0 = None   # block input when it arrives as a pending sum (allocated on first use)
 
     def add_norm(self, x, res, gamma, beta, hsum, y, stream=None):
         ld = lambda t: 0 if t is None else t.stride(0)
@@ -158,18 +160,64 @@ class DeviceBlock:
                         b.n_heads, b.n_kv_heads, b.head_dim, float(b.scale), _dt(self.d.dtype), out,
                         out.stride(0), stream)
 
-    def forward(self, X=None, stream=None):
-        d = self.d
+    def forward(self, X=None, stream=None, res=None, last_sum=True):
+        """Runs the block on X (default: the workload's input), or on X + res when res is given (the
+        previous block's pending residual sum, fused into this block's first norm).  With last_sum the
+        final residual sum is written to h2 and returned; without it the two terms (h1, fc2 output) are
+        returned for the caller to fuse into its next call."""
+        d, i0 = self.d, self.base
         x = d.X if X is None else X
-        self.add_norm(x, None, self.g1, self.b1, None, self.a1, stream)
-        qkv = d.probe_linear(0, self.a1, stream)
+        if res is None:
+            self.add_norm(x, None, self.g1, self.b1, None, self.a1, stream)
+        else:
+            if self.h0 is None:
+                self.h0 = torch.empty_like(self.h1)
+            self.add_norm(x, res, self.g1, self.b1, self.h0, self.a1, stream)
+            x = self.h0
+        qkv = d.probe_linear(i0, self.a1, stream)
         self.attention(qkv, self.att, stream)
-        o = d.probe_linear(1, self.att, stream)
+        o = d.probe_linear(i0 + 1, self.att, stream)
         self.add_norm(x, o, self.g2, self.b2, self.h1, self.a2, stream)
-        d.probe_linear(2, self.a2, stream)
-        f2 = d.probe_linear(3, d.Y[2], stream)
+        d.probe_linear(i0 + 2, self.a2, stream)
+        f2 = d.probe_linear(i0 + 3, d.Y[i0 + 2], stream)
+        if not last_sum:
+            return self.h1, f2
         self.add_norm(self.h1, f2, None, None, self.h2, None, stream)
         return self.h2
+
+
+class DeviceModel:
+    """A stack of decoder blocks, a final norm and the LM head on a DeviceWorkload built from
+    workloads.decoder_model: the teacher-forced scoring pass of a whole model under the batch's candidate
+    table, followed by the estimate and the lazy update of every probed layer."""
+
+    def __init__(self, d):
+        self.d = d
+        blocks = d.w.meta["blocks"]
+        self.blocks = [DeviceBlock(d, blk, 4 * i) for i, blk in enumerate(blocks)]
+        gf, bf = d.w.meta["final_norm"]
+        up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(d.device)
+        self.gf, self.bf = up(gf), up(bf)
+        self.final = torch.empty_like(self.blocks[0].h1)
+
+    def forward(self, stream=None):
+        """Every residual sum is fused into the norm that follows it: a block hands its two terms on."""
+        x, res = self.d.X, None
+        for blk in self.blocks:
+            x, res = blk.forward(x, stream, res, last_sum=False)
+        self.blocks[-1].add_norm(x, res, self.gf, self.bf, None, self.final, stream)
+        self.d.score(self.final, stream)
+        return self.final
+
+    def step(self, lr=1e-7, update=True, stream=None):
+        d = self.d
+        self.forward(stream)
+        d.estimate(stream)
+        if update:
+            col0 = np.arange(d.batch.K, dtype=np.int32) * d.w.r
+            for i, l in enumerate(d.layers):
+                if l.bank is not None and l.bank.R_used >= d.w.r * d.batch.K:
+                    d.bank_update(i, lr, col0, 0, stream=stream)
 
 
 class LoopDriver:

@@ -283,6 +283,24 @@ class Block:
     fc2: Layer
 
 
+def _block_params(cfg, dtype, index, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R):
+    """Block number `index` of a model: its four layers (tensor ids 8*index .. 8*index + 6) and norms."""
+    shapes = [("qkv", (n_heads + 2 * n_kv_heads) * head_dim, hidden, 0), ("o", hidden, n_heads * head_dim, 0),
+              ("fc1", ffn, hidden, 1), ("fc2", hidden, ffn, 0)]
+    layers = []
+    for i, (nm, m, n, act) in enumerate(shapes):
+        sub = 4 * index + i
+        W = _normal(cfg, _TAG_W, sub, (m, n), n ** -0.5, dtype)
+        P, Vb = _bank(cfg, sub, m, n, R)
+        bias = _normal(cfg, _TAG_BIAS, sub, (m,), 0.1, "f32") if with_bias else None
+        layers.append(Layer(nm if index == 0 else "%s.%d" % (nm, index), m, n, 2 * sub, W, act, P, Vb, R, None, bias))
+    gains = [np.float32(1) + _normal(cfg, _TAG_NORM, 4 * index + j, (hidden,), 0.1, "f32") for j in range(2)]
+    shifts = [_normal(cfg, _TAG_NORM, 4 * index + 2 + j, (hidden,), 0.1, "f32") if norm_kind == 0 else None
+              for j in range(2)]
+    return Block(norm_kind, 1e-5 if norm_kind == 0 else 1e-6, gains[0], shifts[0], gains[1], shifts[1],
+                 n_heads, n_kv_heads, head_dim, float(head_dim) ** -0.5, *layers)
+
+
 def decoder_block(name, cfg, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, r, eps, R,
                   batch):
     """A decoder block on the given batch (the tuple _pair_batch returns): unit-variance input rows,
@@ -290,20 +308,29 @@ def decoder_block(name, cfg, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn, 
     cu, seq_cand, cand_dir, cand_sign, seq_ex, seq_len_a = batch
     K = int(cand_dir.max()) + 1
     X = _replicated_rows(cfg, _TAG_X, seq_ex, seq_len_a, hidden, 1.0, dtype)
-    shapes = [("qkv", (n_heads + 2 * n_kv_heads) * head_dim, hidden, 0), ("o", hidden, n_heads * head_dim, 0),
-              ("fc1", ffn, hidden, 1), ("fc2", hidden, ffn, 0)]
-    layers = []
-    for i, (nm, m, n, act) in enumerate(shapes):
-        W = _normal(cfg, _TAG_W, i, (m, n), n ** -0.5, dtype)
-        P, Vb = _bank(cfg, i, m, n, R)
-        bias = _normal(cfg, _TAG_BIAS, i, (m,), 0.1, "f32") if with_bias else None
-        layers.append(Layer(nm, m, n, 2 * i, W, act, P, Vb, R, None, bias))
-    gains = [np.float32(1) + _normal(cfg, _TAG_NORM, j, (hidden,), 0.1, "f32") for j in range(2)]
-    shifts = [_normal(cfg, _TAG_NORM, 2 + j, (hidden,), 0.1, "f32") if norm_kind == 0 else None for j in range(2)]
-    blk = Block(norm_kind, 1e-5 if norm_kind == 0 else 1e-6, gains[0], shifts[0], gains[1], shifts[1],
-                n_heads, n_kv_heads, head_dim, float(head_dim) ** -0.5, *layers)
+    blk = _block_params(cfg, dtype, 0, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R)
+    layers = [blk.qkv, blk.o, blk.fc1, blk.fc2]
     return Workload(name, cfg, dtype, r, eps, cu, seq_cand, cand_dir, cand_sign, _seeds(cfg, K), layers, False, X,
                     None, None, 1, {"block": blk})
+
+
+def decoder_model(name, cfg, dtype, n_blocks, hidden, n_heads, n_kv_heads, head_dim, ffn, vocab, norm_kind,
+                  with_bias, r, eps, R, batch, reduction=0):
+    """n_blocks decoder blocks, a final norm and an LM head on the given batch: the teacher-forced scoring
+    pass of a whole (randomly initialised) model.  workload.layers holds the 4 * n_blocks probed linears in
+    execution order; meta["blocks"] their blocks; meta["final_norm"] = (gain, shift or None)."""
+    cu, seq_cand, cand_dir, cand_sign, seq_ex, seq_len_a = batch
+    K = int(cand_dir.max()) + 1
+    X = _replicated_rows(cfg, _TAG_X, seq_ex, seq_len_a, hidden, 1.0, dtype)
+    tgt = _replicated_rows(cfg, _TAG_TGT, seq_ex, seq_len_a, 1, 0, "f32", integer_high=vocab)
+    blocks = [_block_params(cfg, dtype, b, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R)
+              for b in range(n_blocks)]
+    layers = [l for blk in blocks for l in (blk.qkv, blk.o, blk.fc1, blk.fc2)]
+    gf = np.float32(1) + _normal(cfg, _TAG_NORM, 4 * n_blocks, (hidden,), 0.1, "f32")
+    bf = _normal(cfg, _TAG_NORM, 4 * n_blocks + 1, (hidden,), 0.1, "f32") if norm_kind == 0 else None
+    head = _normal(cfg, _TAG_HEAD, 0, (vocab, hidden), hidden ** -0.5, dtype)
+    return Workload(name, cfg, dtype, r, eps, cu, seq_cand, cand_dir, cand_sign, _seeds(cfg, K), layers, False, X,
+                    head, tgt, reduction, {"blocks": blocks, "final_norm": (gf, bf)})
 
 
 def opt_block(hidden=5120, n_heads=40, head_dim=128, ffn=20480, n_ex=64, seq_len=128, r=8, eps=1e-3, R=64, cfg=5,

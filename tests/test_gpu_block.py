@@ -14,7 +14,7 @@ from oracle import zo_block as ob
 from oracle import zo_oracle as zo
 from paper_2605_28760_amd import binding as zb
 from paper_2605_28760_amd import workloads as wl
-from paper_2605_28760_amd.runner import DeviceBatch, DeviceBlock, DeviceWorkload
+from paper_2605_28760_amd.runner import DeviceBatch, DeviceBlock, DeviceModel, DeviceWorkload
 from zo_testlib import assert_close, oracle_batch, to_np
 
 DEV = "cuda:0"
@@ -289,3 +289,64 @@ def test_block_foreground_rows_bit_identical():
     np.testing.assert_array_equal(mixed[fg_rows], plain[fg_rows])
     probe_rows = np.setdiff1d(np.arange(w.T), fg_rows)
     assert np.abs(mixed[probe_rows] - plain[probe_rows]).max() > 0
+
+
+# ------------------------------------------------------------------ whole model
+
+def _oracle_model(w):
+    return ob.model_forward(oracle_batch(w), w.X, w.meta["blocks"], w.meta["final_norm"], w.head, w.targets,
+                            w.r, w.eps, w.dtype, w.reduction)
+
+
+def test_model_fp32_scoring_pass_and_estimate():
+    """Two decoder blocks, final norm, LM head: per-candidate losses and the projected gradient of the
+    whole model against the oracle (fp32: rel 1e-5 per op; losses abs 1e-3; gradient rel 5e-2)."""
+    batch = wl._pair_batch([33, 64, 5, 90], [0, 1, 0, 1], 1, [20])
+    w = wl.decoder_model("model-small-f32", 70, "f32", 2, 96, 3, 1, 32, 160, 211, 0, True, 4, 1e-3, 8, batch)
+    d = DeviceWorkload(w, DEV)
+    model = DeviceModel(d)
+    model.step(update=False)
+    torch.cuda.synchronize()
+    want = _oracle_model(w)
+    assert_close(to_np(model.final), want["final"], 1e-4, "final hidden")      # 17 chained fp32 stages
+    assert_close(to_np(d.tok_nll), want["tok_nll"], 1e-4, "tok_nll", atol=1e-4)
+    assert np.array_equal(to_np(d.cand_cnt), want["cand_cnt"])
+    assert_close(to_np(d.cand_loss), want["cand_loss"], 0.0, "cand_loss", atol=1e-3)
+    assert_close(to_np(d.proj_grad), want["proj_grad"], 5e-2, "proj_grad")
+    assert np.abs(want["proj_grad"]).min() > 1e-4
+
+
+def test_model_bf16_scoring_pass_updates_and_foreground_rows():
+    batch = wl._pair_batch([70, 131, 9, 200], [0, 1, 0, 1], 1, [140])
+    w = wl.decoder_model("model-small-bf16", 71, "bf16", 2, 256, 2, 1, 128, 512, 1000, 1, False, 8, 1e-3, 32, batch)
+    d = DeviceWorkload(w, DEV)
+    model = DeviceModel(d)
+    model.step(update=False)
+    torch.cuda.synchronize()
+    want = _oracle_model(w)
+    # seventeen stages of bf16 storage lie between the input and the scored rows: individual entries may
+    # be off by two storage roundings (the bound of the single block, 4e-2), the mean losses by 1e-3
+    assert_close(to_np(model.final), want["final"], 4e-2, "final hidden")
+    assert_close(to_np(d.cand_loss), want["cand_loss"], 0.0, "cand_loss", atol=1e-3)
+    # scoring and estimate on the device's own final rows: the tolerances of the scoring path
+    tok = zo.token_nll(to_np(model.final), w.head, w.targets)
+    assert_close(to_np(d.tok_nll), tok, 1e-4, "tok_nll of the device rows", atol=1e-3)
+    loss, grad = zo.estimate(oracle_batch(w), to_np(d.cand_sum), to_np(d.cand_cnt), w.eps, w.reduction)
+    assert_close(to_np(d.proj_grad), grad, 5e-2, "proj_grad from the device sums")
+    # foreground rows: identical to a pass in which nothing is probed
+    fg_rows = np.concatenate([np.arange(w.cu_seqlens[s], w.cu_seqlens[s + 1]) for s in np.nonzero(w.seq_cand < 0)[0]])
+    mixed = to_np(model.final)[fg_rows]
+    plain_model = DeviceModel(DeviceWorkload(wl.foreground_only(w), DEV))
+    plain_model.forward()
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(mixed, to_np(plain_model.final)[fg_rows])
+    # the lazy update of all eight layers moves every bank by beta * U of its own tensor
+    before = [l.P.clone() for l in d.layers]
+    model.step(lr=1e-2, update=True)
+    torch.cuda.synchronize()
+    pg = to_np(d.proj_grad)
+    for i, l in enumerate(w.layers):
+        new = zo.bank_update(zo.Bank(l.P, l.Vb, l.R_used), oracle_batch(w), l.m, l.n, w.r, l.tensor_id, pg, 1e-2,
+                             np.arange(len(w.dir_seed)) * w.r, None, False, "bf16")
+        assert_close(to_np(d.layers[i].P), new.P, 1e-5, "P of %s" % l.name, atol=1e-7)
+        assert not torch.equal(before[i], d.layers[i].P)

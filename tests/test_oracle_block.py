@@ -266,3 +266,68 @@ def test_block_candidates_equal_the_block_with_mutated_weights():
     # both candidate sequences see different inputs, so compare each with its own centre instead
     base2 = zb.block_forward(_batch([6], [0], [-1], [0], [99]), x[6:12], blk, r, eps, "f32", "f64")["h2"]
     assert np.abs(minus - base2).max() > 1e-5
+
+
+# ---------------------------------------------------------------- whole model
+
+def _model(seed, n_blocks, d, H, Hkv, dh, ffn, vocab, kind, R=0):
+    g = _rng(seed)
+    blocks = []
+    for b in range(n_blocks):
+        blk = _block(seed * 10 + b, d, H, Hkv, dh, ffn, kind, R=R)
+        for i, name in enumerate(("qkv", "o", "fc1", "fc2")):
+            getattr(blk, name).tensor_id = 2 * (4 * b + i)
+        blocks.append(blk)
+    final = (1 + 0.1 * g.normal(size=d), 0.1 * g.normal(size=d) if kind == zb.LAYER_NORM else None)
+    head = g.normal(size=(vocab, d)) / np.sqrt(d)
+    return blocks, final, head
+
+
+def test_model_candidates_equal_the_model_with_mutated_weights():
+    """Per-candidate losses of the factorised model = losses of an ordinary model whose eight probed
+    weights were densely overwritten (Sec. 2.3: the two evaluations are algebraically the same)."""
+    d, H, Hkv, dh, ffn, vocab, r, eps = 24, 2, 1, 12, 40, 50, 3, 1e-2
+    blocks, final, head = _model(41, 2, d, H, Hkv, dh, ffn, vocab, zb.LAYER_NORM, R=4)
+    lens = [7, 7, 5]
+    batch = _batch(lens, [0, 1, 2], [0, 0, -1], [1, -1, 0], [1234])
+    g = _rng(42)
+    x = g.normal(size=(sum(lens), d)); x[7:14] = x[0:7]          # the +/- pair sees the same rows
+    targets = g.integers(0, vocab, size=sum(lens)); targets[7:14] = targets[0:7]
+    got = zb.model_forward(batch, x, blocks, final, head, targets, r, eps, "f32", 0, "f64")
+    cu = batch.cu_seqlens
+    for s, cand in enumerate([0, 1, 2]):
+        mutated = []
+        for blk in blocks:
+            m = types.SimpleNamespace(**vars(blk))
+            for name in ("qkv", "o", "fc1", "fc2"):
+                l = getattr(blk, name)
+                Wc = zo.candidate_weight(l.W, batch, cand, r, eps, l.tensor_id, zo.Bank(l.P, l.Vb, l.R_used), "f32")
+                setattr(m, name, types.SimpleNamespace(W=Wc, tensor_id=l.tensor_id, act=l.act, bias=l.bias,
+                                                       P=None, Vb=None, R_used=0))
+            mutated.append(m)
+        a, b = int(cu[s]), int(cu[s + 1])
+        plain = _batch([b - a], [0], [-1], [0], [1234])      # one centre candidate without a bank
+        want = zb.model_forward(plain, x[a:b], mutated, final, head, targets[a:b], r, eps, "f32", 0, "f64")
+        np.testing.assert_allclose(got["cand_loss"][cand], want["cand_loss"][0], rtol=1e-10)
+    # the estimate is the two-point difference of those losses
+    np.testing.assert_allclose(got["proj_grad"][0], (got["cand_loss"][0] - got["cand_loss"][1]) / (2 * eps), rtol=1e-12)
+    assert abs(got["proj_grad"][0]) > 1e-6
+
+
+def test_model_antithetic_losses_average_to_the_centre_loss_to_second_order():
+    d, H, Hkv, dh, ffn, vocab, r = 16, 2, 2, 8, 24, 30, 2
+    blocks, final, head = _model(43, 2, d, H, Hkv, dh, ffn, vocab, zb.RMS_NORM)
+    for blk in blocks:
+        blk.fc1.act = 0      # no ReLU kinks: softmax, norms and the NLL keep the model smooth and nonlinear
+    lens = [6, 6, 6]
+    g = _rng(44)
+    x = np.tile(g.normal(size=(6, d)), (3, 1))
+    targets = np.tile(g.integers(0, vocab, size=6), 3)
+    gaps = []
+    for eps in (8e-3, 4e-3, 2e-3):
+        batch = _batch(lens, [0, 1, 2], [0, 0, -1], [1, -1, 0], [77])
+        out = zb.model_forward(batch, x, blocks, final, head, targets, r, eps, "f32", 0, "f64")
+        gaps.append(0.5 * (out["cand_loss"][0] + out["cand_loss"][1]) - out["cand_loss"][2])
+    assert abs(gaps[0]) > 1e-9
+    np.testing.assert_allclose(gaps[0] / gaps[1], 4.0, rtol=0.15)
+    np.testing.assert_allclose(gaps[1] / gaps[2], 4.0, rtol=0.15)
