@@ -21,6 +21,11 @@ definitions of the model families it evaluates, written here directly:
   block        h1 = x  + Wo . attention(split(Wqkv . norm1(x)))
                h2 = h1 + W2 . act(W1 . norm2(h1))
                (pre-norm; every linear is a probe linear under the row's candidate)
+  qk_norm_rope (Qwen3 family) per head: q, k <- rms_norm over the head dimension, then the
+               rotary embedding: the pair (x[i], x[i + dh/2]) of a row at position p of its
+               sequence is rotated by the angle p * theta^(-2i/dh)
+  swiglu       (gated MLP) a[j] = silu(g[j]) * u[j] for the fused projection output [g | u],
+               silu(x) = x / (1 + exp(-x))
 
 Nothing here is blocked, fused or reordered: scores are formed in full per
 sequence and head.  Pins: tests/test_oracle_block.py (library routines on
@@ -101,12 +106,48 @@ def attention(q, k, v, cu_seqlens, n_heads, n_kv_heads, head_dim, scale, dtype="
     return _zo._round_out(out, dtype)
 
 
+def qk_norm_rope(q, k, cu_seqlens, n_heads, n_kv_heads, head_dim, gamma_q, gamma_k, norm_eps, theta, dtype="f64"):
+    """Per-head RMS norm (skipped when gamma_q is None) and rotary embedding (skipped when theta is
+    None) of the packed query and key rows; a row's position is its offset in its own sequence."""
+    q = np.asarray(q, np.float64).copy()
+    k = np.asarray(k, np.float64).copy()
+    T = q.shape[0]
+    cu = np.asarray(cu_seqlens, np.int64)
+    pos = np.zeros(T, np.float64)
+    for i in range(len(cu) - 1):
+        pos[cu[i]:cu[i + 1]] = np.arange(cu[i + 1] - cu[i])
+    half = head_dim // 2
+    if theta is not None:
+        inv_freq = float(theta) ** (-2.0 * np.arange(half) / head_dim)
+        ang = pos[:, None] * inv_freq[None, :]
+        cos, sin = np.cos(ang), np.sin(ang)
+    for x, heads, gamma in ((q, n_heads, gamma_q), (k, n_kv_heads, gamma_k)):
+        for h in range(heads):
+            v = x[:, h * head_dim:(h + 1) * head_dim]
+            if gamma is not None:
+                v = rms_norm(v, gamma, norm_eps)
+            if theta is not None:
+                a, b = v[:, :half], v[:, half:]
+                v = np.concatenate([a * cos - b * sin, b * cos + a * sin], axis=1)
+            x[:, h * head_dim:(h + 1) * head_dim] = v
+    return _zo._round_out(q, dtype), _zo._round_out(k, dtype)
+
+
+def swiglu(gu, dtype="f64"):
+    gu = np.asarray(gu, np.float64)
+    f = gu.shape[1] // 2
+    g, u = gu[:, :f], gu[:, f:]
+    return _zo._round_out(g / (1.0 + np.exp(-g)) * u, dtype)
+
+
 def block_forward(batch, x, blk, r, eps, dtype, store=None):
     """One pre-norm decoder block under the batch's candidate table.
 
     blk: object with attributes norm_kind, norm_eps, g1, b1, g2, b2 (b* None
     for RMS norm), n_heads, n_kv_heads, head_dim, scale and the four layers
-    qkv, o, fc1, fc2 (each with W, bias, tensor_id, act, P, Vb, R_used).
+    qkv, o, fc1, fc2 (each with W, bias, tensor_id, act, P, Vb, R_used).  Optional attributes
+    select the Qwen3 form: gq, gk (per-head RMS norm gains of queries and keys), rope_theta (rotary
+    embedding), gated (fc1 is the fused [gate | up] projection and feeds swiglu).
     dtype is the type of the generated factors; every intermediate is rounded
     to the storage type `store` (default: dtype), as a kernel that writes it to
     memory does.  Returns a dict of all intermediates."""
@@ -119,14 +160,20 @@ def block_forward(batch, x, blk, r, eps, dtype, store=None):
     nkv = blk.n_kv_heads * blk.head_dim
     _, a1 = add_norm(x, None, blk.g1, blk.b1, blk.norm_kind, blk.norm_eps, store)
     qkv = lin(blk.qkv, a1)
-    att = attention(qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:nq + 2 * nkv], batch.cu_seqlens,
-                    blk.n_heads, blk.n_kv_heads, blk.head_dim, blk.scale, store)
+    q, k, v = qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:nq + 2 * nkv]
+    gq, theta = getattr(blk, "gq", None), getattr(blk, "rope_theta", None)
+    if gq is not None or theta is not None:
+        q, k = qk_norm_rope(q, k, batch.cu_seqlens, blk.n_heads, blk.n_kv_heads, blk.head_dim, gq,
+                            getattr(blk, "gk", None), blk.norm_eps, theta, store)
+    att = attention(q, k, v, batch.cu_seqlens, blk.n_heads, blk.n_kv_heads, blk.head_dim, blk.scale, store)
     o = lin(blk.o, att)
     h1, a2 = add_norm(x, o, blk.g2, blk.b2, blk.norm_kind, blk.norm_eps, store)
     f1 = lin(blk.fc1, a2)
+    if getattr(blk, "gated", False):
+        f1 = swiglu(f1, store)
     f2 = lin(blk.fc2, f1)
     h2 = _zo._round_out(np.asarray(h1, np.float64) + f2, store)
-    return dict(a1=a1, qkv=qkv, att=att, o=o, h1=h1, a2=a2, f1=f1, f2=f2, h2=h2)
+    return dict(a1=a1, qkv=qkv, q=q, k=k, att=att, o=o, h1=h1, a2=a2, f1=f1, f2=f2, h2=h2)
 
 
 def model_forward(batch, x, blocks, final_norm, head, targets, r, eps, dtype, reduction, store=None):

@@ -331,3 +331,101 @@ def test_model_antithetic_losses_average_to_the_centre_loss_to_second_order():
     assert abs(gaps[0]) > 1e-9
     np.testing.assert_allclose(gaps[0] / gaps[1], 4.0, rtol=0.15)
     np.testing.assert_allclose(gaps[1] / gaps[2], 4.0, rtol=0.15)
+
+
+# ---------------------------------------------------------------- Qwen3-family pieces
+
+def test_rope_is_a_complex_rotation_of_each_pair():
+    """The pair (x[i], x[i + dh/2]) as a complex number is multiplied by exp(1j * p * theta^(-2i/dh))."""
+    dh, H, T = 16, 2, 11
+    g = _rng(60)
+    q = g.normal(size=(T, H * dh)); k = g.normal(size=(T, dh))
+    cu = [0, 4, 4, 11]
+    theta = 10000.0
+    gq, gk = zb.qk_norm_rope(q, k, cu, H, 1, dh, None, None, 0.0, theta)
+    pos = np.array([0, 1, 2, 3, 0, 1, 2, 3, 4, 5, 6])
+    freq = theta ** (-2.0 * np.arange(dh // 2) / dh)
+    rot = np.exp(1j * pos[:, None] * freq[None, :])
+    for x, got, heads in ((q, gq, H), (k, gk, 1)):
+        for h in range(heads):
+            z = (x[:, h * dh:h * dh + dh // 2] + 1j * x[:, h * dh + dh // 2:(h + 1) * dh]) * rot
+            np.testing.assert_allclose(got[:, h * dh:h * dh + dh // 2], z.real, rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(got[:, h * dh + dh // 2:(h + 1) * dh], z.imag, rtol=1e-12, atol=1e-13)
+
+
+def test_rope_identity_at_position_zero_norm_preservation_and_relative_positions():
+    dh, T = 8, 9
+    g = _rng(61)
+    q = g.normal(size=(T, dh)); k = g.normal(size=(T, dh))
+    gq, gk = zb.qk_norm_rope(q, k, [0, 3, 9], 1, 1, dh, None, None, 0.0, 500.0)
+    np.testing.assert_array_equal(gq[[0, 3]], q[[0, 3]])                      # first row of each sequence
+    np.testing.assert_allclose((gq ** 2).sum(1), (q ** 2).sum(1), rtol=1e-12)
+    # <rope(a, p1), rope(b, p2)> depends on p1 - p2 only: the same two vectors at positions (1, 4) and (2, 5)
+    a, b = g.normal(size=dh), g.normal(size=dh)
+    rows = np.tile(a, (6, 1)); keys = np.tile(b, (6, 1))
+    rq, rk = zb.qk_norm_rope(rows, keys, [0, 6], 1, 1, dh, None, None, 0.0, 500.0)
+    np.testing.assert_allclose(rq[4] @ rk[1], rq[5] @ rk[2], rtol=1e-12)
+    assert abs(rq[4] @ rk[1] - rq[4] @ rk[2]) > 1e-6
+
+
+def test_qk_norm_matches_library_rms_norm_per_head():
+    dh, H, Hkv, T = 16, 3, 1, 5
+    g = _rng(62)
+    q = g.normal(size=(T, H * dh)) * 3; k = g.normal(size=(T, Hkv * dh)) * 0.2
+    gam_q, gam_k = 1 + 0.1 * g.normal(size=dh), 1 + 0.1 * g.normal(size=dh)
+    gq, gk = zb.qk_norm_rope(q, k, [0, T], H, Hkv, dh, gam_q, gam_k, 1e-6, None)
+    want_q = torch.nn.functional.rms_norm(torch.tensor(q).reshape(T, H, dh), (dh,), torch.tensor(gam_q), 1e-6)
+    want_k = torch.nn.functional.rms_norm(torch.tensor(k).reshape(T, Hkv, dh), (dh,), torch.tensor(gam_k), 1e-6)
+    np.testing.assert_allclose(gq, want_q.reshape(T, H * dh).numpy(), rtol=1e-12)
+    np.testing.assert_allclose(gk, want_k.reshape(T, Hkv * dh).numpy(), rtol=1e-12)
+    # the norm comes before the rotation: norm, then rotate == the function with both switched on
+    both_q, both_k = zb.qk_norm_rope(q, k, [0, T], H, Hkv, dh, gam_q, gam_k, 1e-6, 1e4)
+    rq, rk = zb.qk_norm_rope(gq, gk, [0, T], H, Hkv, dh, None, None, 0.0, 1e4)
+    np.testing.assert_allclose(both_q, rq, rtol=1e-13)
+    np.testing.assert_allclose(both_k, rk, rtol=1e-13)
+
+
+def test_swiglu_matches_library_silu():
+    g = _rng(63)
+    gu = g.normal(size=(7, 24)) * 3
+    want = torch.nn.functional.silu(torch.tensor(gu[:, :12])) * torch.tensor(gu[:, 12:])
+    np.testing.assert_allclose(zb.swiglu(gu), want.numpy(), rtol=1e-12, atol=1e-14)
+
+
+def test_gated_rotary_block_foreground_equals_a_plain_torch_block():
+    """The Qwen3 form of the block (RMS norms, per-head q/k norms, rotary embedding, grouped heads, gated
+    MLP), all sequences foreground, against the same block rebuilt from torch functions."""
+    d, H, Hkv, dh, F_, theta = 32, 4, 2, 8, 40, 1e4
+    blk = _block(64, d, H, Hkv, dh, F_, zb.RMS_NORM)
+    g = _rng(65)
+    blk.fc1 = _layer(g, 2 * F_, d, 14, act=0, bias=False)
+    blk.fc2 = _layer(g, d, F_, 16, bias=False)
+    blk.qkv.bias = blk.o.bias = None
+    blk.gq, blk.gk, blk.rope_theta, blk.gated = 1 + 0.1 * g.normal(size=dh), 1 + 0.1 * g.normal(size=dh), theta, True
+    lens = [6, 9]
+    batch = _batch(lens, [-1, -1], [0, 0], [1, -1], [7])
+    x = g.normal(size=(sum(lens), d))
+    got = zb.block_forward(batch, x, blk, 4, 1e-3, "f32", "f64")["h2"]
+    F = torch.nn.functional
+    t = lambda a: torch.tensor(np.asarray(a, np.float64))
+
+    def rope(z):                       # z [L, heads, dh]
+        L = z.shape[0]
+        freq = theta ** (-2.0 * torch.arange(dh // 2, dtype=torch.float64) / dh)
+        ang = torch.arange(L, dtype=torch.float64)[:, None] * freq[None, :]
+        cos, sin = torch.cos(ang)[:, None, :], torch.sin(ang)[:, None, :]
+        a, b = z[..., :dh // 2], z[..., dh // 2:]
+        return torch.cat([a * cos - b * sin, b * cos + a * sin], dim=-1)
+    want = []
+    for lo, hi in ((0, 6), (6, 15)):
+        h0 = t(x[lo:hi]); L = hi - lo
+        qkv = F.linear(F.rms_norm(h0, (d,), t(blk.g1), blk.norm_eps), t(blk.qkv.W))
+        q = rope(F.rms_norm(qkv[:, :H * dh].reshape(L, H, dh), (dh,), t(blk.gq), blk.norm_eps))
+        k = rope(F.rms_norm(qkv[:, H * dh:(H + Hkv) * dh].reshape(L, Hkv, dh), (dh,), t(blk.gk), blk.norm_eps))
+        v = qkv[:, (H + Hkv) * dh:].reshape(L, Hkv, dh)
+        att = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None], v.permute(1, 0, 2)[None],
+                                             is_causal=True, enable_gqa=True)[0].permute(1, 0, 2).reshape(L, H * dh)
+        h1 = h0 + F.linear(att, t(blk.o.W))
+        gu = F.linear(F.rms_norm(h1, (d,), t(blk.g2), blk.norm_eps), t(blk.fc1.W))
+        want.append((h1 + F.linear(F.silu(gu[:, :F_]) * gu[:, F_:], t(blk.fc2.W))).numpy())
+    np.testing.assert_allclose(got, np.concatenate(want), rtol=1e-9, atol=1e-11)
