@@ -69,6 +69,7 @@ def _block_section(name, n_rep):
     stages = [
         ("norm1", lambda: blk.add_norm(x, None, blk.g1, blk.b1, None, blk.a1, st)),
         ("qkv", lambda: d.probe_linear(0, blk.a1, st)),
+        ("qk_norm_rope", lambda: blk.qk_norm_rope(d.Y[0], st)),
         ("attention", lambda: blk.attention(d.Y[0], blk.att, st)),
         ("o", lambda: d.probe_linear(1, blk.att, st)),
         ("add_norm2", lambda: blk.add_norm(x, d.Y[1], blk.g2, blk.b2, blk.h1, blk.a2, st)),
@@ -76,7 +77,8 @@ def _block_section(name, n_rep):
         ("fc2", lambda: d.probe_linear(3, d.Y[2], st)),
         ("residual", lambda: blk.add_norm(blk.h1, d.Y[3], None, None, blk.h2, None, st)),
     ]
-
+    if not b.rope_theta and b.gq is None:
+        stages.pop(2)
     def timed(fn):
         fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -97,7 +99,8 @@ def _block_section(name, n_rep):
     gemm_flops = sum(2.0 * T * l.m * l.n for l in w.layers)
     gemm_ms = ms["qkv"] + ms["o"] + ms["fc1"] + ms["fc2"]
     return {"workload": w.name, "rows": T, "hidden": hid, "heads": [b.n_heads, b.n_kv_heads, b.head_dim],
-            "norm": "layer" if b.norm_kind == 0 else "rms", "block_ms": block_ms, "stage_ms": ms,
+            "norm": "layer" if b.norm_kind == 0 else "rms", "qk_norm_rope": bool(b.rope_theta), "gated_mlp": b.fc1.act == 2,
+            "block_ms": block_ms, "stage_ms": ms,
             "tokens_per_s": T / (block_ms * 1e-3),
             "attention": {"tflops_causal": att_flops / (ms["attention"] * 1e-3) / 1e12,
                           "gbs": att_bytes / (ms["attention"] * 1e-3) / 1e9,

@@ -154,7 +154,9 @@ int32_t zo_batch_index(const zo_batch* batch, int32_t* tok_seq, int32_t* tok_can
  *             on the vector ALU; ZO_BF16: bf16 operands, fp32 accumulation on
  *             the matrix cores, U and V rounded to bf16)
  *   out_dtype type of Y: equal to in_dtype, or ZO_F32 with ZO_BF16 inputs
- *   bias      fp32 [m] or NULL;  act 0 = none, 1 = ReLU
+ *   bias      fp32 [m] or NULL;  act 0 = none, 1 = ReLU, 2 = gated SiLU (the gated MLP of the
+ *             Qwen3 family): output features are (gate_j, up_j) pairs in adjacent rows of W and
+ *             Y[t, j] = silu(gate_j) * up_j, silu(x) = x / (1 + exp(-x)); Y then has m/2 columns
  *   r         rank of the probe, 1..64;  eps probe scale;  tensor_id even id of the layer
  *   bank      NULL or R_used = 0: no bank
  * ZO_BF16 requires n % 64 == 0 (and m % 8 == 0 for bf16 output), 16-byte aligned X, W, Y and leading dimensions
@@ -353,6 +355,24 @@ int32_t zo_attention(const zo_batch* batch, const void* Q, int64_t ldq, const vo
                      const void* V, int64_t ldv, int32_t n_heads, int32_t n_kv_heads,
                      int32_t head_dim, float scale, zo_dtype dtype, void* O, int64_t ldo,
                      void* stream);
+
+/*
+ * The extra joining operation of the Qwen3 family (standard definitions; the paper
+ * evaluates Qwen3-8B but does not spell them out; the family's gated MLP is
+ * activation 2 of zo_probe_linear).
+ *
+ * zo_qk_norm_rope, in place on the query and key rows (column ranges of the fused
+ * projection output, as for zo_attention): per head
+ *   x <- x / sqrt(mean(x^2) + norm_eps) * gamma          (gamma_q for queries, gamma_k for keys,
+ *                                                         fp32 [head_dim]; both NULL: no norm)
+ * and then the rotary embedding: with p the row's offset in its own sequence,
+ *   (x[i], x[i + head_dim/2]) <- rotation of that pair by the angle p * rope_theta^(-2i/head_dim)
+ * (rope_theta <= 0: no rotation).  head_dim even, <= 256; one rounding to dtype.
+ */
+int32_t zo_qk_norm_rope(const zo_batch* batch, void* Q, int64_t ldq, void* K, int64_t ldk,
+                        int32_t n_heads, int32_t n_kv_heads, int32_t head_dim,
+                        const float* gamma_q, const float* gamma_k, float norm_eps,
+                        float rope_theta, zo_dtype dtype, void* stream);
 
 #ifdef __cplusplus
 }

@@ -24,8 +24,8 @@ definitions of the model families it evaluates, written here directly:
   qk_norm_rope (Qwen3 family) per head: q, k <- rms_norm over the head dimension, then the
                rotary embedding: the pair (x[i], x[i + dh/2]) of a row at position p of its
                sequence is rotated by the angle p * theta^(-2i/dh)
-  swiglu       (gated MLP) a[j] = silu(g[j]) * u[j] for the fused projection output [g | u],
-               silu(x) = x / (1 + exp(-x))
+  gated MLP    fc1 is the fused gate/up projection with activation 2 of the probe linear
+               (silu(gate_j) * up_j over adjacent output features), fc2 maps the ffn columns back
 
 Nothing here is blocked, fused or reordered: scores are formed in full per
 sequence and head.  Pins: tests/test_oracle_block.py (library routines on
@@ -133,13 +133,6 @@ def qk_norm_rope(q, k, cu_seqlens, n_heads, n_kv_heads, head_dim, gamma_q, gamma
     return _zo._round_out(q, dtype), _zo._round_out(k, dtype)
 
 
-def swiglu(gu, dtype="f64"):
-    gu = np.asarray(gu, np.float64)
-    f = gu.shape[1] // 2
-    g, u = gu[:, :f], gu[:, f:]
-    return _zo._round_out(g / (1.0 + np.exp(-g)) * u, dtype)
-
-
 def block_forward(batch, x, blk, r, eps, dtype, store=None):
     """One pre-norm decoder block under the batch's candidate table.
 
@@ -147,7 +140,7 @@ def block_forward(batch, x, blk, r, eps, dtype, store=None):
     for RMS norm), n_heads, n_kv_heads, head_dim, scale and the four layers
     qkv, o, fc1, fc2 (each with W, bias, tensor_id, act, P, Vb, R_used).  Optional attributes
     select the Qwen3 form: gq, gk (per-head RMS norm gains of queries and keys), rope_theta (rotary
-    embedding), gated (fc1 is the fused [gate | up] projection and feeds swiglu).
+    embedding); a gated MLP is simply fc1.act == 2 (fused gate/up projection, half as many outputs).
     dtype is the type of the generated factors; every intermediate is rounded
     to the storage type `store` (default: dtype), as a kernel that writes it to
     memory does.  Returns a dict of all intermediates."""
@@ -169,8 +162,6 @@ def block_forward(batch, x, blk, r, eps, dtype, store=None):
     o = lin(blk.o, att)
     h1, a2 = add_norm(x, o, blk.g2, blk.b2, blk.norm_kind, blk.norm_eps, store)
     f1 = lin(blk.fc1, a2)
-    if getattr(blk, "gated", False):
-        f1 = swiglu(f1, store)
     f2 = lin(blk.fc2, f1)
     h2 = _zo._round_out(np.asarray(h1, np.float64) + f2, store)
     return dict(a1=a1, qkv=qkv, q=q, k=k, att=att, o=o, h1=h1, a2=a2, f1=f1, f2=f2, h2=h2)

@@ -138,7 +138,9 @@ def _round_out(Y, out_dtype):
 
 def probe_linear(batch: Batch, X, W, r, eps, tensor_id, bank: Optional[Bank] = None,
                  bias=None, act=0, factor_dtype="f32", out_dtype="f64", rows=None):
-    """Y[t, :] = act(X[t, :] W_{cand(t)}^T + bias), rounded to out_dtype.
+    """Y[t, :] = act(X[t, :] W_{cand(t)}^T + bias), rounded to out_dtype.  act 0 = none, 1 = ReLU,
+    2 = gated SiLU: the m output features are (gate_j, up_j) pairs in adjacent rows of W and the
+    result is silu(gate_j) * up_j, m/2 columns, silu(x) = x / (1 + exp(-x)).
 
     rows: optional index array restricting the computation to those token
     rows (the returned array then has len(rows) rows, in that order).
@@ -157,6 +159,10 @@ def probe_linear(batch: Batch, X, W, r, eps, tensor_id, bank: Optional[Bank] = N
         Y += np.asarray(bias, dtype=np.float64)[None, :]
     if act == 1:
         Y = np.maximum(Y, 0.0)
+    elif act == 2:
+        # gated MLP: output features come in (gate, up) pairs; the layer returns m/2 columns
+        gate, up = Y[:, 0::2], Y[:, 1::2]
+        Y = gate / (1.0 + np.exp(-gate)) * up
     elif act != 0:
         raise ValueError(act)
     return _round_out(Y, out_dtype)

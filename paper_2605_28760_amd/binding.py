@@ -84,6 +84,9 @@ _PROTOS = {
     "zo_attention": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p,
                                  C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_float, C.c_int, C.c_void_p,
                                  C.c_int64, C.c_void_p]),
+    "zo_qk_norm_rope": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
+                                    C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_int,
+                                    C.c_void_p]),
 }
 EXPORTS = tuple(_PROTOS)
 
@@ -242,3 +245,9 @@ def zo_add_norm(X, ldx, R, ldr, gamma, beta, kind, norm_eps, n_tokens, d, dtype,
 def zo_attention(batch, Q, ldq, K, ldk, V, ldv, n_heads, n_kv_heads, head_dim, scale, dtype, O, ldo, stream=None):
     _check(lib().zo_attention(C.byref(batch), _ptr(Q), ldq, _ptr(K), ldk, _ptr(V), ldv, n_heads, n_kv_heads,
                               head_dim, scale, dtype, _ptr(O), ldo, _stream(stream)))
+
+
+def zo_qk_norm_rope(batch, Q, ldq, K, ldk, n_heads, n_kv_heads, head_dim, gamma_q, gamma_k, norm_eps, rope_theta,
+                    dtype, stream=None):
+    _check(lib().zo_qk_norm_rope(C.byref(batch), _ptr(Q), ldq, _ptr(K), ldk, n_heads, n_kv_heads, head_dim,
+                                 _ptr(gamma_q), _ptr(gamma_k), norm_eps, rope_theta, dtype, _stream(stream)))

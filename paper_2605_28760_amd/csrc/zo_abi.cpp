@@ -233,7 +233,9 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   if (in_dtype != ZO_F32 && in_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "in_dtype %d", (int)in_dtype);
   if (!(out_dtype == in_dtype || (in_dtype == ZO_BF16 && out_dtype == ZO_F32)))
     return fail(ZO_ERR_UNSUPPORTED, "in_dtype %d with out_dtype %d", (int)in_dtype, (int)out_dtype);
-  if (act != 0 && act != 1) return fail(ZO_ERR_UNSUPPORTED, "activation %d", act);
+  if (act < 0 || act > 2) return fail(ZO_ERR_UNSUPPORTED, "activation %d", act);
+  if (act == 2 && m % 2 != 0) return fail(ZO_ERR_SHAPE, "the gated activation pairs output features: m = %d is odd", m);
+  const int m_out = act == 2 ? m / 2 : m;   // columns of Y
   const int T = batch->n_tokens;
   int R = 0;
   if (bank) {
@@ -246,11 +248,11 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   if (!X || !W || !Y) return fail(ZO_ERR_NULL, "X, W or Y is NULL");
   if (int32_t st = check_matrix("X", X, ldx, n, in_dtype)) return st;
   if (int32_t st = check_matrix("W", W, ldw, n, in_dtype)) return st;
-  if (int32_t st = check_matrix("Y", Y, ldy, m, out_dtype)) return st;
+  if (int32_t st = check_matrix("Y", Y, ldy, m_out, out_dtype)) return st;
   if (in_dtype == ZO_BF16 && (n % zo::kTileK != 0 || n == 0))
     return fail(ZO_ERR_UNSUPPORTED, "bf16 path needs n %% %d == 0 (n = %d)", zo::kTileK, n);
-  if (out_dtype == ZO_BF16 && m % 8 != 0)
-    return fail(ZO_ERR_UNSUPPORTED, "bf16 output needs m %% 8 == 0 (m = %d)", m);
+  if (out_dtype == ZO_BF16 && m_out % 8 != 0)
+    return fail(ZO_ERR_UNSUPPORTED, "bf16 output needs a multiple of 8 output columns (m = %d, activation %d)", m, act);
   const ProbePlan plan = plan_probe(T, batch->n_seqs, batch->n_dirs, m, n, r, R, in_dtype);
   if (!workspace) return fail(ZO_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total);
   if (((uintptr_t)workspace & 255u) != 0) return fail(ZO_ERR_WORKSPACE, "workspace not 256-byte aligned");
@@ -557,6 +559,30 @@ int32_t zo_attention(const zo_batch* batch, const void* Q, int64_t ldq, const vo
   a.cu = batch->cu_seqlens; a.S = batch->n_seqs; a.T = batch->n_tokens;
   a.n_heads = n_heads; a.group = n_heads / n_kv_heads; a.dh = head_dim; a.scale = scale; a.bf16 = dtype == ZO_BF16;
   ZO_HIP(zo::launch_attention(a, (hipStream_t)stream), "zo_attention");
+  return ZO_OK;
+}
+
+int32_t zo_qk_norm_rope(const zo_batch* batch, void* Q, int64_t ldq, void* K, int64_t ldk, int32_t n_heads,
+                        int32_t n_kv_heads, int32_t head_dim, const float* gamma_q, const float* gamma_k,
+                        float norm_eps, float rope_theta, zo_dtype dtype, void* stream) {
+  if (int32_t st = check_batch(batch)) return st;
+  if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
+  if (n_heads < 1 || n_kv_heads < 1 || head_dim < 2)
+    return fail(ZO_ERR_SHAPE, "n_heads = %d, n_kv_heads = %d, head_dim = %d", n_heads, n_kv_heads, head_dim);
+  if (head_dim % 2 != 0 || head_dim > 256)
+    return fail(ZO_ERR_UNSUPPORTED, "head_dim = %d: even values up to 256 are covered", head_dim);
+  if ((gamma_q == nullptr) != (gamma_k == nullptr)) return fail(ZO_ERR_NULL, "gamma_q and gamma_k go together");
+  if (!(norm_eps >= 0.0f)) return fail(ZO_ERR_SHAPE, "norm_eps = %g", (double)norm_eps);
+  if ((int64_t)n_heads * head_dim > kMaxLd) return fail(ZO_ERR_SHAPE, "n_heads * head_dim too large");
+  if (batch->n_tokens == 0) return ZO_OK;
+  if (!Q || !K) return fail(ZO_ERR_NULL, "Q or K is NULL");
+  if (int32_t st = check_matrix("Q", Q, ldq, n_heads * head_dim, dtype)) return st;
+  if (int32_t st = check_matrix("K", K, ldk, n_kv_heads * head_dim, dtype)) return st;
+  zo::QkRopeArgs a;
+  a.Q = Q; a.ldq = ldq; a.K = K; a.ldk = ldk; a.cu = batch->cu_seqlens; a.S = batch->n_seqs; a.T = batch->n_tokens;
+  a.n_heads = n_heads; a.n_kv_heads = n_kv_heads; a.dh = head_dim; a.gamma_q = gamma_q; a.gamma_k = gamma_k;
+  a.eps = norm_eps; a.theta = rope_theta > 0.0f ? rope_theta : 0.0f; a.bf16 = dtype == ZO_BF16;
+  ZO_HIP(zo::launch_qk_norm_rope(a, (hipStream_t)stream), "zo_qk_norm_rope");
   return ZO_OK;
 }
 

@@ -8,6 +8,8 @@
 //                                      the row stays in registers between the passes (HBM-bound)
 //   k_attention_bf16                   online-softmax attention on 16x16x32 bf16 MFMA, head_dim 128
 //   k_attention_f32                    plain fp32 attention on the vector ALU (any head_dim <= 256)
+//   k_qk_norm_rope_*                   per-head RMS norm of queries and keys + rotary embedding, in place
+//                                      (the Qwen3 family; its gated MLP is an epilogue of the probe linear)
 #include "zo_device.hpp"
 #include "zo_internal.hpp"
 
@@ -513,7 +515,140 @@ __global__ __launch_bounds__(kAttnWaves* kWave, 2) void k_attention_bf16(AttnArg
   }
 }
 
+// ------------------------------------------------------------------ per-head q/k norm + rotary embedding
+
+// Rotation angle of pair i (of dh/2) at position pos: pos * theta^(-2i/dh).
+__device__ __forceinline__ float rope_angle(float log2_theta, int i, int dh, int pos) {
+  return (float)pos * exp2f(-(float)(2 * i) / (float)dh * log2_theta);
+}
+
+// bf16, head dimension 128, in place.  A wave takes four heads of one token: the 16 lanes of a head hold
+// elements 4j..4j+3 and their rotation partners 64+4j..64+4j+3 (j = lane % 16), so the per-head sum of
+// squares is four shuffles and the rotation is lane-local.  Heads 0..H-1 are queries, H..H+Hkv-1 keys.
+__global__ __launch_bounds__(256) void k_qk_norm_rope_bf16(QkRopeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int groups = (a.n_heads + a.n_kv_heads + 3) >> 2;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= (int64_t)a.T * groups) return;
+  const int t = (int)(item / groups), head = (int)(item % groups) * 4 + (lane >> 4);
+  const int j = lane & 15;
+  const bool live = head < a.n_heads + a.n_kv_heads;
+  const bool is_q = head < a.n_heads;
+  bf16_t* row = nullptr;
+  if (live)
+    row = is_q ? (bf16_t*)a.Q + (int64_t)t * a.ldq + head * 128 : (bf16_t*)a.K + (int64_t)t * a.ldk + (head - a.n_heads) * 128;
+  float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // [0..3] first half, [4..7] partners
+  if (live) {
+    const uint2 lo = *reinterpret_cast<const uint2*>(row + 4 * j), hi = *reinterpret_cast<const uint2*>(row + 64 + 4 * j);
+    x[0] = __uint_as_float(lo.x << 16); x[1] = __uint_as_float(lo.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(lo.y << 16); x[3] = __uint_as_float(lo.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(hi.x << 16); x[5] = __uint_as_float(hi.x & 0xFFFF0000u);
+    x[6] = __uint_as_float(hi.y << 16); x[7] = __uint_as_float(hi.y & 0xFFFF0000u);
+  }
+  if (a.gamma_q) {
+    float ss = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+    const float rstd = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
+    const float* gam = is_q ? a.gamma_q : a.gamma_k;
+    const float4 g0 = *reinterpret_cast<const float4*>(gam + 4 * j), g1 = *reinterpret_cast<const float4*>(gam + 64 + 4 * j);
+    x[0] *= rstd * g0.x; x[1] *= rstd * g0.y; x[2] *= rstd * g0.z; x[3] *= rstd * g0.w;
+    x[4] *= rstd * g1.x; x[5] *= rstd * g1.y; x[6] *= rstd * g1.z; x[7] *= rstd * g1.w;
+  }
+  if (a.theta > 0.f) {
+    const int pos = t - a.cu[seq_of_row(a.cu, a.S, t)];
+    const float l2t = log2f(a.theta);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float sn, cs;
+      sincosf(rope_angle(l2t, 4 * j + e, 128, pos), &sn, &cs);
+      const float p = x[e], q = x[4 + e];
+      x[e] = p * cs - q * sn;
+      x[4 + e] = q * cs + p * sn;
+    }
+  }
+  if (live) {
+    *reinterpret_cast<uint2*>(row + 4 * j) = make_uint2(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]));
+    *reinterpret_cast<uint2*>(row + 64 + 4 * j) = make_uint2(pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+  }
+}
+
+// Any even head dimension up to 256 and either storage type: one wave per (token, head), lane l holds the
+// pairs l and l + 64.  With fp32 storage the angle is formed in double precision, so that positions in the
+// thousands still give angles good to fp32 rounding.
+template <typename Tio>
+__global__ __launch_bounds__(256) void k_qk_norm_rope_any(QkRopeArgs a) {
+  const int lane = threadIdx.x & 63;
+  const int heads = a.n_heads + a.n_kv_heads;
+  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (item >= (int64_t)a.T * heads) return;
+  const int t = (int)(item / heads), head = (int)(item % heads);
+  const bool is_q = head < a.n_heads;
+  const int dh = a.dh, half = dh >> 1;
+  Tio* row = is_q ? (Tio*)a.Q + (int64_t)t * a.ldq + head * dh : (Tio*)a.K + (int64_t)t * a.ldk + (head - a.n_heads) * dh;
+  float lo[2], hi[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int i = lane + c * kWave;
+    lo[c] = i < half ? ld_elem(row, i) : 0.f;
+    hi[c] = i < half ? ld_elem(row, half + i) : 0.f;
+  }
+  if (a.gamma_q) {
+    const float ss = wave_sum(lo[0] * lo[0] + hi[0] * hi[0] + lo[1] * lo[1] + hi[1] * hi[1]);
+    const float rstd = 1.0f / sqrtf(ss / (float)dh + a.eps);
+    const float* gam = is_q ? a.gamma_q : a.gamma_k;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int i = lane + c * kWave;
+      if (i < half) { lo[c] *= rstd * gam[i]; hi[c] *= rstd * gam[half + i]; }
+    }
+  }
+  if (a.theta > 0.f) {
+    const int pos = t - a.cu[seq_of_row(a.cu, a.S, t)];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int i = lane + c * kWave;
+      if (i >= half) continue;
+      float sn, cs;
+      if (sizeof(Tio) == 4) {
+        double dsn, dcs;
+        sincos((double)pos * exp2(-(double)(2 * i) / (double)dh * log2((double)a.theta)), &dsn, &dcs);
+        sn = (float)dsn; cs = (float)dcs;
+      } else {
+        sincosf(rope_angle(log2f(a.theta), i, dh, pos), &sn, &cs);
+      }
+      const float p = lo[c], q = hi[c];
+      lo[c] = p * cs - q * sn;
+      hi[c] = q * cs + p * sn;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    const int i = lane + c * kWave;
+    if (i < half) { st_elem(row, i, lo[c]); st_elem(row, half + i, hi[c]); }
+  }
+}
+
 }  // namespace
+
+hipError_t launch_qk_norm_rope(const QkRopeArgs& a, hipStream_t st) {
+  if (a.T == 0 || (!a.gamma_q && !(a.theta > 0.f))) return hipSuccess;
+  const int heads = a.n_heads + a.n_kv_heads;
+  auto aligned = [](const void* p, int64_t ld) { return ((uintptr_t)p & 7u) == 0 && ld % 4 == 0; };
+  const bool fast = a.bf16 && a.dh == 128 && aligned(a.Q, a.ldq) && aligned(a.K, a.ldk) &&
+                    (((uintptr_t)a.gamma_q | (uintptr_t)a.gamma_k) & 15u) == 0;
+  if (fast) {
+    const int64_t items = (int64_t)a.T * ((heads + 3) / 4);
+    k_qk_norm_rope_bf16<<<dim3((unsigned)((items + 3) / 4)), 256, 0, st>>>(a);
+  } else {
+    const int64_t items = (int64_t)a.T * heads;
+    if (a.bf16) k_qk_norm_rope_any<bf16_t><<<dim3((unsigned)((items + 3) / 4)), 256, 0, st>>>(a);
+    else k_qk_norm_rope_any<float><<<dim3((unsigned)((items + 3) / 4)), 256, 0, st>>>(a);
+  }
+  return hipGetLastError();
+}
 
 hipError_t launch_add_norm(const NormArgs& a, hipStream_t st) {
   if (a.T == 0 || a.d == 0) return hipSuccess;

@@ -322,7 +322,10 @@ static int gemm_grid(int total_tiles) {
 // state a plain GEMM starts from, so foreground rows come out bit-identical to an
 // all-foreground call.
 // ---------------------------------------------------------------------------------------
-template <bool kSide, bool kOutBf16, bool kBias>
+// silu(gate) * up, the gated-MLP epilogue (activation 2): adjacent output features are (gate, up) pairs
+__device__ __forceinline__ float silu_mul(float gate, float up) { return gate / (1.0f + __expf(-gate)) * up; }
+
+template <bool kSide, bool kOutBf16, bool kBias, bool kGate>
 __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
@@ -407,15 +410,58 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
         const int t = tbase + cb * 16 + r16;
         if (t >= p.T) continue;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < RB; ++rb) {
+          const int o0 = obase + rb * 16 + 4 * g;   // this lane's 4 consecutive out features
+          float y[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            const int o = obase + rb * 16 + 4 * g + v;
-            if (o >= p.m) continue;
-            float y = acc[rb][cb][v];
-            if constexpr (kBias) y += p.bias[o];
-            Y[(int64_t)t * p.ldy + o] = fmaxf(y, floor_val);
+            y[v] = acc[rb][cb][v];
+            if constexpr (kBias) y[v] += p.bias[min(o0 + v, p.m - 1)];
           }
+          if constexpr (kGate) {   // m is even, so a pair is inside or outside as a whole
+            if (o0 < p.m) Y[(int64_t)t * p.ldy + (o0 >> 1)] = silu_mul(y[0], y[1]);
+            if (o0 + 2 < p.m) Y[(int64_t)t * p.ldy + (o0 >> 1) + 1] = silu_mul(y[2], y[3]);
+          } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              if (o0 + v < p.m) Y[(int64_t)t * p.ldy + o0 + v] = fmaxf(y[v], floor_val);
+          }
+        }
+      }
+      return;
+    }
+    if constexpr (kGate) {
+      // bf16, gated: a lane's 4 features become 2 outputs (one dword); 16 tokens x 64 outputs at a time
+      // through 2 KiB of this wave's LDS region (16-byte slots XOR-swizzled by the token), then 16-byte
+      // stores covering 128 contiguous bytes per token row.
+      char* region = lds + kStagesLds + wave * 4096;
+      bf16_t* Y = (bf16_t*)p.Y;
+      const int chunk = lane_t & 7;             // 8 outputs (16 bytes) of a token row
+      const int oo = (obase >> 1) + chunk * 8;  // first of them
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          float y[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) y[e] = acc[rb][cb][e];
+          if constexpr (kBias) {
+            const int ob = obase + rb * 16 + 4 * g;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] += p.bias[min(ob + e, p.m - 1)];
+          }
+          // outputs rb*8 + 2g, +1 of the token's 64: slot rb, bytes 4g..4g+3
+          *(uint32_t*)(region + r16 * 128 + ((rb ^ (r16 & 7)) << 4) + 4 * g) =
+              pack_bf16x2(silu_mul(y[0], y[1]), silu_mul(y[2], y[3]));
+        }
+        // the wave reads back what it wrote itself: LDS operations of one wave complete in order
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+          const int tl = it * 8 + (lane_t >> 3);
+          const int t = tbase + cb * 16 + tl;
+          const u32x4 val = *(const u32x4_alias*)(region + tl * 128 + ((chunk ^ (tl & 7)) << 4));
+          if (t < p.T && oo < (p.m >> 1)) *(u32x4_alias*)(Y + (int64_t)t * p.ldy + oo) = val;   // m % 16 == 0
+        }
       }
       return;
     }
@@ -460,24 +506,28 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
   persistent_gemm<false>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
 }
 
-template <bool kSide, bool kOutBf16, bool kBias>
+template <bool kSide, bool kOutBf16, bool kBias, bool kGate>
 static hipError_t launch_probe_variant(const ProbeGemmArgs& a, hipStream_t st) {
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias>,
+    hipError_t e = hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias, kGate>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     if (e != hipSuccess) return e;
     configured = true;
   }
   const int n_tm = (a.m + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias>), dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds,
+  hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias, kGate>), dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds,
                      st, a, n_tm, n_tn);
   return hipGetLastError();
 }
 
 template <bool kSide, bool kOutBf16>
 static hipError_t launch_probe_bias(const ProbeGemmArgs& a, hipStream_t st) {
-  return a.bias ? launch_probe_variant<kSide, kOutBf16, true>(a, st) : launch_probe_variant<kSide, kOutBf16, false>(a, st);
+  if (a.act == 2)
+    return a.bias ? launch_probe_variant<kSide, kOutBf16, true, true>(a, st)
+                  : launch_probe_variant<kSide, kOutBf16, false, true>(a, st);
+  return a.bias ? launch_probe_variant<kSide, kOutBf16, true, false>(a, st)
+                : launch_probe_variant<kSide, kOutBf16, false, false>(a, st);
 }
 
 hipError_t launch_probe_gemm_bf16(const ProbeGemmArgs& a, hipStream_t st) {

@@ -209,6 +209,18 @@ struct AttnArgs {
   float scale;
   int bf16;
 };
+struct QkRopeArgs {
+  void* Q; int64_t ldq;             // [T][n_heads * dh], in place
+  void* K; int64_t ldk;             // [T][n_kv_heads * dh], in place
+  const int32_t* cu; int S, T;
+  int n_heads, n_kv_heads, dh;
+  const float* gamma_q; const float* gamma_k;   // both null: no norm
+  float eps;
+  float theta;                      // <= 0: no rotation
+  int bf16;
+};
+hipError_t launch_qk_norm_rope(const QkRopeArgs& a, hipStream_t st);
+
 int attention_f32_max_head_dim();
 int attention_bf16_head_dim();
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);

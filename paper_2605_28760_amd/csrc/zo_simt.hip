@@ -76,9 +76,11 @@ __global__ __launch_bounds__(256) void k_probe_f32(ProbeF32Args p) {
     if (t >= p.T) continue;
     int kind = kKindForeground;
     if (p.has_side) kind = p.seq_kind[p.tok_seq[t]];
+    float y4[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int mm = n0 + tx * 4 + j;
+      y4[j] = 0.0f;
       if (mm >= p.m) continue;
       float y = acc[i][j];
       if (kind >= kKindCentre) {   // foreground rows skip the side state entirely
@@ -93,7 +95,15 @@ __global__ __launch_bounds__(256) void k_probe_f32(ProbeF32Args p) {
       }
       if (p.bias) y += p.bias[mm];
       if (p.act == 1) y = fmaxf(y, 0.0f);
-      p.Y[(int64_t)t * p.ldy + mm] = y;
+      y4[j] = y;
+      if (p.act != 2) p.Y[(int64_t)t * p.ldy + mm] = y;
+    }
+    if (p.act == 2) {   // (gate, up) pairs of adjacent output features -> one output column each (m is even)
+#pragma unroll
+      for (int j = 0; j < 4; j += 2) {
+        const int mm = n0 + tx * 4 + j;
+        if (mm < p.m) p.Y[(int64_t)t * p.ldy + (mm >> 1)] = y4[j] / (1.0f + expf(-y4[j])) * y4[j + 1];
+      }
     }
   }
 }

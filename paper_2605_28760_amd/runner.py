@@ -71,7 +71,9 @@ class DeviceWorkload:
         self.targets = None if w.targets is None else torch.from_numpy(np.ascontiguousarray(w.targets, np.int32)).to(self.device)
         b = self.batch
         T = b.T
-        self.Y = [torch.empty((T, l.m), device=self.device, dtype=_tt(self.out_dtype)) for l in self.layers]
+        # a gated layer (activation 2) returns one column per (gate, up) pair of output features
+        self.Y = [torch.empty((T, l.m // 2 if l.act == 2 else l.m), device=self.device, dtype=_tt(self.out_dtype))
+                  for l in self.layers]
         ws = 0
         for l in self.layers:
             R = l.bank.R_used if l.bank is not None else 0
@@ -146,11 +148,24 @@ class DeviceBlock:
         self.a1, self.h1, self.a2, self.h2 = (torch.empty((T, hidden), device=dev, dtype=tt) for _ in range(4))
         self.att = torch.empty((T, blk.n_heads * blk.head_dim), device=dev, dtype=tt)
         self.h0 = None   # block input when it arrives as a pending sum (allocated on first use)
+        # the Qwen3 form
+        self.gq, self.gk = up(getattr(blk, "gq", None)), up(getattr(blk, "gk", None))
+        self.rope_theta = getattr(blk, "rope_theta", None)
 
     def add_norm(self, x, res, gamma, beta, hsum, y, stream=None):
         ld = lambda t: 0 if t is None else t.stride(0)
         zb.zo_add_norm(x, ld(x), res, ld(res), gamma, beta, self.blk.norm_kind, float(self.blk.norm_eps),
                        x.shape[0], x.shape[1], _dt(self.d.dtype), hsum, ld(hsum), y, ld(y), stream)
+
+    def qk_norm_rope(self, qkv, stream=None, batch=None):
+        """Per-head q/k norm and rotary embedding, in place on the projection output (Qwen3 form only)."""
+        b = self.blk
+        if self.gq is None and not self.rope_theta:
+            return
+        nq, nkv = b.n_heads * b.head_dim, b.n_kv_heads * b.head_dim
+        zb.zo_qk_norm_rope((batch or self.d.batch).struct, qkv[:, :nq], qkv.stride(0), qkv[:, nq:nq + nkv],
+                           qkv.stride(0), b.n_heads, b.n_kv_heads, b.head_dim, self.gq, self.gk, float(b.norm_eps),
+                           float(self.rope_theta or 0.0), _dt(self.d.dtype), stream)
 
     def attention(self, qkv, out, stream=None, batch=None):
         b = self.blk
@@ -175,11 +190,12 @@ class DeviceBlock:
             self.add_norm(x, res, self.g1, self.b1, self.h0, self.a1, stream)
             x = self.h0
         qkv = d.probe_linear(i0, self.a1, stream)
+        self.qk_norm_rope(qkv, stream)
         self.attention(qkv, self.att, stream)
         o = d.probe_linear(i0 + 1, self.att, stream)
         self.add_norm(x, o, self.g2, self.b2, self.h1, self.a2, stream)
-        d.probe_linear(i0 + 2, self.a2, stream)
-        f2 = d.probe_linear(i0 + 3, d.Y[i0 + 2], stream)
+        f1 = d.probe_linear(i0 + 2, self.a2, stream)
+        f2 = d.probe_linear(i0 + 3, f1, stream)
         if not last_sum:
             return self.h1, f2
         self.add_norm(self.h1, f2, None, None, self.h2, None, stream)

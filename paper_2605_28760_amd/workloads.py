@@ -47,7 +47,7 @@ class Layer:
     n: int                      # in features
     tensor_id: int              # even id; U uses it, V uses tensor_id | 1
     W: np.ndarray               # [m, n]
-    act: int = 0                # 0 none, 1 ReLU
+    act: int = 0                # 0 none, 1 ReLU, 2 gated SiLU over (gate, up) row pairs: m/2 outputs
     P: Optional[np.ndarray] = None    # [m, R_cap] fp32
     Vb: Optional[np.ndarray] = None   # [n, R_cap] fp32
     R_used: int = 0
@@ -281,12 +281,19 @@ class Block:
     o: Layer
     fc1: Layer
     fc2: Layer
+    # the Qwen3 form: per-head RMS-norm gains of queries and keys and the rotary base; its gated MLP
+    # is fc1 with 2 * ffn output features ((gate_j, up_j) in adjacent rows) and activation 2
+    gq: Optional[np.ndarray] = None
+    gk: Optional[np.ndarray] = None
+    rope_theta: Optional[float] = None
 
 
-def _block_params(cfg, dtype, index, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R):
-    """Block number `index` of a model: its four layers (tensor ids 8*index .. 8*index + 6) and norms."""
+def _block_params(cfg, dtype, index, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R,
+                  qwen=False):
+    """Block number `index` of a model: its four layers (tensor ids 8*index .. 8*index + 6) and norms.
+    qwen: per-head q/k norms, rotary embedding (base 1e6) and a gated MLP instead of fc1 -> ReLU -> fc2."""
     shapes = [("qkv", (n_heads + 2 * n_kv_heads) * head_dim, hidden, 0), ("o", hidden, n_heads * head_dim, 0),
-              ("fc1", ffn, hidden, 1), ("fc2", hidden, ffn, 0)]
+              ("fc1", 2 * ffn if qwen else ffn, hidden, 2 if qwen else 1), ("fc2", hidden, ffn, 0)]
     layers = []
     for i, (nm, m, n, act) in enumerate(shapes):
         sub = 4 * index + i
@@ -297,25 +304,30 @@ def _block_params(cfg, dtype, index, hidden, n_heads, n_kv_heads, head_dim, ffn,
     gains = [np.float32(1) + _normal(cfg, _TAG_NORM, 4 * index + j, (hidden,), 0.1, "f32") for j in range(2)]
     shifts = [_normal(cfg, _TAG_NORM, 4 * index + 2 + j, (hidden,), 0.1, "f32") if norm_kind == 0 else None
               for j in range(2)]
-    return Block(norm_kind, 1e-5 if norm_kind == 0 else 1e-6, gains[0], shifts[0], gains[1], shifts[1],
-                 n_heads, n_kv_heads, head_dim, float(head_dim) ** -0.5, *layers)
+    blk = Block(norm_kind, 1e-5 if norm_kind == 0 else 1e-6, gains[0], shifts[0], gains[1], shifts[1],
+                n_heads, n_kv_heads, head_dim, float(head_dim) ** -0.5, *layers)
+    if qwen:
+        blk.gq = np.float32(1) + _normal(cfg, _TAG_NORM, 1000 + 2 * index, (head_dim,), 0.1, "f32")
+        blk.gk = np.float32(1) + _normal(cfg, _TAG_NORM, 1001 + 2 * index, (head_dim,), 0.1, "f32")
+        blk.rope_theta = 1e6
+    return blk
 
 
 def decoder_block(name, cfg, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, r, eps, R,
-                  batch):
+                  batch, qwen=False):
     """A decoder block on the given batch (the tuple _pair_batch returns): unit-variance input rows,
     weights N(0, 1/fan_in), norm gains around 1, small biases, banks as in the chain workloads."""
     cu, seq_cand, cand_dir, cand_sign, seq_ex, seq_len_a = batch
     K = int(cand_dir.max()) + 1
     X = _replicated_rows(cfg, _TAG_X, seq_ex, seq_len_a, hidden, 1.0, dtype)
-    blk = _block_params(cfg, dtype, 0, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R)
+    blk = _block_params(cfg, dtype, 0, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R, qwen)
     layers = [blk.qkv, blk.o, blk.fc1, blk.fc2]
     return Workload(name, cfg, dtype, r, eps, cu, seq_cand, cand_dir, cand_sign, _seeds(cfg, K), layers, False, X,
                     None, None, 1, {"block": blk})
 
 
 def decoder_model(name, cfg, dtype, n_blocks, hidden, n_heads, n_kv_heads, head_dim, ffn, vocab, norm_kind,
-                  with_bias, r, eps, R, batch, reduction=0):
+                  with_bias, r, eps, R, batch, reduction=0, qwen=False):
     """n_blocks decoder blocks, a final norm and an LM head on the given batch: the teacher-forced scoring
     pass of a whole (randomly initialised) model.  workload.layers holds the 4 * n_blocks probed linears in
     execution order; meta["blocks"] their blocks; meta["final_norm"] = (gain, shift or None)."""
@@ -323,7 +335,7 @@ def decoder_model(name, cfg, dtype, n_blocks, hidden, n_heads, n_kv_heads, head_
     K = int(cand_dir.max()) + 1
     X = _replicated_rows(cfg, _TAG_X, seq_ex, seq_len_a, hidden, 1.0, dtype)
     tgt = _replicated_rows(cfg, _TAG_TGT, seq_ex, seq_len_a, 1, 0, "f32", integer_high=vocab)
-    blocks = [_block_params(cfg, dtype, b, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R)
+    blocks = [_block_params(cfg, dtype, b, hidden, n_heads, n_kv_heads, head_dim, ffn, norm_kind, with_bias, R, qwen)
               for b in range(n_blocks)]
     layers = [l for blk in blocks for l in (blk.qkv, blk.o, blk.fc1, blk.fc2)]
     gf = np.float32(1) + _normal(cfg, _TAG_NORM, 4 * n_blocks, (hidden,), 0.1, "f32")
@@ -343,13 +355,13 @@ def opt_block(hidden=5120, n_heads=40, head_dim=128, ffn=20480, n_ex=64, seq_len
 
 def qwen_block(hidden=4096, n_heads=32, n_kv_heads=8, head_dim=128, ffn=12288, n_ex=32, n_dirs=16, len_lo=16,
                len_hi=512, r=16, eps=1e-3, R=128, cfg=6, dtype="bf16"):
-    """One Qwen3-8B-shaped decoder block (RMS norm, no biases, 32 query heads over 8 key/value heads)
-    on the ragged batch of config 4.  The MLP is the two-matrix fc1 -> ReLU -> fc2 of the chain
-    workloads, at the same shapes."""
+    """One Qwen3-8B-shaped decoder block (RMS norm, no biases, 32 query heads over 8 key/value heads,
+    per-head q/k norms, rotary embedding, gated MLP with a fused 2 x 12288 gate/up projection) on the
+    ragged batch of config 4."""
     lengths = _rng(cfg, _TAG_LEN).integers(len_lo, len_hi + 1, size=n_ex)
     batch = _pair_batch(lengths, np.arange(n_ex) % n_dirs)
     return decoder_block("b4-qwen3-block-ragged", cfg, dtype, hidden, n_heads, n_kv_heads, head_dim, ffn, 1, False,
-                         r, eps, R, batch)
+                         r, eps, R, batch, qwen=True)
 
 
 BUILDERS = {"c1": tiny_fp32, "c2": opt_layer_set, "c3": opt_scoring, "c4": ragged_packed,

@@ -83,7 +83,9 @@ def test_probe_linear_validation():
     assert _status(_probe, b, X=FAKE + 2) == zb.ZO_ERR_SHAPE
     assert _status(_probe, b, dt=zb.ZO_F32, odt=zb.ZO_BF16) == zb.ZO_ERR_UNSUPPORTED
     assert _status(_probe, b, dt=5) == zb.ZO_ERR_UNSUPPORTED
-    assert _status(_probe, b, act=2) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(_probe, b, act=3) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(_probe, b, act=2, m=63, dt=zb.ZO_F32) == zb.ZO_ERR_SHAPE            # (gate, up) pairs need an even m
+    assert _status(_probe, b, act=2, m=24) == zb.ZO_ERR_UNSUPPORTED                    # 12 bf16 output columns
     assert _status(_probe, b, ws=None) == zb.ZO_ERR_WORKSPACE
     assert _status(_probe, b, ws=FAKE + 16) == zb.ZO_ERR_WORKSPACE
     assert _status(_probe, b, ws_bytes=16) == zb.ZO_ERR_WORKSPACE
@@ -214,3 +216,19 @@ def test_attention_validation():
     assert _status(att, dt=7) == zb.ZO_ERR_UNSUPPORTED
     assert _status(att, _host_batch(lens=(3, 2), T=6)) == zb.ZO_ERR_INDEX
     att(_host_batch(lens=(0, 0)), Q=None, O=None)                   # an empty batch needs no buffers
+
+
+def test_qk_norm_rope_validation():
+    def rope(batch=None, **k):
+        zb.zo_qk_norm_rope(batch or _host_batch(), k.get("Q", FAKE), k.get("ldq", 512), k.get("K", FAKE),
+                           k.get("ldk", 512), k.get("H", 4), k.get("Hkv", 2), k.get("dh", 128), k.get("gq", FAKE),
+                           k.get("gk", FAKE), k.get("eps", 1e-6), 1e6, k.get("dt", zb.ZO_BF16))
+    assert _status(rope, Q=None) == zb.ZO_ERR_NULL
+    assert _status(rope, gk=None) == zb.ZO_ERR_NULL                 # the two gains go together
+    assert _status(rope, dh=127) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(rope, dh=512, ldq=4096, ldk=4096) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(rope, H=0) == zb.ZO_ERR_SHAPE
+    assert _status(rope, ldk=128) == zb.ZO_ERR_SHAPE
+    assert _status(rope, eps=-1.0) == zb.ZO_ERR_SHAPE
+    assert _status(rope, dt=9) == zb.ZO_ERR_UNSUPPORTED
+    rope(_host_batch(lens=(0, 0)), Q=None, K=None)

@@ -235,7 +235,12 @@ def _stagewise_block_parity(w, rtol):
     x = np.asarray(w.X, np.float64)
     _, a1 = ob.add_norm(x, None, b.g1, b.b1, b.norm_kind, b.norm_eps, w.dtype)
     assert_close(got["a1"], a1, rtol, "a1")
-    assert_close(got["qkv"], lin(b.qkv, got["a1"]), rtol, "qkv")
+    qkv_want = lin(b.qkv, got["a1"])
+    if b.gq is not None or b.rope_theta:     # the device applies both in place on the projection output
+        q_, k_ = ob.qk_norm_rope(qkv_want[:, :nq], qkv_want[:, nq:nq + nkv], w.cu_seqlens, b.n_heads, b.n_kv_heads,
+                                 b.head_dim, b.gq, b.gk, b.norm_eps, b.rope_theta, w.dtype)
+        qkv_want = np.concatenate([q_, k_, qkv_want[:, nq + nkv:]], axis=1)
+    assert_close(got["qkv"], qkv_want, 2 * rtol if b.gq is not None else rtol, "qkv")
     qkv = got["qkv"]
     att = ob.attention(qkv[:, :nq], qkv[:, nq:nq + nkv], qkv[:, nq + nkv:], w.cu_seqlens, b.n_heads, b.n_kv_heads,
                        b.head_dim, b.scale, w.dtype)
@@ -350,3 +355,54 @@ def test_model_bf16_scoring_pass_updates_and_foreground_rows():
                              np.arange(len(w.dir_seed)) * w.r, None, False, "bf16")
         assert_close(to_np(d.layers[i].P), new.P, 1e-5, "P of %s" % l.name, atol=1e-7)
         assert not torch.equal(before[i], d.layers[i].P)
+
+
+# ------------------------------------------------------------------ Qwen3-family pieces
+
+def _run_qk_norm_rope(q, k, lens, H, Hkv, dh, gq, gk, eps, theta, dtype):
+    batch, cu = _plain_batch(lens)
+    nq, nkv = H * dh, Hkv * dh
+    qkv = torch.cat([_dev(q, dtype), _dev(k, dtype), torch.full((q.shape[0], 16), 5.0, device=DEV, dtype=_dev(q, dtype).dtype)],
+                    dim=1).contiguous()
+    up = lambda a: None if a is None else torch.from_numpy(np.asarray(a, np.float32)).to(DEV)
+    zb.zo_qk_norm_rope(batch.struct, qkv[:, :nq], qkv.stride(0), qkv[:, nq:nq + nkv], qkv.stride(0), H, Hkv, dh,
+                       up(gq), up(gk), eps, theta or 0.0, zb.ZO_BF16 if dtype == "bf16" else zb.ZO_F32)
+    torch.cuda.synchronize()
+    assert (to_np(qkv[:, nq + nkv:]) == 5.0).all()
+    return to_np(qkv[:, :nq]), to_np(qkv[:, nq:nq + nkv]), cu
+
+
+@pytest.mark.parametrize("dtype,H,Hkv,dh", [("bf16", 8, 2, 128), ("bf16", 5, 1, 128), ("bf16", 2, 2, 64), ("f32", 3, 1, 32),
+                                            ("f32", 2, 2, 256), ("f32", 1, 1, 6)])
+@pytest.mark.parametrize("norm,theta", [(True, 1e6), (False, 1e4), (True, None)])
+def test_qk_norm_rope_matches_oracle(dtype, H, Hkv, dh, norm, theta):
+    lens = [1, 0, 130, 7, 300]
+    T = sum(lens)
+    g = _rng(H * 100 + dh)
+    q, k = g.normal(size=(T, H * dh)) * 2, g.normal(size=(T, Hkv * dh)) * 0.5
+    gq = 1 + 0.2 * g.normal(size=dh) if norm else None
+    gk = 1 + 0.2 * g.normal(size=dh) if norm else None
+    got_q, got_k, cu = _run_qk_norm_rope(q, k, lens, H, Hkv, dh, gq, gk, 1e-6, theta, dtype)
+    f32 = lambda a: None if a is None else np.asarray(a, np.float32).astype(np.float64)
+    want_q, want_k = ob.qk_norm_rope(_vals(q, dtype), _vals(k, dtype), cu, H, Hkv, dh, f32(gq), f32(gk), 1e-6, theta, dtype)
+    rtol = 1e-5 if dtype == "f32" else 2e-2
+    assert_close(got_q, want_q, rtol, "q")
+    assert_close(got_k, want_k, rtol, "k")
+    if theta and not norm:      # first row of every sequence sits at position 0: untouched, bit for bit
+        for a in (0, 1, 131, 138):
+            np.testing.assert_array_equal(got_q[a], _vals(q, dtype)[a])
+
+
+def test_qwen_form_block_bf16_and_fp32():
+    """RMS norms, per-head q/k norms, rotary embedding, grouped heads, gated MLP: stage by stage and
+    end to end, with candidates and a foreground sequence in the batch."""
+    batch = _small_batch([70, 131, 9, 200, 40], 2, 1)
+    w = wl.decoder_block("blk-qwen", 80, "bf16", 256, 4, 2, 128, 384, 1, False, 8, 1e-3, 32, batch, qwen=True)
+    got = _stagewise_block_parity(w, 2e-2)
+    want = ob.block_forward(oracle_batch(w), w.X, w.meta["block"], w.r, w.eps, "bf16")
+    assert_close(got["h2"], want["h2"], 4e-2, "h2 end to end")
+    batch = _small_batch([33, 64, 5, 90], 1, 1)
+    w = wl.decoder_block("blk-qwen-f32", 81, "f32", 96, 3, 1, 32, 160, 1, False, 4, 1e-3, 8, batch, qwen=True)
+    got = _stagewise_block_parity(w, 1e-5)
+    want = ob.block_forward(oracle_batch(w), w.X, w.meta["block"], w.r, w.eps, "f32")
+    assert_close(got["h2"], want["h2"], 5e-5, "h2 end to end (fp32)")

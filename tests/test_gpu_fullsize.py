@@ -169,15 +169,24 @@ def _check_block_full_size(w, seqs):
     x = np.asarray(w.X[rows], np.float64)
     _, a1 = ob.add_norm(x, None, b.g1, b.b1, b.norm_kind, b.norm_eps, w.dtype)
     assert_close(at(blk.a1), a1, 2e-2, "a1 sampled rows")
+    nq, nkv = b.n_heads * b.head_dim, b.n_kv_heads * b.head_dim
     for i, inp in enumerate([blk.a1, blk.att, blk.a2, d.Y[2]]):
         x_in = np.zeros((w.T, w.layers[i].n), dtype=np.float32)
         x_in[rows] = at(inp)
-        assert_close(at(d.Y[i]), oracle_layer(w, i, x_in, rows=rows), 2e-2, "Y[%s] sampled rows" % w.layers[i].name)
+        want = oracle_layer(w, i, x_in, rows=rows)
+        if i == 0 and (b.gq is not None or b.rope_theta):
+            # the device normalises and rotates queries and keys in place; a row's angle needs its position
+            qf, kf = np.zeros((w.T, nq)), np.zeros((w.T, nkv))
+            qf[rows], kf[rows] = want[:, :nq], want[:, nq:nq + nkv]
+            qf, kf = ob.qk_norm_rope(qf, kf, w.cu_seqlens, b.n_heads, b.n_kv_heads, b.head_dim, b.gq, b.gk,
+                                     b.norm_eps, b.rope_theta, w.dtype)
+            want = np.concatenate([qf[rows], kf[rows], want[:, nq + nkv:]], axis=1)
+        assert_close(at(d.Y[i]), want, 4e-2 if (i == 0 and b.gq is not None) else 2e-2,
+                     "Y[%s] sampled rows" % w.layers[i].name)
     h1, a2 = ob.add_norm(x, at(d.Y[1]), b.g2, b.b2, b.norm_kind, b.norm_eps, w.dtype)
     np.testing.assert_array_equal(at(blk.h1), h1)
     assert_close(at(blk.a2), a2, 2e-2, "a2 sampled rows")
     np.testing.assert_array_equal(at(h2), zo._round_out(at(blk.h1).astype(np.float64) + at(d.Y[3]), w.dtype))
-    nq, nkv = b.n_heads * b.head_dim, b.n_kv_heads * b.head_dim
     cu = w.cu_seqlens
     for s_ in seqs:
         lo, hi = int(cu[s_]), int(cu[s_ + 1])

@@ -393,7 +393,7 @@ def test_es_style_one_sided_candidates():
     assert_close(to_np(d.cand_loss), out["cand_loss"], 1e-5, "cand_loss vs oracle chain", atol=1e-3)
 
 
-def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0):
+def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0, bias=False):
     """One bf16 probe linear with its own input on an arbitrary candidate table."""
     rng = np.random.default_rng(seed)
     cu = np.zeros(len(lens) + 1, np.int32); cu[1:] = np.cumsum(lens)
@@ -403,18 +403,20 @@ def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0):
     W = wl.as_bf16_values((rng.standard_normal((m, n)) / np.sqrt(n)).astype(np.float32))
     P = (rng.standard_normal((m, R)) * 1e-2).astype(np.float32) if R else None
     Vb = (rng.standard_normal((n, R)) * 1e-2).astype(np.float32) if R else None
-    layer = wl.Layer("odd", m, n, 6, W, act, P, Vb, R, X)
+    layer = wl.Layer("odd", m, n, 6, W, act, P, Vb, R, X, (rng.standard_normal(m) * 0.3).astype(np.float32) if bias else None)
     return wl.Workload("odd-shapes", 9, "bf16", r, 1e-3, cu, np.array(seq_cand, np.int32),
                        np.array(cand_dir, np.int32), np.array(cand_sign, np.float32),
                        (np.arange(K, dtype=np.uint64) + np.uint64(991 + seed)), [layer], False)
 
 
-@pytest.mark.parametrize("case", range(10))
+@pytest.mark.parametrize("case", range(13))
 def test_bf16_probe_linear_odd_shapes(case):
     """Shapes that leave ragged tails in every tile dimension of the matrix-core kernel (out features
     not a multiple of 16, 128 or 256; one token; token counts just past a tile; many short sequences of
     different directions inside one token tile; ranks 1 and 64; a bank wider than one side-down pass;
-    input widths whose 64-column steps do not divide evenly among the side-down pass's k ranges)."""
+    input widths whose 64-column steps do not divide evenly among the side-down pass's k ranges; bias with
+    ReLU; the gated activation with and without bias, with out-feature counts that end inside a wave's
+    128-feature strip and inside a 16-feature block)."""
     cases = [
         dict(lens=[1], seq_cand=[0], cand_dir=[0], cand_sign=[1], m=8, n=64, r=1, R=0),
         dict(lens=[257, 3], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=200, n=128, r=5, R=16),
@@ -428,6 +430,9 @@ def test_bf16_probe_linear_odd_shapes(case):
         dict(lens=[2, 254, 2], seq_cand=[0, -1, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=1032, n=64, r=2, R=8),
         dict(lens=[70, 9], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=64, n=1344, r=33, R=136),
         dict(lens=[40, 0, 100, 65], seq_cand=[1, 0, -1, 2], cand_dir=[0, 1, -1], cand_sign=[1, -1, 0], m=48, n=1600, r=8, R=16),
+        dict(lens=[200, 70], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=264, n=128, r=8, R=16, act=1, bias=True),
+        dict(lens=[257, 3, 60], seq_cand=[0, 1, -1], cand_dir=[0, 0], cand_sign=[1, -1], m=528, n=128, r=8, R=16, act=2, bias=True),
+        dict(lens=[130, 5], seq_cand=[1, 0], cand_dir=[0, 0], cand_sign=[1, -1], m=1072, n=64, r=4, R=0, act=2),
     ]
     w = _single_layer(case, **cases[case])
     d = DeviceWorkload(w, DEV)

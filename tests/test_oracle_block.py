@@ -385,11 +385,18 @@ def test_qk_norm_matches_library_rms_norm_per_head():
     np.testing.assert_allclose(both_k, rk, rtol=1e-13)
 
 
-def test_swiglu_matches_library_silu():
+def test_gated_activation_of_the_probe_linear_matches_library_silu():
+    """act = 2: adjacent output features are (gate, up) pairs; the layer returns silu(gate) * up."""
     g = _rng(63)
-    gu = g.normal(size=(7, 24)) * 3
-    want = torch.nn.functional.silu(torch.tensor(gu[:, :12])) * torch.tensor(gu[:, 12:])
-    np.testing.assert_allclose(zb.swiglu(gu), want.numpy(), rtol=1e-12, atol=1e-14)
+    m, n, T = 24, 10, 7
+    W = g.normal(size=(m, n)); bias = g.normal(size=m)
+    batch = _batch([T], [-1], [0], [1], [5])
+    X = g.normal(size=(T, n))
+    pre = zo.probe_linear(batch, X, W, 2, 1e-3, 0, None, bias=bias, act=0)
+    got = zo.probe_linear(batch, X, W, 2, 1e-3, 0, None, bias=bias, act=2)
+    want = torch.nn.functional.silu(torch.tensor(pre[:, 0::2])) * torch.tensor(pre[:, 1::2])
+    assert got.shape == (T, m // 2)
+    np.testing.assert_allclose(got, want.numpy(), rtol=1e-12, atol=1e-14)
 
 
 def test_gated_rotary_block_foreground_equals_a_plain_torch_block():
@@ -398,10 +405,10 @@ def test_gated_rotary_block_foreground_equals_a_plain_torch_block():
     d, H, Hkv, dh, F_, theta = 32, 4, 2, 8, 40, 1e4
     blk = _block(64, d, H, Hkv, dh, F_, zb.RMS_NORM)
     g = _rng(65)
-    blk.fc1 = _layer(g, 2 * F_, d, 14, act=0, bias=False)
+    blk.fc1 = _layer(g, 2 * F_, d, 14, act=2, bias=False)     # rows 2j, 2j+1 = gate_j, up_j
     blk.fc2 = _layer(g, d, F_, 16, bias=False)
     blk.qkv.bias = blk.o.bias = None
-    blk.gq, blk.gk, blk.rope_theta, blk.gated = 1 + 0.1 * g.normal(size=dh), 1 + 0.1 * g.normal(size=dh), theta, True
+    blk.gq, blk.gk, blk.rope_theta = 1 + 0.1 * g.normal(size=dh), 1 + 0.1 * g.normal(size=dh), theta
     lens = [6, 9]
     batch = _batch(lens, [-1, -1], [0, 0], [1, -1], [7])
     x = g.normal(size=(sum(lens), d))
@@ -427,5 +434,5 @@ def test_gated_rotary_block_foreground_equals_a_plain_torch_block():
                                              is_causal=True, enable_gqa=True)[0].permute(1, 0, 2).reshape(L, H * dh)
         h1 = h0 + F.linear(att, t(blk.o.W))
         gu = F.linear(F.rms_norm(h1, (d,), t(blk.g2), blk.norm_eps), t(blk.fc1.W))
-        want.append((h1 + F.linear(F.silu(gu[:, :F_]) * gu[:, F_:], t(blk.fc2.W))).numpy())
+        want.append((h1 + F.linear(F.silu(gu[:, 0::2]) * gu[:, 1::2], t(blk.fc2.W))).numpy())
     np.testing.assert_allclose(got, np.concatenate(want), rtol=1e-9, atol=1e-11)
