@@ -36,15 +36,17 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   // Vb stage: [half h of the K step][16-col block][col][4 chunks of 16 B], chunk index XOR (col>>2)&3
   __shared__ __attribute__((aligned(1024))) char s_vb[2][NBB > 0 ? NBB * 2048 : 16];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int n_items = *a.n_items;
-  if ((int)blockIdx.y * 4 >= n_items) return;   // the grid is sized for the worst case; whole workgroups without items leave
-  const int item_raw = blockIdx.y * 4 + wave;
+  // The grid is sized for the worst case (most items, largest k-split); the k-split and the number
+  // of items are known on the device.  Block b is (group b / ksplit, split b % ksplit), so the blocks
+  // without work are the last ones of the grid and are dispatched after every block that has some.
+  const int n_items = a.n_items[0];
+  const int ksplit = a.n_items[1];
+  const int group = blockIdx.x / ksplit, split = blockIdx.x - group * ksplit;
+  if (group * 4 >= n_items) return;
+  const int item_raw = group * 4 + wave;
   const bool live = item_raw < n_items;
   // waves without an item still take part in the workgroup's Vb loads and barriers
-  const SideItem it = a.items[live ? item_raw : (n_items > 0 ? n_items - 1 : 0)];
-  const int split = blockIdx.x;
-  const int ksplit = a.n_items[1];   // chosen on the device for the number of items; the grid covers the cap
-  if (split >= ksplit) return;
+  const SideItem it = a.items[live ? item_raw : n_items - 1];
   const int NC = a.RP + a.Rp;
   const int lr = lane & 15, lg = lane >> 4;
   // each split walks its own contiguous K range in steps of 64; the first (steps mod k-split) splits
@@ -167,12 +169,11 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
 // cbd = index of the 16-column direction block.
 __global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int cbd) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int item = blockIdx.x * 4 + wave;
-  if (item >= *a.n_items) return;
-  const SideItem it = a.items[item];
-  const int split = blockIdx.y;
   const int ksplit = a.n_items[1];
-  if (split >= ksplit) return;
+  const int group = blockIdx.x / ksplit, split = blockIdx.x - group * ksplit;
+  const int item = group * 4 + wave;
+  if (item >= a.n_items[0]) return;
+  const SideItem it = a.items[item];
   const int NC = a.RP + a.Rp;
   const int lr = lane & 15, lg = lane >> 4;
   const int steps_total = a.n / 64;
@@ -230,7 +231,7 @@ __global__ void k_side_reduce(SideDownArgs a) {
 
 template <int NBB, bool kDir>
 static void launch_pass(const SideDownArgs& a, int cb0, hipStream_t st) {
-  dim3 grid(a.ks_cap, (a.max_items + 3) / 4);
+  dim3 grid(a.ks_cap * ((a.max_items + 3) / 4));
   hipLaunchKernelGGL((k_side_down<NBB, kDir>), grid, dim3(256), 0, st, a, cb0);
 }
 
@@ -261,7 +262,7 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
     done += nb;
   }
   for (int cbd = 1; cbd < a.RP / 16; ++cbd) {   // ranks above 16
-    dim3 grid((a.max_items + 3) / 4, a.ks_cap);
+    dim3 grid(a.ks_cap * ((a.max_items + 3) / 4));
     hipLaunchKernelGGL(k_side_down_dirblock, grid, dim3(256), 0, st, a, cbd);
   }
   hipError_t e = hipGetLastError();
