@@ -259,6 +259,40 @@ def main():
         loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
                      "fold_all_layers_ms": e0.elapsed_time(e1)}
 
+    # Secondary: the lazy update of 40 layers (20 copies of this workload's two layer shapes, one rank-r
+    # block per direction, accumulate mode) as one multi-layer call against 40 single-layer calls.
+    def bank_update_40():
+        shapes = [(l.m, l.n) for l in w.layers] * 20
+        R_cap = int(w.layers[0].R_used)
+        Ps = [torch.zeros((m, R_cap), device="cuda:0") for m, _ in shapes]
+        Vs = [torch.zeros((n, R_cap), device="cuda:0") for _, n in shapes]
+        banks = [zb.make_bank(R_cap, R_cap, Ps[i], Vs[i]) for i in range(len(shapes))]
+        arr = zb.make_layer_banks([(banks[i], m, n, 2 * i) for i, (m, n) in enumerate(shapes)])
+        dt = zb.ZO_BF16
+
+        def multi():
+            zb.zo_bank_update_multi(arr, w.r, n_upd, d.batch.dir_seed, None, d.proj_grad, 1e-7, None, col0, 0, dt, stream)
+
+        def single():
+            for i, (m, n) in enumerate(shapes):
+                zb.zo_bank_update(banks[i], m, n, w.r, n_upd, d.batch.dir_seed, 2 * i, d.proj_grad, 1e-7, None, col0, 0,
+                                  dt, stream)
+
+        def timed(fn):
+            fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(n_sec):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / n_sec
+        nbytes = sum(2 * m * w.r * 4 * n_upd for m, _ in shapes)
+        t_multi, t_single = timed(multi), timed(single)
+        return {"layers": len(shapes), "bytes": int(nbytes), "multi_ms": t_multi, "per_layer_calls_ms": t_single,
+                "multi_gbs": nbytes / (t_multi * 1e-3) / 1e9}
+    bank40 = bank_update_40() if n_upd > 0 else None
+
     block_info = None
     if not args.no_block:
         block_info = _block_section({"c3": "b3"}.get(args.workload, "b4"), n_sec)
@@ -268,6 +302,7 @@ def main():
     breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
     ms_per_step = elapsed / args.steps * 1e3
     value = T * args.steps / elapsed
+    cand_rows = int(sum(int(w.cu_seqlens[s_ + 1] - w.cu_seqlens[s_]) for s_ in range(len(w.seq_cand)) if w.seq_cand[s_] >= 0))
 
     # dominant kernel: the fused head GEMM + log-sum-exp (zo_score; its three merge kernels are < 1 % of it)
     head_flops = 2.0 * T * hid * vocab
@@ -292,6 +327,8 @@ def main():
                    "layers": [[l.name, l.m, l.n] for l in w.layers], "bank_rank": int(w.layers[0].R_used),
                    "vocab": int(vocab), "hidden": int(hid)},
         "roofline": roofline,
+        # rows of sequences that carry a candidate (all rows unless the batch mixes in foreground sequences)
+        "candidate_rows": cand_rows, "candidate_rows_per_s": cand_rows * args.steps / elapsed,
         "chain_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
         "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "breakdown_ms": breakdown, "probe_linear_calls": calls, "input_setup_s": gen_s,
@@ -301,6 +338,7 @@ def main():
         "native_over_matched": ms_per_step / plain_ms,
         "loop": loop_info,
         "block": block_info,
+        "bank_update_40_layers": bank40,
         "active_token_scoring": {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms},
         "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},
         # bytes the update step moves (P read + write per layer) against rewriting the dense weights

@@ -253,6 +253,28 @@ int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n
                        void* stream);
 
 /*
+ * The same lazy update for many layers in one call (Sec. 4 counts the update of the
+ * whole model as one state transition of 26 MB): every layer gets beta_k U_k of its
+ * own tensor id in the same column blocks host_col0[k] (and, with append, V_k).  One
+ * layer's update moves 2 * m * r * 4 bytes, a few hundred KB at the paper's sizes, so
+ * per-layer launches cost more than the traffic; here up to 48 layers and 32
+ * directions share a launch.  Other arguments and errors as zo_bank_update; nothing
+ * is launched unless every layer passes validation.
+ */
+typedef struct zo_layer_bank {
+  zo_bank bank;
+  int32_t m, n;          /* shape of the layer's weight */
+  uint32_t tensor_id;
+  int32_t reserved;
+} zo_layer_bank;
+
+int32_t zo_bank_update_multi(zo_layer_bank* layers, int32_t n_layers, int32_t r, int32_t n_dirs,
+                             const uint64_t* dir_seed, const uint64_t* dir_seed_v,
+                             const float* proj_grad, float lr, const float* dir_weight,
+                             const int32_t* host_col0, int32_t append, zo_dtype factor_dtype,
+                             void* stream);
+
+/*
  * Device-resident schedule of the multi-step loop (Sec. 3.2: V_k reused over an
  * interval of nu steps, U_t fresh every step, one bank block per interval; with
  * B blocks the reuse covers nu * B steps before the bank must be folded or the

@@ -36,6 +36,11 @@ class zo_bank(C.Structure):
     _fields_ = [("R_cap", C.c_int32), ("R_used", C.c_int32), ("P", C.c_void_p), ("Vb", C.c_void_p)]
 
 
+class zo_layer_bank(C.Structure):
+    _fields_ = [("bank", zo_bank), ("m", C.c_int32), ("n", C.c_int32), ("tensor_id", C.c_uint32),
+                ("reserved", C.c_int32)]
+
+
 class zo_sched(C.Structure):
     """Layout of the device-resident schedule state (for host-side initialisation and read-back)."""
     _fields_ = [("next_step", C.c_int64), ("step", C.c_int64), ("interval", C.c_int32), ("block", C.c_int32),
@@ -87,6 +92,8 @@ _PROTOS = {
     "zo_qk_norm_rope": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
                                     C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_int,
                                     C.c_void_p]),
+    "zo_bank_update_multi": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_float, C.c_void_p, C.c_void_p, C.c_int32, C.c_int, C.c_void_p]),
 }
 EXPORTS = tuple(_PROTOS)
 
@@ -251,3 +258,20 @@ def zo_qk_norm_rope(batch, Q, ldq, K, ldk, n_heads, n_kv_heads, head_dim, gamma_
                     dtype, stream=None):
     _check(lib().zo_qk_norm_rope(C.byref(batch), _ptr(Q), ldq, _ptr(K), ldk, n_heads, n_kv_heads, head_dim,
                                  _ptr(gamma_q), _ptr(gamma_k), norm_eps, rope_theta, dtype, _stream(stream)))
+
+
+def make_layer_banks(entries):
+    """entries: sequence of (zo_bank, m, n, tensor_id).  Returns a ctypes array of zo_layer_bank that shares
+    nothing with the given structs: R_used changes made by an append are read back from the array."""
+    arr = (zo_layer_bank * len(entries))()
+    for i, (bank, m, n, tid) in enumerate(entries):
+        arr[i].bank.R_cap, arr[i].bank.R_used, arr[i].bank.P, arr[i].bank.Vb = bank.R_cap, bank.R_used, bank.P, bank.Vb
+        arr[i].m, arr[i].n, arr[i].tensor_id = m, n, tid
+    return arr
+
+
+def zo_bank_update_multi(layers, r, n_dirs, dir_seed, dir_seed_v, proj_grad, lr, dir_weight, host_col0, append,
+                         factor_dtype, stream=None):
+    _check(lib().zo_bank_update_multi(C.addressof(layers) if len(layers) else None, len(layers), r, n_dirs,
+                                      _ptr(dir_seed), _ptr(dir_seed_v), _ptr(proj_grad), lr, _ptr(dir_weight),
+                                      _ptr(host_col0), append, factor_dtype, _stream(stream)))

@@ -420,6 +420,25 @@ int32_t check_bank_update(const zo_bank* bank, int32_t m, int32_t n, int32_t r, 
   if (factor_dtype != ZO_F32 && factor_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "factor_dtype %d", (int)factor_dtype);
   return ZO_OK;
 }
+
+// The column blocks [col0[k], col0[k] + r) of the directions: inside the bank, pairwise disjoint, and
+// when accumulating, inside the columns in use.  *new_used = R_used after an append.
+int32_t check_col_blocks(const zo_bank* bank, int32_t r, int32_t n_dirs, const int32_t* host_col0, int32_t append,
+                         int* new_used) {
+  *new_used = bank->R_used;
+  for (int k = 0; k < n_dirs; ++k) {
+    const int c0 = host_col0[k];
+    if (c0 < 0) return fail(ZO_ERR_SHAPE, "col0[%d] = %d", k, c0);
+    if (c0 + r > bank->R_cap) return fail(ZO_ERR_BANK_FULL, "direction %d: columns [%d, %d) exceed R_cap = %d", k, c0, c0 + r, bank->R_cap);
+    if (!append && c0 + r > bank->R_used)
+      return fail(ZO_ERR_SHAPE, "direction %d accumulates into columns [%d, %d) beyond R_used = %d", k, c0, c0 + r, bank->R_used);
+    for (int j = 0; j < k; ++j)
+      if (c0 < host_col0[j] + r && host_col0[j] < c0 + r)
+        return fail(ZO_ERR_SHAPE, "column blocks of directions %d and %d overlap", j, k);
+    if (c0 + r > *new_used) *new_used = c0 + r;
+  }
+  return ZO_OK;
+}
 }  // namespace
 
 int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, const uint64_t* dir_seed,
@@ -431,18 +450,8 @@ int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n
   if (n_dirs == 0) return ZO_OK;
   if (!dir_seed || !proj_grad || !host_col0) return fail(ZO_ERR_NULL, "dir_seed, proj_grad or host_col0 is NULL");
   if (!bank->P || (append && !bank->Vb)) return fail(ZO_ERR_NULL, "bank.P / bank.Vb is NULL");
-  int new_used = bank->R_used;
-  for (int k = 0; k < n_dirs; ++k) {
-    const int c0 = host_col0[k];
-    if (c0 < 0) return fail(ZO_ERR_SHAPE, "col0[%d] = %d", k, c0);
-    if (c0 + r > bank->R_cap) return fail(ZO_ERR_BANK_FULL, "direction %d: columns [%d, %d) exceed R_cap = %d", k, c0, c0 + r, bank->R_cap);
-    if (!append && c0 + r > bank->R_used)
-      return fail(ZO_ERR_SHAPE, "direction %d accumulates into columns [%d, %d) beyond R_used = %d", k, c0, c0 + r, bank->R_used);
-    for (int j = 0; j < k; ++j)
-      if (c0 < host_col0[j] + r && host_col0[j] < c0 + r)
-        return fail(ZO_ERR_SHAPE, "column blocks of directions %d and %d overlap", j, k);
-    if (c0 + r > new_used) new_used = c0 + r;
-  }
+  int new_used = 0;
+  if (int32_t st = check_col_blocks(bank, r, n_dirs, host_col0, append, &new_used)) return st;
   zo::BankUpdateArgs a;
   a.P = bank->P; a.Vb = bank->Vb; a.R_cap = bank->R_cap; a.m = m; a.n = n; a.r = r;
   a.seed = dir_seed; a.seed_v = dir_seed_v; a.tensor_id = tensor_id; a.proj_grad = proj_grad; a.lr = lr;
@@ -450,6 +459,48 @@ int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n
   a.default_weight = 1.0f / (float)n_dirs; a.append = append; a.bf16 = factor_dtype == ZO_BF16;
   ZO_HIP(zo::launch_bank_update(a, n_dirs, host_col0, (hipStream_t)stream), "zo_bank_update");
   if (append) bank->R_used = new_used;
+  return ZO_OK;
+}
+
+int32_t zo_bank_update_multi(zo_layer_bank* layers, int32_t n_layers, int32_t r, int32_t n_dirs,
+                             const uint64_t* dir_seed, const uint64_t* dir_seed_v, const float* proj_grad, float lr,
+                             const float* dir_weight, const int32_t* host_col0, int32_t append,
+                             zo_dtype factor_dtype, void* stream) {
+  if (n_layers < 0) return fail(ZO_ERR_SHAPE, "n_layers = %d", n_layers);
+  if (n_layers > 0 && !layers) return fail(ZO_ERR_NULL, "layers is NULL");
+  if (append != 0 && append != 1) return fail(ZO_ERR_UNSUPPORTED, "append = %d", append);
+  // everything is validated before the first launch
+  for (int i = 0; i < n_layers; ++i)
+    if (int32_t st = check_bank_update(&layers[i].bank, layers[i].m, layers[i].n, r, n_dirs, factor_dtype)) return st;
+  if (n_layers == 0 || n_dirs == 0) return ZO_OK;
+  if (!dir_seed || !proj_grad || !host_col0) return fail(ZO_ERR_NULL, "dir_seed, proj_grad or host_col0 is NULL");
+  for (int i = 0; i < n_layers; ++i) {
+    const zo_bank* b = &layers[i].bank;
+    int new_used = 0;
+    if (!b->P || (append && !b->Vb)) return fail(ZO_ERR_NULL, "layer %d: bank.P / bank.Vb is NULL", i);
+    if (int32_t st = check_col_blocks(b, r, n_dirs, host_col0, append, &new_used)) return st;
+  }
+  zo::BankUpdateArgs a;   // what the layers share; the per-layer fields are filled in on the device
+  a.P = nullptr; a.Vb = nullptr; a.R_cap = 0; a.m = 0; a.n = 0; a.tensor_id = 0; a.r = r;
+  a.seed = dir_seed; a.seed_v = dir_seed_v; a.proj_grad = proj_grad; a.lr = lr;
+  a.dir_weight = dir_weight; a.sched = nullptr; a.n_dirs = n_dirs;
+  a.default_weight = 1.0f / (float)n_dirs; a.append = append; a.bf16 = factor_dtype == ZO_BF16;
+  constexpr int kChunk = 192;
+  zo::BankLayer chunk[kChunk];
+  for (int l0 = 0; l0 < n_layers; l0 += kChunk) {
+    const int nl = n_layers - l0 < kChunk ? n_layers - l0 : kChunk;
+    for (int i = 0; i < nl; ++i) {
+      const zo_layer_bank& l = layers[l0 + i];
+      chunk[i] = zo::BankLayer{l.bank.P, l.bank.Vb, l.bank.R_cap, l.m, l.n, l.tensor_id};
+    }
+    ZO_HIP(zo::launch_bank_update_multi(a, chunk, nl, n_dirs, host_col0, (hipStream_t)stream), "zo_bank_update_multi");
+  }
+  if (append)
+    for (int i = 0; i < n_layers; ++i) {
+      int new_used = 0;
+      check_col_blocks(&layers[i].bank, r, n_dirs, host_col0, append, &new_used);
+      layers[i].bank.R_used = new_used;
+    }
   return ZO_OK;
 }
 

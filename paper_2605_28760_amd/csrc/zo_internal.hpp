@@ -178,6 +178,12 @@ struct BankUpdateArgs {
 };
 // col0: host array of n_dirs block offsets (passed to the kernel by value in batches)
 hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st);
+// the same update (same seeds, coefficients and column blocks) for many layers in one launch per 48 layers
+struct BankLayer { float* P; float* Vb; int32_t R_cap, m, n; uint32_t tensor_id; };
+constexpr int kBankMaxLayers = 48;
+struct BankLayerSet { BankLayer l[kBankMaxLayers]; };
+hipError_t launch_bank_update_multi(const BankUpdateArgs& common, const BankLayer* layers, int n_layers, int n_dirs,
+                                    const int32_t* col0, hipStream_t st);
 
 // W (fp32 or bf16, in place) += P[:, :R] Vb[:, :R]^T, then the R columns of P and Vb are zeroed.
 struct FoldArgs {

@@ -242,15 +242,13 @@ hipError_t launch_estimate_es(const BatchDev& b, const float* cand_sum, const in
 constexpr int kBankBatch = 32;
 struct BankCols { int32_t first_dir; int32_t n; int32_t col0[kBankBatch]; };
 
-// grid.y = direction within the batch; grid.x covers max(m, n) * r entries.
-__global__ void k_bank_update(BankUpdateArgs a, BankCols cols) {
-  const int kb = blockIdx.y;
+// Entry idx of direction kb (within the batch `cols`) of one layer's update.
+__device__ __forceinline__ void bank_update_entry(const BankUpdateArgs& a, const BankCols& cols, int kb, int64_t idx) {
   const int k = cols.first_dir + kb;
   // block and mode: from the host (by value) or from the device-resident schedule
   const int col0 = a.sched ? (a.sched->block * a.n_dirs + k) * a.r : cols.col0[kb];
   const bool append = a.sched ? a.sched->append != 0 : a.append != 0;
   if (col0 < 0 || col0 + a.r > a.R_cap) return;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (idx < (int64_t)a.m * a.r) {
     const int i = (int)(idx / a.r), j = (int)(idx % a.r);
     const float w = a.dir_weight ? a.dir_weight[k] : a.default_weight;
@@ -268,6 +266,19 @@ __global__ void k_bank_update(BankUpdateArgs a, BankCols cols) {
   }
 }
 
+// grid.y = direction within the batch; grid.x covers max(m, n) * r entries.
+__global__ void k_bank_update(BankUpdateArgs a, BankCols cols) {
+  bank_update_entry(a, cols, blockIdx.y, (int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+}
+
+// The same update for many layers in one launch (grid.z = layer): at the paper's sizes one layer's
+// update is a few hundred KB and its launch costs more than its traffic.
+__global__ void k_bank_update_multi(BankUpdateArgs a, BankCols cols, BankLayerSet layers) {
+  const BankLayer& l = layers.l[blockIdx.z];
+  a.P = l.P; a.Vb = l.Vb; a.R_cap = l.R_cap; a.m = l.m; a.n = l.n; a.tensor_id = l.tensor_id;
+  bank_update_entry(a, cols, blockIdx.y, (int64_t)blockIdx.x * blockDim.x + threadIdx.x);
+}
+
 hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st) {
   const int rows = (a.append || a.sched) ? (a.m > a.n ? a.m : a.n) : a.m;
   const int64_t total = (int64_t)rows * a.r;
@@ -280,6 +291,33 @@ hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t
     hipLaunchKernelGGL(k_bank_update, dim3((unsigned)((total + 255) / 256), cols.n), dim3(256), 0, st, a, cols);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_bank_update_multi(const BankUpdateArgs& common, const BankLayer* layers, int n_layers, int n_dirs,
+                                    const int32_t* col0, hipStream_t st) {
+  for (int l0 = 0; l0 < n_layers; l0 += kBankMaxLayers) {
+    BankLayerSet set;
+    const int nl = n_layers - l0 < kBankMaxLayers ? n_layers - l0 : kBankMaxLayers;
+    int64_t total = 0;
+    for (int i = 0; i < kBankMaxLayers; ++i) {
+      set.l[i] = layers[l0 + (i < nl ? i : 0)];
+      const BankLayer& l = set.l[i];
+      const int rows = common.append ? (l.m > l.n ? l.m : l.n) : l.m;
+      if (i < nl && (int64_t)rows * common.r > total) total = (int64_t)rows * common.r;
+    }
+    if (total == 0) continue;
+    for (int first = 0; first < n_dirs; first += kBankBatch) {
+      BankCols cols;
+      cols.first_dir = first;
+      cols.n = n_dirs - first < kBankBatch ? n_dirs - first : kBankBatch;
+      for (int i = 0; i < kBankBatch; ++i) cols.col0[i] = i < cols.n ? col0[first + i] : 0;
+      hipLaunchKernelGGL(k_bank_update_multi, dim3((unsigned)((total + 255) / 256), cols.n, nl), dim3(256), 0, st, common,
+                         cols, set);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }

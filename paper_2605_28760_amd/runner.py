@@ -116,6 +116,16 @@ class DeviceWorkload:
         zb.zo_bank_update(l.bank, l.m, l.n, self.w.r, len(col0), self.batch.dir_seed, l.tensor_id,
                           self.proj_grad, float(lr), dir_weight, col0, append, _dt(self.dtype), stream)
 
+    def bank_update_all(self, lr, col0, append=0, dir_weight=None, stream=None):
+        """The same update for every layer that has a bank, in shared launches (zo_bank_update_multi)."""
+        col0 = np.ascontiguousarray(col0, np.int32)
+        banked = [l for l in self.layers if l.bank is not None]
+        arr = zb.make_layer_banks([(l.bank, l.m, l.n, l.tensor_id) for l in banked])
+        zb.zo_bank_update_multi(arr, self.w.r, len(col0), self.batch.dir_seed, None, self.proj_grad, float(lr),
+                                dir_weight, col0, append, _dt(self.dtype), stream)
+        for l, e in zip(banked, arr):
+            l.bank.R_used = e.bank.R_used
+
     # -- one pass of the whole path --------------------------------------------------------
     def step(self, lr=1e-7, update=True, stream=None):
         for i in range(len(self.layers)):
@@ -230,10 +240,7 @@ class DeviceModel:
         self.forward(stream)
         d.estimate(stream)
         if update:
-            col0 = np.arange(d.batch.K, dtype=np.int32) * d.w.r
-            for i, l in enumerate(d.layers):
-                if l.bank is not None and l.bank.R_used >= d.w.r * d.batch.K:
-                    d.bank_update(i, lr, col0, 0, stream=stream)
+            d.bank_update_all(lr, np.arange(d.batch.K, dtype=np.int32) * d.w.r, 0, stream=stream)
 
 
 class LoopDriver:

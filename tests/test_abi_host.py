@@ -232,3 +232,23 @@ def test_qk_norm_rope_validation():
     assert _status(rope, eps=-1.0) == zb.ZO_ERR_SHAPE
     assert _status(rope, dt=9) == zb.ZO_ERR_UNSUPPORTED
     rope(_host_batch(lens=(0, 0)), Q=None, K=None)
+
+
+def test_bank_update_multi_validation():
+    def upd(entries, **k):
+        arr = zb.make_layer_banks(entries)
+        zb.zo_bank_update_multi(arr, k.get("r", 4), k.get("K", 1), k.get("seed", FAKE), None, FAKE, 1e-3, None,
+                                np.array(k.get("col0", [0]), np.int32), k.get("append", 0), k.get("dt", zb.ZO_BF16))
+        return arr
+    good = (zb.make_bank(8, 8, FAKE, FAKE), 64, 64, 0)
+    assert _status(upd, [good, (zb.make_bank(8, 8, None, FAKE), 64, 64, 2)]) == zb.ZO_ERR_NULL
+    assert "layer 1" in zb.last_error()
+    assert _status(upd, [good, (zb.make_bank(8, 2, FAKE, FAKE), 64, 64, 2)]) == zb.ZO_ERR_SHAPE      # beyond R_used
+    assert _status(upd, [good], col0=[6]) == zb.ZO_ERR_BANK_FULL
+    assert _status(upd, [good], r=0) == zb.ZO_ERR_SHAPE
+    assert _status(upd, [good], seed=None) == zb.ZO_ERR_NULL
+    assert _status(upd, [good], append=2) == zb.ZO_ERR_UNSUPPORTED
+    assert _status(upd, [good, (zb.make_bank(8, 8, FAKE, FAKE), -1, 64, 2)]) == zb.ZO_ERR_SHAPE
+    upd([])                                             # no layers: nothing to do
+    upd([good], K=0, col0=[])                           # no directions either
+    assert C.sizeof(zb.zo_layer_bank) == 40

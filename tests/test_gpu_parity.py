@@ -266,6 +266,36 @@ def test_bank_update_parity(dtype):
     assert e.value.status == zb.ZO_ERR_BANK_FULL
 
 
+def test_bank_update_of_many_layers_in_one_call_equals_the_per_layer_updates():
+    """zo_bank_update_multi over 50 layers of mixed shapes (more than one launch holds), accumulate and
+    append, against zo_bank_update layer by layer: bit for bit, including the columns left alone."""
+    rng = np.random.default_rng(77)
+    r, K, R_cap = 4, 3, 24
+    shapes = [(int(rng.integers(1, 300)), int(rng.integers(1, 300))) for _ in range(50)]
+    seeds = torch.from_numpy((np.arange(K, dtype=np.uint64) + np.uint64(4242)).view(np.int64)).to(DEV)
+    seeds_v = torch.from_numpy((np.arange(K, dtype=np.uint64) + np.uint64(777)).view(np.int64)).to(DEV)
+    pg = torch.from_numpy(rng.standard_normal(K).astype(np.float32)).to(DEV)
+    wts = torch.from_numpy(rng.random(K).astype(np.float32)).to(DEV)
+    for append, col0 in ((1, [8, 0, 16]), (0, [16, 8, 0])):
+        col0 = np.array(col0, np.int32)
+        P0 = [torch.from_numpy(rng.standard_normal((m, R_cap)).astype(np.float32)).to(DEV) for m, n in shapes]
+        V0 = [torch.from_numpy(rng.standard_normal((n, R_cap)).astype(np.float32)).to(DEV) for m, n in shapes]
+        Pa, Va = [p.clone() for p in P0], [v.clone() for v in V0]
+        Pb, Vb = [p.clone() for p in P0], [v.clone() for v in V0]
+        used = 0 if append else R_cap
+        singles = [zb.make_bank(R_cap, used, Pa[i], Va[i]) for i in range(len(shapes))]
+        for i, (m, n) in enumerate(shapes):
+            zb.zo_bank_update(singles[i], m, n, r, K, seeds, 2 * i, pg, 0.5, wts, col0, append, zb.ZO_BF16, dir_seed_v=seeds_v)
+        arr = zb.make_layer_banks([(zb.make_bank(R_cap, used, Pb[i], Vb[i]), m, n, 2 * i) for i, (m, n) in enumerate(shapes)])
+        zb.zo_bank_update_multi(arr, r, K, seeds, seeds_v, pg, 0.5, wts, col0, append, zb.ZO_BF16)
+        _sync()
+        for i in range(len(shapes)):
+            assert torch.equal(Pa[i], Pb[i]) and torch.equal(Va[i], Vb[i]), i
+            assert arr[i].bank.R_used == singles[i].R_used == (20 if append else R_cap)
+            assert not torch.equal(Pa[i], P0[i])
+            assert torch.equal(Pa[i][:, 20:], P0[i][:, 20:])
+
+
 def test_lazy_update_then_probe_matches_oracle():
     """One full step with update, then a second forward: the bank the GPU wrote
     must act in the next probe exactly as the oracle's updated bank does."""
