@@ -439,14 +439,15 @@ def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0, 
                        (np.arange(K, dtype=np.uint64) + np.uint64(991 + seed)), [layer], False)
 
 
-@pytest.mark.parametrize("case", range(13))
+@pytest.mark.parametrize("case", range(14))
 def test_bf16_probe_linear_odd_shapes(case):
     """Shapes that leave ragged tails in every tile dimension of the matrix-core kernel (out features
     not a multiple of 16, 128 or 256; one token; token counts just past a tile; many short sequences of
     different directions inside one token tile; ranks 1 and 64; a bank wider than one side-down pass;
     input widths whose 64-column steps do not divide evenly among the side-down pass's k ranges; bias with
     ReLU; the gated activation with and without bias, with out-feature counts that end inside a wave's
-    128-feature strip and inside a 16-feature block)."""
+    128-feature strip and inside a 16-feature block; the largest rank with a bank of 528 columns, which
+    takes five side-down passes over the input)."""
     cases = [
         dict(lens=[1], seq_cand=[0], cand_dir=[0], cand_sign=[1], m=8, n=64, r=1, R=0),
         dict(lens=[257, 3], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=200, n=128, r=5, R=16),
@@ -463,6 +464,7 @@ def test_bf16_probe_linear_odd_shapes(case):
         dict(lens=[200, 70], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=264, n=128, r=8, R=16, act=1, bias=True),
         dict(lens=[257, 3, 60], seq_cand=[0, 1, -1], cand_dir=[0, 0], cand_sign=[1, -1], m=528, n=128, r=8, R=16, act=2, bias=True),
         dict(lens=[130, 5], seq_cand=[1, 0], cand_dir=[0, 0], cand_sign=[1, -1], m=1072, n=64, r=4, R=0, act=2),
+        dict(lens=[90, 40, 7], seq_cand=[0, -1, 1], cand_dir=[0, -1], cand_sign=[1, 0], m=40, n=576, r=64, R=528),
     ]
     w = _single_layer(case, **cases[case])
     d = DeviceWorkload(w, DEV)
