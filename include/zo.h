@@ -159,8 +159,9 @@ int32_t zo_batch_index(const zo_batch* batch, int32_t* tok_seq, int32_t* tok_can
  *             Y[t, j] = silu(gate_j) * up_j, silu(x) = x / (1 + exp(-x)); Y then has m/2 columns
  *   r         rank of the probe, 1..64;  eps probe scale;  tensor_id even id of the layer
  *   bank      NULL or R_used = 0: no bank
- * ZO_BF16 requires n % 64 == 0 (and m % 8 == 0 for bf16 output), 16-byte aligned X, W, Y and leading dimensions
- * that keep rows 16-byte aligned.
+ * ZO_BF16 requires n % 64 == 0 (and, for bf16 output, a multiple of 8 output columns: m % 8 == 0, or
+ * m % 16 == 0 with act 2), 16-byte aligned X, W, Y and leading dimensions that keep rows 16-byte aligned.
+ * Y [T x m] above means [T x m/2] with act 2.
  */
 size_t zo_probe_linear_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t n_dirs,
                                        int32_t m, int32_t n, int32_t r, int32_t R_used,
