@@ -242,6 +242,24 @@ class DeviceModel:
         if update:
             d.bank_update_all(lr, np.arange(d.batch.K, dtype=np.int32) * d.w.r, 0, stream=stream)
 
+    def capture(self, lr=1e-7, update=True):
+        """Captures one step (scoring pass, estimate, updates) into a HIP graph after one eager warm-up
+        step on a side stream, which configures the kernels; nothing in a step depends on the host.
+        The warm-up step is a real step: with update it moves the banks."""
+        side = torch.cuda.Stream(device=self.d.device)
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            self.step(lr, update, stream=side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.step(lr, update, stream=torch.cuda.current_stream())
+        return self.graph
+
+    def replay(self):
+        self.graph.replay()
+
 
 class LoopDriver:
     """The multi-step loop of Sec. 3.2 on one DeviceWorkload: per step, the device-resident schedule

@@ -406,3 +406,34 @@ def test_qwen_form_block_bf16_and_fp32():
     got = _stagewise_block_parity(w, 1e-5)
     want = ob.block_forward(oracle_batch(w), w.X, w.meta["block"], w.r, w.eps, "f32")
     assert_close(got["h2"], want["h2"], 5e-5, "h2 end to end (fp32)")
+
+
+def test_model_step_replayed_from_a_graph_equals_eager_steps():
+    """The whole-model step (Qwen3 form: norms, q/k norm + rotary, attention, gated MLP, head scoring,
+    estimate, the update of all layers in one call) captured once and replayed, with unrelated eager
+    work between the replays, against the same number of eager steps: bit for bit, banks included."""
+    batch = wl._pair_batch([70, 131, 9, 200], [0, 1, 0, 1], 1, [40])
+    def build():
+        w = wl.decoder_model("model-graph", 72, "bf16", 2, 256, 2, 1, 128, 384, 777, 1, False, 8, 1e-3, 32, batch,
+                             qwen=True)
+        d = DeviceWorkload(w, DEV)
+        return d, DeviceModel(d)
+    d1, eager = build()
+    snaps = []
+    for _ in range(4):          # the graph side runs one warm-up step before the capture: 1 + 3 replays
+        eager.step(lr=1e-2)
+        torch.cuda.synchronize()
+        snaps.append((eager.final.clone(), d1.cand_loss.clone(), d1.proj_grad.clone(), [l.P.clone() for l in d1.layers]))
+    d2, graphed = build()
+    graphed.capture(lr=1e-2)
+    # the capture itself does not run the step: the state is that after the warm-up step
+    assert all(torch.equal(a, l.P) for a, l in zip(snaps[0][3], d2.layers))
+    for k in range(1, 4):
+        graphed.replay()
+        junk = torch.randn(1 << 16, device=DEV).sum()      # unrelated eager work between replays
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        assert torch.equal(graphed.final, snaps[k][0]), k
+        assert torch.equal(d2.cand_loss, snaps[k][1]) and torch.equal(d2.proj_grad, snaps[k][2]), k
+        assert all(torch.equal(a, l.P) for a, l in zip(snaps[k][3], d2.layers)), k
+    assert not torch.equal(snaps[0][3][0], snaps[3][3][0])      # the banks did move from step to step
