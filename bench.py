@@ -236,7 +236,7 @@ def main():
     loop_info = None
     n_blocks = int(w.layers[0].R_used) // (w.r * d.batch.K) if w.layers[0].P is not None else 0
     if n_blocks >= 1:
-        loop = LoopDriver(d, nu=4, n_blocks=n_blocks, lr=1e-7, base_u=1, base_v=2)
+        loop = LoopDriver(d, nu=4, n_blocks=n_blocks, lr=1e-10, base_u=1, base_v=2)   # small enough for the losses to stay put
 
         def time_loop(fn, n):
             loop.reset()
