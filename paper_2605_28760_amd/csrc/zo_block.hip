@@ -522,56 +522,81 @@ __device__ __forceinline__ float rope_angle(float log2_theta, int i, int dh, int
   return (float)pos * exp2f(-(float)(2 * i) / (float)dh * log2_theta);
 }
 
-// bf16, head dimension 128, in place.  A wave takes four heads of one token: the 16 lanes of a head hold
-// elements 4j..4j+3 and their rotation partners 64+4j..64+4j+3 (j = lane % 16), so the per-head sum of
-// squares is four shuffles and the rotation is lane-local.  Heads 0..H-1 are queries, H..H+Hkv-1 keys.
+// bf16, head dimension 128, in place.  One wave per token, four heads at a time: the 16 lanes of a head
+// hold elements 4j..4j+3 and their rotation partners 64+4j..64+4j+3 (j = lane % 16), so the per-head sum
+// of squares is four shuffles and the rotation is lane-local.  The token's position and the four
+// (cos, sin) pairs of a lane depend on neither the head nor on queries versus keys: they are computed
+// once per token, under the first loads.  Heads 0..H-1 are queries, H..H+Hkv-1 keys.
 __global__ __launch_bounds__(256) void k_qk_norm_rope_bf16(QkRopeArgs a) {
   const int lane = threadIdx.x & 63;
-  const int groups = (a.n_heads + a.n_kv_heads + 3) >> 2;
-  const int64_t item = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (item >= (int64_t)a.T * groups) return;
-  const int t = (int)(item / groups), head = (int)(item % groups) * 4 + (lane >> 4);
-  const int j = lane & 15;
-  const bool live = head < a.n_heads + a.n_kv_heads;
-  const bool is_q = head < a.n_heads;
-  bf16_t* row = nullptr;
-  if (live)
-    row = is_q ? (bf16_t*)a.Q + (int64_t)t * a.ldq + head * 128 : (bf16_t*)a.K + (int64_t)t * a.ldk + (head - a.n_heads) * 128;
-  float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // [0..3] first half, [4..7] partners
-  if (live) {
-    const uint2 lo = *reinterpret_cast<const uint2*>(row + 4 * j), hi = *reinterpret_cast<const uint2*>(row + 64 + 4 * j);
-    x[0] = __uint_as_float(lo.x << 16); x[1] = __uint_as_float(lo.x & 0xFFFF0000u);
-    x[2] = __uint_as_float(lo.y << 16); x[3] = __uint_as_float(lo.y & 0xFFFF0000u);
-    x[4] = __uint_as_float(hi.x << 16); x[5] = __uint_as_float(hi.x & 0xFFFF0000u);
-    x[6] = __uint_as_float(hi.y << 16); x[7] = __uint_as_float(hi.y & 0xFFFF0000u);
-  }
-  if (a.gamma_q) {
-    float ss = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
-#pragma unroll
-    for (int o = 8; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
-    const float rstd = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
-    const float* gam = is_q ? a.gamma_q : a.gamma_k;
-    const float4 g0 = *reinterpret_cast<const float4*>(gam + 4 * j), g1 = *reinterpret_cast<const float4*>(gam + 64 + 4 * j);
-    x[0] *= rstd * g0.x; x[1] *= rstd * g0.y; x[2] *= rstd * g0.z; x[3] *= rstd * g0.w;
-    x[4] *= rstd * g1.x; x[5] *= rstd * g1.y; x[6] *= rstd * g1.z; x[7] *= rstd * g1.w;
-  }
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= a.T) return;
+  const int heads = a.n_heads + a.n_kv_heads;
+  const int groups = (heads + 3) >> 2;
+  const int j = lane & 15, hh = lane >> 4;
+  auto row_of = [&](int head) -> bf16_t* {
+    return head < a.n_heads ? (bf16_t*)a.Q + (int64_t)t * a.ldq + head * 128
+                            : (bf16_t*)a.K + (int64_t)t * a.ldk + (head - a.n_heads) * 128;
+  };
+  auto load = [&](int grp, uint2& lo, uint2& hi) {
+    const int head = grp * 4 + hh;
+    lo = hi = make_uint2(0u, 0u);
+    if (head < heads) {
+      const bf16_t* row = row_of(head);
+      lo = *reinterpret_cast<const uint2*>(row + 4 * j);
+      hi = *reinterpret_cast<const uint2*>(row + 64 + 4 * j);
+    }
+  };
+  uint2 lo, hi;
+  load(0, lo, hi);
+  float cs[4] = {1.f, 1.f, 1.f, 1.f}, sn[4] = {0.f, 0.f, 0.f, 0.f};
   if (a.theta > 0.f) {
     const int pos = t - a.cu[seq_of_row(a.cu, a.S, t)];
     const float l2t = log2f(a.theta);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      float sn, cs;
-      sincosf(rope_angle(l2t, 4 * j + e, 128, pos), &sn, &cs);
-      const float p = x[e], q = x[4 + e];
-      x[e] = p * cs - q * sn;
-      x[4 + e] = q * cs + p * sn;
-    }
+    for (int e = 0; e < 4; ++e) sincosf(rope_angle(l2t, 4 * j + e, 128, pos), &sn[e], &cs[e]);
   }
-  if (live) {
-    *reinterpret_cast<uint2*>(row + 4 * j) = make_uint2(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]));
-    *reinterpret_cast<uint2*>(row + 64 + 4 * j) = make_uint2(pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+  float4 gq0 = make_float4(1.f, 1.f, 1.f, 1.f), gq1 = gq0, gk0 = gq0, gk1 = gq0;
+  if (a.gamma_q) {
+    gq0 = *reinterpret_cast<const float4*>(a.gamma_q + 4 * j);
+    gq1 = *reinterpret_cast<const float4*>(a.gamma_q + 64 + 4 * j);
+    gk0 = *reinterpret_cast<const float4*>(a.gamma_k + 4 * j);
+    gk1 = *reinterpret_cast<const float4*>(a.gamma_k + 64 + 4 * j);
+  }
+  for (int grp = 0; grp < groups; ++grp) {
+    uint2 nlo, nhi;
+    if (grp + 1 < groups) load(grp + 1, nlo, nhi);   // the next four heads travel under this group's arithmetic
+    const int head = grp * 4 + hh;
+    const bool is_q = head < a.n_heads;
+    float x[8];   // [0..3] first half, [4..7] partners
+    x[0] = __uint_as_float(lo.x << 16); x[1] = __uint_as_float(lo.x & 0xFFFF0000u);
+    x[2] = __uint_as_float(lo.y << 16); x[3] = __uint_as_float(lo.y & 0xFFFF0000u);
+    x[4] = __uint_as_float(hi.x << 16); x[5] = __uint_as_float(hi.x & 0xFFFF0000u);
+    x[6] = __uint_as_float(hi.y << 16); x[7] = __uint_as_float(hi.y & 0xFFFF0000u);
+    if (a.gamma_q) {
+      float ss = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss += x[e] * x[e];
+#pragma unroll
+      for (int o = 8; o >= 1; o >>= 1) ss += __shfl_xor(ss, o);
+      const float rstd = 1.0f / sqrtf(ss * (1.0f / 128.0f) + a.eps);
+      const float4 g0 = is_q ? gq0 : gk0, g1 = is_q ? gq1 : gk1;
+      x[0] *= rstd * g0.x; x[1] *= rstd * g0.y; x[2] *= rstd * g0.z; x[3] *= rstd * g0.w;
+      x[4] *= rstd * g1.x; x[5] *= rstd * g1.y; x[6] *= rstd * g1.z; x[7] *= rstd * g1.w;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float p = x[e], q = x[4 + e];
+      x[e] = p * cs[e] - q * sn[e];
+      x[4 + e] = q * cs[e] + p * sn[e];
+    }
+    if (head < heads) {
+      bf16_t* row = row_of(head);
+      *reinterpret_cast<uint2*>(row + 4 * j) = make_uint2(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]));
+      *reinterpret_cast<uint2*>(row + 64 + 4 * j) = make_uint2(pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+    }
+    lo = nlo;
+    hi = nhi;
   }
 }
 
@@ -640,8 +665,7 @@ hipError_t launch_qk_norm_rope(const QkRopeArgs& a, hipStream_t st) {
   const bool fast = a.bf16 && a.dh == 128 && aligned(a.Q, a.ldq) && aligned(a.K, a.ldk) &&
                     (((uintptr_t)a.gamma_q | (uintptr_t)a.gamma_k) & 15u) == 0;
   if (fast) {
-    const int64_t items = (int64_t)a.T * ((heads + 3) / 4);
-    k_qk_norm_rope_bf16<<<dim3((unsigned)((items + 3) / 4)), 256, 0, st>>>(a);
+    k_qk_norm_rope_bf16<<<dim3((unsigned)((a.T + 3) / 4)), 256, 0, st>>>(a);
   } else {
     const int64_t items = (int64_t)a.T * heads;
     if (a.bf16) k_qk_norm_rope_any<bf16_t><<<dim3((unsigned)((items + 3) / 4)), 256, 0, st>>>(a);
