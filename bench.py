@@ -114,6 +114,44 @@ def _block_section(name, n_rep):
             "share_outside_probe_linears": 1.0 - gemm_ms / sum(ms.values())}
 
 
+def _layer_set_section(n_rep):
+    """Secondary: the six OPT-13B-shaped linears at 16 x 256 x {+,-} = 8192 rows (one direction of rank 8, bank of
+    rank 64), each zo_probe_linear call timed alone on its own input, with the candidates and with every
+    sequence foreground (the plain GEMM of the same shape)."""
+    import numpy as np
+    import torch
+    from paper_2605_28760_amd import workloads as wl
+    from paper_2605_28760_amd.runner import DeviceBatch, DeviceWorkload
+    w = wl.BUILDERS["c2"]()
+    d = DeviceWorkload(w, "cuda:0")
+    st = torch.cuda.current_stream()
+    fg = DeviceBatch(w.cu_seqlens, np.full_like(w.seq_cand, -1), w.cand_dir, w.cand_sign, w.dir_seed, "cuda:0")
+
+    def timed(fn):
+        fn()
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(n_rep):
+            fn()
+        e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_rep
+    layers, total_ms, total_flops = {}, 0.0, 0.0
+    for i, l in enumerate(w.layers):
+        ms = timed(lambda: d.probe_linear(i, stream=st))
+        plain = timed(lambda: d.probe_linear(i, stream=st, batch=fg))
+        flops = 2.0 * w.T * l.m * l.n
+        layers[l.name] = {"m": l.m, "n": l.n, "ms": ms, "tflops": flops / (ms * 1e-3) / 1e12,
+                          "frac_mfma_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, "plain_ms": plain}
+        total_ms += ms
+        total_flops += flops
+    return {"workload": w.name, "rows": w.T, "r": w.r, "bank_rank": int(w.layers[0].R_used), "layers": layers,
+            "all_six_ms": total_ms, "tflops": total_flops / (total_ms * 1e-3) / 1e12,
+            "frac_mfma_peak": total_flops / (total_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "candidate_tokens_per_s_through_the_six": w.T / (total_ms * 1e-3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -122,6 +160,8 @@ def main():
     ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-block", action="store_true", help="skip the decoder-block secondary measurement")
+    ap.add_argument("--no-layer-set", action="store_true",
+                    help="skip the secondary measurement of the six OPT-13B-shaped linears at 8192 rows")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -299,6 +339,10 @@ def main():
     if not args.no_block:
         block_info = _block_section({"c3": "b3"}.get(args.workload, "b4"), n_sec)
 
+    layer_set_info = None
+    if args.workload == "c3" and not args.no_layer_set:
+        layer_set_info = _layer_set_section(n_sec)
+
     seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
     seg_ms = seg.mean(axis=0)
     breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
@@ -340,6 +384,7 @@ def main():
         "native_over_matched": ms_per_step / plain_ms,
         "loop": loop_info,
         "block": block_info,
+        "layer_set": layer_set_info,
         "bank_update_40_layers": bank40,
         "active_token_scoring": {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms},
         "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},

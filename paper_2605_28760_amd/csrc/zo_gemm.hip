@@ -143,29 +143,51 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
 //
 // With kGather the N rows of the B operand are rows b_rows[0..N-1] of a matrix of B_rows_total rows
 // (smaller than 2 GiB); the row list of a tile is fetched one tile ahead of the load cursor.
-template <bool kGather, class Pre, class Post>
+template <bool kGather, bool kSplit, class Pre, class Post>
 __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
-                                                int n_tm, int n_tn, char* lds, Pre pre, Post post,
+                                                int n_tm, int n_tn, int n_split, char* lds, Pre pre, Post post,
                                                 const int32_t* __restrict__ b_rows = nullptr, int B_rows_total = 0) {
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // Workgroup -> tiles.  Consecutive workgroup ids land on consecutive XCDs, so blockIdx.x % 8
+  // Workgroup -> work items.  Consecutive workgroup ids land on consecutive XCDs, so blockIdx.x % 8
   // is the XCD and blockIdx.x / 8 a slot on it.  The raster is cut into chunks of `slots`
   // positions (32 on a full chip: an 8x4 block of tiles, 12 operand slices for 32 tiles in
   // that XCD's L2); chunk c goes to XCD c % 8, so at any time the eight XCDs work on eight
   // neighbouring chunks, which share their eight weight-row tiles: the weight slices reach
   // the chip once per step, not once per XCD.
+  //
+  // With kSplit the last n_split raster positions are two work items each, the halves of 128 A rows
+  // of the tile: a last round that would occupy at most half of the workgroups with whole tiles
+  // occupies twice as many with halves.  A half is a tile whose A rows start 128 further down and in
+  // which only the waves of the upper wave row (one per SIMD) multiply and store; the others only
+  // take part in the loads (the whole 256-row stage is still filled: a branch around a load would split
+  // the K loop's schedule) and barriers.  The K order of an output element is the same either way.
   const int total = n_tm * n_tn;
+  const int first_split = total - (kSplit ? n_split : 0);
   const int xcd = blockIdx.x % kXcds;
   const int slots = gridDim.x / kXcds;
   const int stride = kXcds * slots;
-  const int L_end = total;
+  const int L_end = total + (kSplit ? n_split : 0);
   int L = xcd * slots + blockIdx.x / kXcds;
   if (L >= L_end) return;
+  // item -> first A row, first B row of its tile; returns whether it is a half
+  auto item_at = [&](int I, int& m0, int& n0) -> bool {
+    int pos = I, half = 0;
+    const bool is_half = kSplit && I >= first_split;
+    if (is_half) {
+      pos = first_split + ((I - first_split) >> 1);
+      half = (I - first_split) & 1;
+    }
+    int tm, tn;
+    tile_at(pos, n_tm, n_tn, tm, tn);
+    m0 = tm * BM + half * (BM / 2);
+    n0 = tn * BN;
+    return is_half;
+  };
   const int nk = K / BK;
 
   // LDS -> register mapping
@@ -181,14 +203,14 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   int ld_L = L, ld_kt = 0;
   int idx_next[kLPW] = {};   // gather: B rows of the tile after the cursor's
   {
-    int tm, tn;
-    tile_at(ld_L, n_tm, n_tn, tm, tn);
+    int m0, n0;
+    item_at(ld_L, m0, n0);
     int idx[kLPW] = {};
-    if (kGather) gather_rows(idx, b_rows, N, tn * BN, wave, lane);
-    setup_stream<kGather>(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane, idx, B_rows_total);
+    if (kGather) gather_rows(idx, b_rows, N, n0, wave, lane);
+    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx, B_rows_total);
     if (kGather) {
-      tile_at(min(ld_L + stride, L_end - 1), n_tm, n_tn, tm, tn);
-      gather_rows(idx_next, b_rows, N, tn * BN, wave, lane);
+      item_at(min(ld_L + stride, L_end - 1), m0, n0);
+      gather_rows(idx_next, b_rows, N, n0, wave, lane);
     }
   }
   // load i (0..7) of the cursor's K tile: i < 4 -> A chunk i, else B chunk i - 4
@@ -209,12 +231,12 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     if (ld_L + stride < L_end) {
       ld_L += stride;
       ld_kt = 0;
-      int tm, tn;
-      tile_at(ld_L, n_tm, n_tn, tm, tn);
-      setup_stream<kGather>(ld, A, lda, M, tm * BM, B, ldb, N, tn * BN, K, wave, lane, idx_next, B_rows_total);
+      int m0, n0;
+      item_at(ld_L, m0, n0);
+      setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total);
       if (kGather) {
-        tile_at(min(ld_L + stride, L_end - 1), n_tm, n_tn, tm, tn);
-        gather_rows(idx_next, b_rows, N, tn * BN, wave, lane);
+        item_at(min(ld_L + stride, L_end - 1), m0, n0);
+        gather_rows(idx_next, b_rows, N, n0, wave, lane);
       }
     }
   };
@@ -252,48 +274,62 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
 
   int stage = 0;
   for (; L < L_end; L += stride) {
-    int tm, tn;
-    tile_at(L, n_tm, n_tn, tm, tn);
-    Acc acc;
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    pre(tm, tn, acc);
-    // The first fragments of this tile were already fetched under the previous tile's last
-    // k-step; fetching them again here keeps their 48 registers free during post() and pre().
-    load_frags(0, stage, 0);
+    int m0, n0;
+    const bool is_half = item_at(L, m0, n0);
+    const bool active = !(kSplit && is_half && wm == 1);   // wave-uniform
 
-    auto mfmas = [&](int set) {
+    // the K loop of a wave that multiplies (kActive) or only keeps the operand stream and the barriers going
+    auto k_loop = [&](auto active_c, Acc& acc) __attribute__((always_inline)) {
+      constexpr bool kActive = decltype(active_c)::value;
+      auto mfmas = [&](int set) __attribute__((always_inline)) {
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int cb = 0; cb < CB; ++cb)
+            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
+      };
+      for (int kt = 0; kt < nk; ++kt) {
+        // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
+        __builtin_amdgcn_sched_barrier(0);
+        issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
+        if constexpr (kActive) {
+          load_frags(1, stage, 1);
+          mfmas(0);
+          pattern(std::integral_constant<int, kLoadsEarly>{});
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // the next K tile has landed; every wave is done reading this K tile's stage
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        block_barrier();
+        advance_cursor();
+        __builtin_amdgcn_sched_barrier(0);
+        // k-step 1: first fragments of the next K tile, first loads of the one after it
+        issue_range(stage, 0, kLoadsLate);
+        if constexpr (kActive) {
+          load_frags(0, stage ^ 1, 0);
+          mfmas(1);
+          pattern(std::integral_constant<int, kLoadsLate>{});
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        stage ^= 1;
+      }
+    };
+    if (active) {
+      Acc acc;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-          acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
-    };
-
-    for (int kt = 0; kt < nk; ++kt) {
-      // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
-      __builtin_amdgcn_sched_barrier(0);
-      issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
-      load_frags(1, stage, 1);
-      mfmas(0);
-      pattern(std::integral_constant<int, kLoadsEarly>{});
-      __builtin_amdgcn_sched_barrier(0);
-      // the next K tile has landed; every wave is done reading this K tile's stage
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-      block_barrier();
-      advance_cursor();
-      __builtin_amdgcn_sched_barrier(0);
-      // k-step 1: first fragments of the next K tile, first loads of the one after it
-      issue_range(stage, 0, kLoadsLate);
-      load_frags(0, stage ^ 1, 0);
-      mfmas(1);
-      pattern(std::integral_constant<int, kLoadsLate>{});
-      __builtin_amdgcn_sched_barrier(0);
-      stage ^= 1;
+        for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      pre(m0, n0, acc);
+      // The first fragments of this tile were already fetched under the previous tile's last
+      // k-step; fetching them again here keeps their 48 registers free during post() and pre().
+      load_frags(0, stage, 0);
+      k_loop(std::true_type{}, acc);
+      post(m0, n0, acc);
+    } else if constexpr (kSplit) {
+      Acc none;   // never touched: this instance of the loop multiplies nothing
+      k_loop(std::false_type{}, none);
     }
-    post(tm, tn, acc);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads before the workgroup ends
 }
@@ -307,6 +343,16 @@ int compute_units() {
     cus = n;
   }
   return cus;
+}
+
+// How many of the last tiles of the raster are cut into two halves of 128 weight rows: all tiles of a last
+// round that would leave at least half of the workgroups without one.  Only when every tile has rows in
+// both halves (the last weight-row tile holds more than 128 rows), so that no half is empty.
+static int split_tiles(int total_tiles, int m) {
+  const int cus = compute_units();
+  const int rem = total_tiles % cus;
+  if (rem == 0 || rem > cus / 2 || (m - 1) % BM < BM / 2) return 0;
+  return rem;
 }
 
 static int gemm_grid(int total_tiles) {
@@ -325,8 +371,10 @@ static int gemm_grid(int total_tiles) {
 // silu(gate) * up, the gated-MLP epilogue (activation 2): adjacent output features are (gate, up) pairs
 __device__ __forceinline__ float silu_mul(float gate, float up) { return gate / (1.0f + __expf(-gate)) * up; }
 
-template <bool kSide, bool kOutBf16, bool kBias, bool kGate>
-__global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn) {
+// kSplit: the variant whose last round is made of half tiles (n_split > 0); the launcher takes it only when
+// the tile count leaves such a round, so every other shape runs the loop without the extra branches.
+template <bool kSide, bool kOutBf16, bool kBias, bool kGate, bool kSplit>
+__global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn, int n_split) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -335,11 +383,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
 
   // side operands have K = RP (direction) and K = Rp (bank), multiples of 16; the K=32
   // instruction takes them 32 at a time, lanes whose k-group lies past the end supply zeros
-  auto side_phase = [&](int tm, int tn, Acc& acc) {
+  auto side_phase = [&](int tile_o0, int tile_t0, Acc& acc) {
     if constexpr (!kSide) return;
     const int lane_t = opaque(lane);
     const int r16 = lane_t & 15, kg = (lane_t >> 4) * 8;
-    const int tile_o0 = tm * BM, tile_t0 = tn * BN;
     const int NC = p.RP + p.Rp;
     const int tile_end = min(tile_t0 + BN, p.T);
     int feat[RB], tok[CB];
@@ -397,11 +444,11 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
   };
 
   // D block (rb, cb): out feature = obase + rb*16 + 4*g + v, token = tbase + cb*16 + r16.
-  auto epilogue = [&](int tm, int tn, Acc& acc) {
+  auto epilogue = [&](int tile_o0, int tile_t0, Acc& acc) {
     const int lane_t = opaque(lane);
     const int r16 = lane_t & 15, g = lane_t >> 4;
-    const int obase = tm * BM + wm * 128;   // first out feature of this wave
-    const int tbase = tn * BN + wn * 64;    // first token of this wave
+    const int obase = tile_o0 + wm * 128;   // first out feature of this wave
+    const int tbase = tile_t0 + wn * 64;    // first token of this wave
     const float floor_val = p.act == 1 ? 0.0f : -INFINITY;   // ReLU as a clamp: no branch in the tile epilogue
     if constexpr (!kOutBf16) {
       float* Y = (float*)p.Y;
@@ -503,22 +550,29 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
     }
   };
 
-  persistent_gemm<false>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, lds, side_phase, epilogue);
+  persistent_gemm<false, kSplit>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, n_split, lds, side_phase, epilogue);
 }
 
-template <bool kSide, bool kOutBf16, bool kBias, bool kGate>
-static hipError_t launch_probe_variant(const ProbeGemmArgs& a, hipStream_t st) {
+template <bool kSide, bool kOutBf16, bool kBias, bool kGate, bool kSplit>
+static hipError_t launch_probe_kernel(const ProbeGemmArgs& a, int n_tm, int n_tn, int n_split, hipStream_t st) {
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias, kGate>,
+    hipError_t e = hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int n_tm = (a.m + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias, kGate>), dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds,
-                     st, a, n_tm, n_tn);
+  hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>), dim3(gemm_grid(n_tm * n_tn + n_split)),
+                     dim3(kThreads), kGemmLds, st, a, n_tm, n_tn, n_split);
   return hipGetLastError();
+}
+
+template <bool kSide, bool kOutBf16, bool kBias, bool kGate>
+static hipError_t launch_probe_variant(const ProbeGemmArgs& a, hipStream_t st) {
+  const int n_tm = (a.m + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
+  const int n_split = split_tiles(n_tm * n_tn, a.m);
+  return n_split > 0 ? launch_probe_kernel<kSide, kOutBf16, kBias, kGate, true>(a, n_tm, n_tn, n_split, st)
+                     : launch_probe_kernel<kSide, kOutBf16, kBias, kGate, false>(a, n_tm, n_tn, 0, st);
 }
 
 template <bool kSide, bool kOutBf16>
@@ -561,10 +615,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
 
   auto no_side = [](int, int, Acc&) {};
   // D block (rb, cb): vocabulary row = vbase + rb*16 + 4*g + v, token = tile_t0 + wn*64 + cb*16 + r16.
-  auto epilogue = [&](int tm, int tn, Acc& acc) {
+  auto epilogue = [&](int tile_v0, int tile_t0, Acc& acc) {
     const int lane_t = opaque(lane), tid_t = opaque(tid);
     const int r16 = lane_t & 15, g = lane_t >> 4;
-    const int tile_v0 = tm * BM, tile_t0 = tn * BN;
+    const int tm = tile_v0 / BM;   // vocabulary tile: the index of this tile's partials
     const int vbase = tile_v0 + wm * 128;  // first vocabulary row of this wave
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
@@ -623,7 +677,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
     block_barrier();   // the exchange buffers are free again for the next tile
   };
 
-  persistent_gemm<kGather>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, lds, no_side, epilogue, p.rows, p.T);
+  persistent_gemm<kGather, false>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, 0, lds, no_side, epilogue, p.rows, p.T);
 }
 
 template <bool kGather>

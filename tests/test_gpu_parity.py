@@ -474,6 +474,25 @@ def test_bf16_probe_linear_odd_shapes(case):
     assert_close(y32, oracle_layer(w, 0, w.layers[0].X, out_dtype="f32"), 2e-2, "fp32 output")
 
 
+@pytest.mark.parametrize("act,bias", [(0, False), (1, True), (2, True)])
+def test_bf16_probe_linear_half_tiles_of_the_last_round(act, bias):
+    """A tile count that leaves a last round of at most half the workgroups (322 tiles on 256 compute
+    units: 66 left over) makes the matrix-core kernel cut those tiles into halves of 128 weight rows.
+    The result must not depend on that: parity with the oracle, and the rows of the halved tiles
+    bit-identical to a call over the last sequences alone, whose 130 tiles are all whole."""
+    lens = [24576, 4000, 0, 4000, 4000, 4421]                      # 40997 rows: 161 token tiles x 2 weight-row tiles
+    w = _single_layer(77, lens, seq_cand=[-1, 0, 1, 1, -1, 2], cand_dir=[0, 0, -1], cand_sign=[1, -1, 0],
+                      m=512, n=64, r=8, R=16, act=act, bias=bias)
+    d = DeviceWorkload(w, DEV)
+    d.probe_linear(0); _sync()
+    _per_layer_parity(w, d)
+    tail = wl.subset_sequences(w, [1, 2, 3, 4, 5])                   # rows 24576 .. : token tiles 96 .. 160
+    dt = DeviceWorkload(tail, DEV)
+    dt.probe_linear(0); _sync()
+    a, b = to_np(d.Y[0])[24576:], to_np(dt.Y[0])
+    assert a.shape == b.shape and np.array_equal(a, b)
+
+
 def test_scoring_with_an_input_pitch_beyond_the_gather_window():
     """H spanning 2 GiB or more (here through a large row pitch) cannot be addressed through the
     scored-token list; the head then multiplies every row.  Same results, same rules for unscored rows."""
