@@ -368,6 +368,13 @@ static int gemm_grid(int total_tiles) {
 // state a plain GEMM starts from, so foreground rows come out bit-identical to an
 // all-foreground call.
 // ---------------------------------------------------------------------------------------
+// 16-byte store of finished outputs with the non-temporal hint: a tile's 128 KiB of Y are written once
+// and read by a later kernel at the earliest, so they should not displace operand slices from the
+// caches (measured on the 20480 x 5120 layer at 16384 rows: 2.64 -> 2.58 ms; with no stores at all 2.56).
+__device__ __forceinline__ void store_streaming(bf16_t* dst, u32x4 val) {
+  __builtin_nontemporal_store(val, (u32x4*)dst);
+}
+
 // silu(gate) * up, the gated-MLP epilogue (activation 2): adjacent output features are (gate, up) pairs
 __device__ __forceinline__ float silu_mul(float gate, float up) { return gate / (1.0f + __expf(-gate)) * up; }
 
@@ -507,7 +514,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
           const int tl = it * 8 + (lane_t >> 3);
           const int t = tbase + cb * 16 + tl;
           const u32x4 val = *(const u32x4_alias*)(region + tl * 128 + ((chunk ^ (tl & 7)) << 4));
-          if (t < p.T && oo < (p.m >> 1)) *(u32x4_alias*)(Y + (int64_t)t * p.ldy + oo) = val;   // m % 16 == 0
+          if (t < p.T && oo < (p.m >> 1)) store_streaming(Y + (int64_t)t * p.ldy + oo, val);   // m % 16 == 0
         }
       }
       return;
@@ -545,7 +552,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
         const int tl = it * 4 + (lane_t >> 4);
         const int t = tbase + cb * 16 + tl;
         const u32x4 val = *(const u32x4_alias*)(region + tl * 256 + ((chunk ^ tl) * 16));
-        if (t < p.T && o < p.m) *(u32x4_alias*)(Y + (int64_t)t * p.ldy + o) = val;   // m % 8 == 0
+        if (t < p.T && o < p.m) store_streaming(Y + (int64_t)t * p.ldy + o, val);   // m % 8 == 0
       }
     }
   };
