@@ -47,7 +47,7 @@ extern "C" {
 typedef enum zo_status {
   ZO_OK = 0,
   ZO_ERR_NULL = -1,        /* a required pointer is NULL */
-  ZO_ERR_SHAPE = -2,       /* negative size, r outside [1,64], R_used > R_cap, bad leading dimension / alignment */
+  ZO_ERR_SHAPE = -2,       /* negative size, r outside [1,512], R_used > R_cap, bad leading dimension / alignment */
   ZO_ERR_INDEX = -3,       /* candidate / direction id out of range, malformed cu_seqlens (host mirrors only) */
   ZO_ERR_BANK_FULL = -4,   /* a direction's column block does not fit in the bank */
   ZO_ERR_WORKSPACE = -5,   /* workspace missing, misaligned or too small */
@@ -157,7 +157,9 @@ int32_t zo_batch_index(const zo_batch* batch, int32_t* tok_seq, int32_t* tok_can
  *   bias      fp32 [m] or NULL;  act 0 = none, 1 = ReLU, 2 = gated SiLU (the gated MLP of the
  *             Qwen3 family): output features are (gate_j, up_j) pairs in adjacent rows of W and
  *             Y[t, j] = silu(gate_j) * up_j, silu(x) = x / (1 + exp(-x)); Y then has m/2 columns
- *   r         rank of the probe, 1..64;  eps probe scale;  tensor_id even id of the layer
+ *   r         rank of the probe, 1..512 (the rank continuum of Sec. 3.3; its 1/sqrt(r) goes into eps; the
+ *             kernels are laid out for the small ranks of the paper's runs, larger ones cost in proportion);
+ *             eps probe scale;  tensor_id even id of the layer
  *   bank      NULL or R_used = 0: no bank
  * ZO_BF16 requires n % 64 == 0 (and, for bf16 output, a multiple of 8 output columns: m % 8 == 0, or
  * m % 16 == 0 with act 2), 16-byte aligned X, W, Y and leading dimensions that keep rows 16-byte aligned.

@@ -229,7 +229,7 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
                         zo_dtype out_dtype, void* workspace, size_t workspace_bytes, void* stream) {
   if (int32_t st = check_batch(batch)) return st;
   if (m < 0 || n < 0) return fail(ZO_ERR_SHAPE, "m = %d, n = %d", m, n);
-  if (r < 1 || r > 64) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, 64]", r);
+  if (r < 1 || r > zo::kMaxRank) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, %d]", r, zo::kMaxRank);
   if (in_dtype != ZO_F32 && in_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "in_dtype %d", (int)in_dtype);
   if (!(out_dtype == in_dtype || (in_dtype == ZO_BF16 && out_dtype == ZO_F32)))
     return fail(ZO_ERR_UNSUPPORTED, "in_dtype %d with out_dtype %d", (int)in_dtype, (int)out_dtype);
@@ -414,7 +414,7 @@ namespace {
 int32_t check_bank_update(const zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n_dirs, zo_dtype factor_dtype) {
   if (!bank) return fail(ZO_ERR_NULL, "bank is NULL");
   if (m < 0 || n < 0 || n_dirs < 0) return fail(ZO_ERR_SHAPE, "m = %d, n = %d, n_dirs = %d", m, n, n_dirs);
-  if (r < 1 || r > 64) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, 64]", r);
+  if (r < 1 || r > zo::kMaxRank) return fail(ZO_ERR_SHAPE, "rank r = %d outside [1, %d]", r, zo::kMaxRank);
   if (bank->R_cap < 0 || bank->R_used < 0 || bank->R_used > bank->R_cap)
     return fail(ZO_ERR_SHAPE, "bank R_used = %d, R_cap = %d", bank->R_used, bank->R_cap);
   if (factor_dtype != ZO_F32 && factor_dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "factor_dtype %d", (int)factor_dtype);

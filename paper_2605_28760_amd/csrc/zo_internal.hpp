@@ -11,6 +11,7 @@ namespace zo {
 constexpr int kTileM = 256;
 constexpr int kTileN = 256;
 constexpr int kTileK = 64;
+constexpr int kMaxRank = 512;     // largest probe rank r (the rank continuum of Sec. 3.3 goes up to 512)
 constexpr int kSideRows = 64;     // rows per side-down work item (one wave)
 constexpr int kSideMaxBlocks = 9; // 16-column blocks a side-down wave accumulates at once
 constexpr int kSimtTile = 64;     // tile edge of the fp32 vector-ALU kernels

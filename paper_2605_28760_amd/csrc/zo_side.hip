@@ -165,9 +165,10 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   // direction columns 16 .. RP-1 exist only for ranks above 16 and are handled by extra passes below
 }
 
-// Direction blocks beyond the first (ranks 17..64): same kernel shape with no bank blocks.
-// cbd = index of the 16-column direction block.
-__global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int cbd) {
+// Direction blocks beyond the first (ranks above 16): the same walk over X with no bank blocks, NDB
+// 16-column blocks of the item's own V per pass (blocks cbd0 .. cbd0 + NDB - 1).
+template <int NDB>
+__global__ __launch_bounds__(256) void k_side_down_dirblocks(SideDownArgs a, int cbd0) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int ksplit = a.n_items[1];
   const int group = blockIdx.x / ksplit, split = blockIdx.x - group * ksplit;
@@ -180,20 +181,28 @@ __global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int 
   const int q = steps_total / ksplit, rem = steps_total - q * ksplit;
   const int k_begin = (split * q + min(split, rem)) * 64, kchunk = (q + (split < rem ? 1 : 0)) * 64;
   const bool has_dir = it.kind >= 0;
-  f32x4 acc[4];
+  f32x4 acc[4][NDB];
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb) acc[rb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+    for (int b = 0; b < NDB; ++b) acc[rb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
   if (has_dir) {
-    const bf16_t* pv = a.Vt + ((int64_t)it.kind * a.RP + cbd * 16 + lr) * a.n + k_begin + lg * 8;
+    const bf16_t* pv = a.Vt + ((int64_t)it.kind * a.RP + cbd0 * 16 + lr) * a.n + k_begin + lg * 8;
     const bf16_t* pa[4];
 #pragma unroll
     for (int rb = 0; rb < 4; ++rb)
       pa[rb] = a.X + (int64_t)(it.row0 + min(rb * 16 + lr, it.nrows - 1)) * a.ldx + k_begin + lg * 8;
     for (int k = 0; k < kchunk; k += 32) {
-      const bf16x8 fb = load_frag(pv + k);
+      bf16x8 fa[4], fb[NDB];
+#pragma unroll
+      for (int rb = 0; rb < 4; ++rb) fa[rb] = load_frag(pa[rb] + k);
+#pragma unroll
+      for (int b = 0; b < NDB; ++b) fb[b] = load_frag(pv + (int64_t)b * 16 * a.n + k);
 #pragma unroll
       for (int rb = 0; rb < 4; ++rb)
-        acc[rb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(load_frag(pa[rb] + k), fb, acc[rb], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < NDB; ++b)
+          acc[rb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[rb], fb[b], acc[rb][b], 0, 0, 0);
     }
   }
 #pragma unroll
@@ -203,9 +212,12 @@ __global__ __launch_bounds__(256) void k_side_down_dirblock(SideDownArgs a, int 
       const int lrow = rb * 16 + lg * 4 + v;
       if (lrow >= it.nrows) continue;
       const int64_t row = it.row0 + lrow;
-      const int col = cbd * 16 + lr;
-      if (ksplit == 1) a.Aside[row * NC + col] = f32_to_bf16(has_dir ? it.scale * acc[rb][v] : 0.0f);
-      else a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][v];
+#pragma unroll
+      for (int b = 0; b < NDB; ++b) {
+        const int col = (cbd0 + b) * 16 + lr;
+        if (ksplit == 1) a.Aside[row * NC + col] = f32_to_bf16(has_dir ? it.scale * acc[rb][b][v] : 0.0f);
+        else a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][b][v];
+      }
     }
 }
 
@@ -261,9 +273,13 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
     launch_pass_n<false>(nb, a, done, st);
     done += nb;
   }
-  for (int cbd = 1; cbd < a.RP / 16; ++cbd) {   // ranks above 16
+  for (int cbd = 1; cbd < a.RP / 16;) {   // ranks above 16: up to 8 further direction blocks per pass over X
     dim3 grid(a.ks_cap * ((a.max_items + 3) / 4));
-    hipLaunchKernelGGL(k_side_down_dirblock, grid, dim3(256), 0, st, a, cbd);
+    const int left = a.RP / 16 - cbd;
+    if (left >= 8) { hipLaunchKernelGGL(k_side_down_dirblocks<8>, grid, dim3(256), 0, st, a, cbd); cbd += 8; }
+    else if (left >= 4) { hipLaunchKernelGGL(k_side_down_dirblocks<4>, grid, dim3(256), 0, st, a, cbd); cbd += 4; }
+    else if (left >= 2) { hipLaunchKernelGGL(k_side_down_dirblocks<2>, grid, dim3(256), 0, st, a, cbd); cbd += 2; }
+    else { hipLaunchKernelGGL(k_side_down_dirblocks<1>, grid, dim3(256), 0, st, a, cbd); cbd += 1; }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -75,7 +75,7 @@ def test_batch_validation():
 def test_probe_linear_validation():
     b = _host_batch()
     assert _status(_probe, b, r=0) == zb.ZO_ERR_SHAPE
-    assert _status(_probe, b, r=65) == zb.ZO_ERR_SHAPE
+    assert _status(_probe, b, r=513) == zb.ZO_ERR_SHAPE
     assert _status(_probe, b, X=None) == zb.ZO_ERR_NULL
     assert _status(_probe, b, n=72) == zb.ZO_ERR_UNSUPPORTED                     # bf16 needs n % 64 == 0
     assert _status(_probe, b, ld=60) == zb.ZO_ERR_SHAPE                          # ld < n

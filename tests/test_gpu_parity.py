@@ -266,6 +266,30 @@ def test_bank_update_parity(dtype):
     assert e.value.status == zb.ZO_ERR_BANK_FULL
 
 
+def test_bank_update_at_rank_128():
+    """The lazy update with a block of 128 columns per direction (rank continuum), append then accumulate."""
+    m, n, r, R_cap = 150, 90, 128, 256
+    seeds = np.array([21, 22], np.uint64)
+    b = zo.Batch(np.array([0, 1], np.int32), np.array([0], np.int32), np.array([0], np.int32), np.array([1.0], np.float32), seeds)
+    grads = np.array([0.75, -1.5], np.float32)
+    Pd = torch.zeros((m, R_cap), device=DEV); Vd = torch.zeros((n, R_cap), device=DEV)
+    bank = zb.make_bank(R_cap, 0, Pd, Vd)
+    g = torch.from_numpy(grads).to(DEV); sd = torch.from_numpy(seeds.view(np.int64)).to(DEV)
+    col0 = np.array([0, 128], np.int32)
+    zb.zo_bank_update(bank, m, n, r, 2, sd, 8, g, 0.2, None, col0, 1, zb.ZO_BF16); _sync()
+    want = zo.bank_update(zo.Bank(np.zeros((m, R_cap), np.float32), np.zeros((n, R_cap), np.float32), 0), b, m, n, r, 8, grads, 0.2,
+                          [0, 128], append=True, factor_dtype="bf16")
+    assert bank.R_used == 256 == want.R_used
+    zb.zo_bank_update(bank, m, n, r, 2, sd, 8, g, 0.1, None, col0, 0, zb.ZO_BF16); _sync()
+    want = zo.bank_update(want, b, m, n, r, 8, grads, 0.1, [0, 128], factor_dtype="bf16")
+    # U and V are rounded to bf16 from fp32 normals that may differ from the oracle's in the last bit: an entry
+    # may land one bf16 step away, rarely; everything else agrees to fp32 accuracy
+    gotP, gotV = Pd.cpu().numpy().astype(np.float64), Vd.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(gotP - want.P) <= 2.0 ** -7 * np.abs(want.P) + 1e-6)
+    assert np.mean(np.abs(gotP - want.P) <= 1e-5 * np.abs(want.P) + 1e-7) >= 0.999
+    assert np.all(np.abs(gotV - want.Vb) <= 2.0 ** -7 * np.abs(want.Vb) + 1e-6)
+
+
 def test_bank_update_of_many_layers_in_one_call_equals_the_per_layer_updates():
     """zo_bank_update_multi over 50 layers of mixed shapes (more than one launch holds), accumulate and
     append, against zo_bank_update layer by layer: bit for bit, including the columns left alone."""
@@ -439,15 +463,16 @@ def _single_layer(seed, lens, seq_cand, cand_dir, cand_sign, m, n, r, R, act=0, 
                        (np.arange(K, dtype=np.uint64) + np.uint64(991 + seed)), [layer], False)
 
 
-@pytest.mark.parametrize("case", range(14))
+@pytest.mark.parametrize("case", range(17))
 def test_bf16_probe_linear_odd_shapes(case):
     """Shapes that leave ragged tails in every tile dimension of the matrix-core kernel (out features
     not a multiple of 16, 128 or 256; one token; token counts just past a tile; many short sequences of
     different directions inside one token tile; ranks 1 and 64; a bank wider than one side-down pass;
     input widths whose 64-column steps do not divide evenly among the side-down pass's k ranges; bias with
     ReLU; the gated activation with and without bias, with out-feature counts that end inside a wave's
-    128-feature strip and inside a 16-feature block; the largest rank with a bank of 528 columns, which
-    takes five side-down passes over the input)."""
+    128-feature strip and inside a 16-feature block; rank 64 with a bank of 528 columns, which takes
+    five side-down passes over the input; the ranks of the rank continuum, 128 next to a bank, 200 and 512,
+    whose direction columns take further passes of 8, 4, 2 or 1 blocks of 16)."""
     cases = [
         dict(lens=[1], seq_cand=[0], cand_dir=[0], cand_sign=[1], m=8, n=64, r=1, R=0),
         dict(lens=[257, 3], seq_cand=[0, 1], cand_dir=[0, 0], cand_sign=[1, -1], m=200, n=128, r=5, R=16),
@@ -465,6 +490,9 @@ def test_bf16_probe_linear_odd_shapes(case):
         dict(lens=[257, 3, 60], seq_cand=[0, 1, -1], cand_dir=[0, 0], cand_sign=[1, -1], m=528, n=128, r=8, R=16, act=2, bias=True),
         dict(lens=[130, 5], seq_cand=[1, 0], cand_dir=[0, 0], cand_sign=[1, -1], m=1072, n=64, r=4, R=0, act=2),
         dict(lens=[90, 40, 7], seq_cand=[0, -1, 1], cand_dir=[0, -1], cand_sign=[1, 0], m=40, n=576, r=64, R=528),
+        dict(lens=[100, 60, 0, 33], seq_cand=[0, 1, 2, -1], cand_dir=[0, 0, 1], cand_sign=[1, -1, 1], m=264, n=256, r=128, R=32),
+        dict(lens=[70, 130], seq_cand=[1, 0], cand_dir=[0, 0], cand_sign=[1, -1], m=136, n=320, r=200, R=0, act=1, bias=True),
+        dict(lens=[258, 5], seq_cand=[0, 1], cand_dir=[0, 1], cand_sign=[1, -1], m=72, n=192, r=512, R=16),
     ]
     w = _single_layer(case, **cases[case])
     d = DeviceWorkload(w, DEV)
