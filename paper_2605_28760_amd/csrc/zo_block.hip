@@ -310,8 +310,12 @@ __global__ __launch_bounds__(kAttnWaves* kWave, 2) void k_attention_bf16(AttnArg
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r16 = lane & 15, g = lane >> 4;
   int seq, qb;
-  if (!find_query_block(a.cu, a.S, blockIdx.x, lane, seq, qb)) return;
-  const int h = blockIdx.y, kvh = h / a.group;
+  // One-dimensional grid, heads fastest: the slots past the last query block (the grid is an upper bound) are
+  // the last workgroups dispatched instead of a burst after every head, and the query heads that share a
+  // key/value head run next to each other (ragged Qwen3-shaped batch: 187 -> 166 us).
+  const int slot_id = blockIdx.x / a.n_heads;
+  if (!find_query_block(a.cu, a.S, slot_id, lane, seq, qb)) return;
+  const int h = blockIdx.x - slot_id * a.n_heads, kvh = h / a.group;
   const int row_a = a.cu[seq], row_b = a.cu[seq + 1];       // the sequence is rows [row_a, row_b)
   const int q0 = row_a + qb * kBQ;
   const int q_last = min(q0 + kBQ, row_b) - 1;
@@ -709,7 +713,7 @@ int attention_bf16_head_dim() { return kDh; }
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
   if (a.T == 0 || a.S == 0 || a.n_heads == 0) return hipSuccess;
   if (a.bf16) {
-    const dim3 grid((a.T + kBQ - 1) / kBQ + a.S, a.n_heads);
+    const dim3 grid(((a.T + kBQ - 1) / kBQ + a.S) * a.n_heads);
     k_attention_bf16<<<grid, kAttnWaves * kWave, 0, st>>>(a);
   } else {
     const dim3 grid(a.T, a.n_heads);
