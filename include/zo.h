@@ -30,8 +30,8 @@
  *   - Every function returns a zo_status.  All argument validation happens
  *     before the first HIP call, so error paths can be exercised on a machine
  *     without a GPU.  zo_last_error() returns a thread-local message.
- *   - Results are deterministic: no atomics, fixed reduction orders, tile
- *     shapes that do not depend on the batch.  A row's result does not depend
+ *   - Results are deterministic: no atomics, and reduction orders that are
+ *     fixed and do not depend on the batch.  A row's result does not depend
  *     on which other rows share the batch.
  */
 #ifndef ZO_H_

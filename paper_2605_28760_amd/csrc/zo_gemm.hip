@@ -22,9 +22,11 @@
 // block of output tiles in that XCD's L2, and the eight XCDs work on
 // neighbouring blocks that share their weight rows.
 //
-// Determinism / batch invariance: the tile shape and the K order never depend
-// on the batch, there is no split-K and no atomic, so a token's result depends
-// only on that token's operands.
+// Determinism / batch invariance: the K order of an output element never
+// depends on the batch (a tile may be computed whole or as two halves of 128
+// weight rows, which changes which wave holds an element, not its arithmetic),
+// there is no split-K and no atomic, so a token's result depends only on that
+// token's operands.
 #include <type_traits>
 
 #include "zo_device.hpp"
