@@ -58,14 +58,23 @@ typedef u32x2 __attribute__((may_alias)) u32x2_alias;   // LDS staging is writte
 typedef u32x4 __attribute__((may_alias)) u32x4_alias;
 typedef f32x4 Acc[RB][CB];
 
-// Position L of the grouped raster -> output tile (tm = weight-row tile, tn = token tile).
-__device__ __forceinline__ void tile_at(int L, int n_tm, int n_tn, int& tm, int& tn) {
-  const int per_group = kGroupM * n_tn;
-  const int g = L / per_group, in_g = L - g * per_group;
+// Position L of the grouped raster -> output tile (tm = weight-row tile, tn = token tile).  The token tiles
+// are taken in super-blocks of tn_super tiles (the last one holds the rest; tn_super >= n_tn: one block):
+// the grouped raster sweeps the token tiles of a block once per group of weight-row tiles, so the block's
+// rows of the token operand are re-read once per group, and a block is sized to stay in the Infinity Cache
+// between two sweeps.
+__device__ __forceinline__ void tile_at(int L, int n_tm, int n_tn, int tn_super, int& tm, int& tn) {
+  const int per_super = n_tm * tn_super;
+  const int sb = L / per_super;
+  const int tn0 = sb * tn_super;
+  const int nt = min(tn_super, n_tn - tn0);
+  const int in_sb = L - sb * per_super;
+  const int per_group = kGroupM * nt;
+  const int g = in_sb / per_group, in_g = in_sb - g * per_group;
   const int first_m = g * kGroupM;
   const int gsize = min(n_tm - first_m, kGroupM);
   tm = first_m + in_g % gsize;
-  tn = in_g / gsize;
+  tn = tn0 + in_g / gsize;
 }
 
 // A copy of x the optimiser cannot see through.  Per-tile code derives its lane-dependent
@@ -148,7 +157,7 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
 template <bool kGather, bool kSplit, class Pre, class Post>
 __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
-                                                int n_tm, int n_tn, int n_split, char* lds, Pre pre, Post post,
+                                                int n_tm, int n_tn, int tn_super, int n_split, char* lds, Pre pre, Post post,
                                                 const int32_t* __restrict__ b_rows = nullptr, int B_rows_total = 0) {
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -185,7 +194,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
       half = (I - first_split) & 1;
     }
     int tm, tn;
-    tile_at(pos, n_tm, n_tn, tm, tn);
+    tile_at(pos, n_tm, n_tn, tn_super, tm, tn);
     m0 = tm * BM + half * (BM / 2);
     n0 = tn * BN;
     return is_half;
@@ -357,6 +366,16 @@ static int split_tiles(int total_tiles, int m) {
   return rem;
 }
 
+// Token tiles per super-block of the raster.  Every group of 8 weight-row tiles sweeps all token tiles of a
+// block; a token operand beyond what the 256 MB Infinity Cache keeps between two sweeps is cut into blocks
+// of at most 128 MB of rows (a multiple of the 4 token tiles of an XCD's block).  The weight matrix is then
+// streamed once per block instead of once.
+static int token_super_block(int n_tn, int64_t token_operand_bytes) {
+  if (token_operand_bytes <= (192ll << 20)) return n_tn;
+  const int n_super = (int)((token_operand_bytes + (128ll << 20) - 1) / (128ll << 20));
+  return ((n_tn + n_super - 1) / n_super + 3) / 4 * 4;
+}
+
 static int gemm_grid(int total_tiles) {
   const int cus = compute_units();
   const int per_xcd = (total_tiles + kXcds - 1) / kXcds;
@@ -383,7 +402,7 @@ __device__ __forceinline__ float silu_mul(float gate, float up) { return gate / 
 // kSplit: the variant whose last round is made of half tiles (n_split > 0); the launcher takes it only when
 // the tile count leaves such a round, so every other shape runs the loop without the extra branches.
 template <bool kSide, bool kOutBf16, bool kBias, bool kGate, bool kSplit>
-__global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn, int n_split) {
+__global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int n_tm, int n_tn, int tn_super, int n_split) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -559,11 +578,12 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
     }
   };
 
-  persistent_gemm<false, kSplit>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, n_split, lds, side_phase, epilogue);
+  persistent_gemm<false, kSplit>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, tn_super, n_split, lds, side_phase, epilogue);
 }
 
 template <bool kSide, bool kOutBf16, bool kBias, bool kGate, bool kSplit>
 static hipError_t launch_probe_kernel(const ProbeGemmArgs& a, int n_tm, int n_tn, int n_split, hipStream_t st) {
+  const int tn_super = token_super_block(n_tn, (int64_t)a.T * a.n * 2);
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>,
@@ -572,7 +592,7 @@ static hipError_t launch_probe_kernel(const ProbeGemmArgs& a, int n_tm, int n_tn
     configured = true;
   }
   hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>), dim3(gemm_grid(n_tm * n_tn + n_split)),
-                     dim3(kThreads), kGemmLds, st, a, n_tm, n_tn, n_split);
+                     dim3(kThreads), kGemmLds, st, a, n_tm, n_tn, tn_super, n_split);
   return hipGetLastError();
 }
 
@@ -609,7 +629,7 @@ int head_vocab_tiles_bf16(int vocab) { return (vocab + BM - 1) / BM; }
 // kGather: only the scored tokens (rows p.rows[0 .. *p.n_rows - 1] of H) are multiplied; token tiles
 // and the partial outputs then run over positions in that list.
 template <bool kGather>
-__global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int n_tm) {
+__global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int n_tm, int tn_super) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int n_tok = kGather ? __builtin_amdgcn_readfirstlane(*p.n_rows) : p.T;   // tokens to score
   if (n_tok == 0) return;
@@ -686,7 +706,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
     block_barrier();   // the exchange buffers are free again for the next tile
   };
 
-  persistent_gemm<kGather, false>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, 0, lds, no_side, epilogue, p.rows, p.T);
+  persistent_gemm<kGather, false>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, tn_super, 0, lds, no_side, epilogue, p.rows, p.T);
 }
 
 template <bool kGather>
@@ -699,7 +719,8 @@ static hipError_t launch_head_variant(const HeadScoreArgs& a, hipStream_t st) {
   }
   // the grid is sized for every token being scored; with fewer, the surplus workgroups find no tile
   const int n_tm = (a.vocab + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
-  hipLaunchKernelGGL(k_head_score<kGather>, dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds, st, a, n_tm);
+  const int tn_super = token_super_block(n_tn, (int64_t)a.T * a.d * 2);
+  hipLaunchKernelGGL(k_head_score<kGather>, dim3(gemm_grid(n_tm * n_tn)), dim3(kThreads), kGemmLds, st, a, n_tm, tn_super);
   return hipGetLastError();
 }
 
