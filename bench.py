@@ -25,9 +25,9 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # Bytes per launch of the dominant kernel that crossed the L2 <-> fabric boundary, from the rocprofv3
-# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/hbm_bytes_bench_c3.txt (FETCH_SIZE scaled by
+# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/hbm_bytes_bench_c3.txt and _c4_c5.txt (FETCH_SIZE scaled by
 # the factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"c3": 1.241e10}
+MEASURED_TRAFFIC_BYTES = {"c3": 1.241e10, "c4": 3.778e10, "c5": 6.704e10}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):
