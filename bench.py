@@ -3,11 +3,13 @@
 One "step" is one pass of the whole path over one synthetic batch that is
 already resident in HBM: probe linears (factor generation, side-down
 projection, MFMA GEMM with side state), fused LM-head scoring, two-point
-estimate and lazy bank update.  The default workload is the OPT-13B-shaped
-scoring chain at batch 64 (64 sequences x 128 tokens x {+,-}, r = 8, bank
-rank 64, vocabulary 50272): the configuration of the paper's headline 98.2 %
-query-share figure and the one on which "candidate-tokens scored/sec (probe
-linear + LM-head scoring)" is defined.
+estimate and lazy bank update.  The headline workload is the largest of the
+chain configurations that fit one GPU: the mixed foreground + probe batch on
+Qwen3-8B shapes (64 sequences of 64-1024 rows, 24 directions x {+,-} of rank
+16, 16 foreground sequences, bank rank 128, vocabulary 151936).  The other
+two chain configurations (the OPT-13B-shaped scoring chain at batch 64 and
+the ragged Qwen3-shaped batch) are timed in the same run and reported as
+nested sections, as are the six OPT-13B-shaped linears at 8192 rows.
 
 Prints ONE JSON line.
 """
@@ -25,9 +27,12 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # Bytes per launch of the dominant kernel that crossed the L2 <-> fabric boundary, from the rocprofv3
-# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in profiles/hbm_bytes_bench_c3.txt and _c4_c5.txt (FETCH_SIZE scaled by
-# the factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {"c3": 1.241e10, "c4": 3.778e10, "c5": 6.704e10}
+# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in the named files under profiles/ (FETCH_SIZE scaled by the
+# factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  They are figures of those profile
+# runs, not of this run: the line names their source next to them.
+MEASURED_TRAFFIC = {"c3": (1.241e10, "profiles/hbm_bytes_bench_c3.txt"),
+                    "c4": (3.778e10, "profiles/hbm_bytes_bench_c4_c5.txt"),
+                    "c5": (6.704e10, "profiles/hbm_bytes_bench_c4_c5.txt")}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):
@@ -152,33 +157,18 @@ def _layer_set_section(n_rep):
             "candidate_tokens_per_s_through_the_six": w.T / (total_ms * 1e-3)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c3", "c4", "c5"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-block", action="store_true", help="skip the decoder-block secondary measurement")
-    ap.add_argument("--no-layer-set", action="store_true",
-                    help="skip the secondary measurement of the six OPT-13B-shaped linears at 8192 rows")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by sequences, one replica per GPU); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
-
+def _chain(name, steps, warmup, full, block, cpu_baseline):
+    """Times one chain workload: `warmup` untimed steps, then `steps` steps bracketed by device
+    synchronisation, with per-call HIP events on the launch stream.  `full` adds the secondary
+    measurements (plain forward, active-token scoring, loop, 40-layer update, decoder block)."""
     import numpy as np
     import torch
     from paper_2605_28760_amd import binding as zb
     from paper_2605_28760_amd import workloads as wl
-    from paper_2605_28760_amd.runner import DeviceWorkload
+    from paper_2605_28760_amd.runner import DeviceBatch, DeviceWorkload, LoopDriver
 
-    zb.lib()   # fails loudly if the HIP library is missing
     t_gen = time.perf_counter()
-    w = wl.BUILDERS[args.workload]()
+    w = wl.BUILDERS[name]()
     d = DeviceWorkload(w, "cuda:0")
     torch.cuda.synchronize()
     gen_s = time.perf_counter() - t_gen
@@ -208,27 +198,61 @@ def main():
                 d.bank_update(i, 1e-7, col0, 0, stream=stream)
         mark(n_layers + 3)
 
-    if args.calibrate_copy:
-        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     n_marks = n_layers + 4
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n_marks)] for _ in range(args.steps)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(n_marks)] for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for k in range(args.steps):
+    for k in range(steps):
         step(ev[k])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    # Secondary, outside the timed region: the same forward with every sequence foreground
-    # (candidate id -1: plain base GEMMs and plain scoring), for the probe / plain ratio.
-    from paper_2605_28760_amd.runner import DeviceBatch
+    seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(steps)])
+    breakdown = {n: float(v) for n, v in zip(names, np.median(seg, axis=0))}   # median over the timed steps
+    ms_per_step = elapsed / steps * 1e3
+    cand_rows = int(sum(int(w.cu_seqlens[s_ + 1] - w.cu_seqlens[s_]) for s_ in range(len(w.seq_cand)) if w.seq_cand[s_] >= 0))
+
+    # dominant kernel: the fused head GEMM + log-sum-exp (zo_score; its merge kernels are < 1 % of it)
+    head_flops = 2.0 * T * hid * vocab
+    head_ms = breakdown["score"]
+    achieved = head_flops / (head_ms * 1e-3) / 1e12
+    traffic, traffic_source = MEASURED_TRAFFIC.get(name, (None, None))
+    roofline = {"kernel": "k_head_score (zo_score)", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                "traffic_source": traffic_source, "avg_ms": head_ms}
+    layer_flops = {l.name: 2.0 * T * l.m * l.n for l in d.layers}
+    calls = {n: {"ms": breakdown[n], "tflops": layer_flops[n] / (breakdown[n] * 1e-3) / 1e12,
+                 "frac_mfma_peak": layer_flops[n] / (breakdown[n] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+             for n in layer_flops}
+    total_flops = head_flops + sum(layer_flops.values())
+    probe_ms = sum(breakdown[n] for n in layer_flops)
+    out = {
+        "value": T * steps / elapsed, "ms_per_step": ms_per_step,
+        "config": {"workload": w.name, "rows": T, "sequences": int(len(w.seq_cand)), "candidates": int(len(w.cand_dir)),
+                   "directions": int(len(w.dir_seed)), "r": w.r, "eps": w.eps,
+                   "layers": [[l.name, l.m, l.n] for l in w.layers], "bank_rank": int(w.layers[0].R_used),
+                   "vocab": int(vocab), "hidden": int(hid)},
+        "roofline": roofline,
+        # rows of sequences that carry a candidate (all rows unless the batch mixes in foreground sequences)
+        "candidate_rows": cand_rows, "candidate_rows_per_s": cand_rows * steps / elapsed,
+        "chain_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
+        "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "breakdown_ms": breakdown, "breakdown_stat": "median over the timed steps",
+        "probe_linear_calls": calls,
+        "probe_linears_frac_mfma_peak": sum(layer_flops.values()) / (probe_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "input_setup_s": gen_s,
+        # bytes the update step moves (P read + write per layer) against rewriting the dense weights
+        # once per candidate state and restoring them (4 x read + write of every probed W)
+        "state_transition_bytes": {
+            "bank_update": int(sum(2 * l.m * w.r * 4 * n_upd for l in w.layers)),
+            "dense_rewrite": int(sum(4 * 2 * l.m * l.n * 2 for l in w.layers))},
+    }
+
+    # The same forward with every sequence foreground (candidate id -1: plain base GEMMs and plain scoring),
+    # for the probe / plain ratio; outside the timed region.
     fg = DeviceBatch(w.cu_seqlens, np.full_like(w.seq_cand, -1), w.cand_dir, w.cand_sign, w.dir_seed, "cuda:0")
 
     def forward(batch):
@@ -236,73 +260,50 @@ def main():
             d.probe_linear(i, stream=stream, batch=batch)
         d.score(stream=stream, batch=batch)
 
-    def time_forward(batch, n):
-        forward(batch)
+    def timed(fn, n):
+        fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
         for _ in range(n):
-            forward(batch)
+            fn()
         e1.record(stream)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
-    n_sec = max(3, min(10, args.steps))
-    plain_ms = time_forward(fg, n_sec)
-    probe_ms = time_forward(None, n_sec)
+    n_sec = max(3, min(10, steps))
+    plain_ms = timed(lambda: forward(fg), n_sec)
+    probe_fwd_ms = timed(lambda: forward(None), n_sec)
+    # the probe linears alone, with the candidates and all foreground: what the side state costs them
+    def linears(batch):
+        for i in range(n_layers):
+            d.probe_linear(i, stream=stream, batch=batch)
+    lin_plain_ms = timed(lambda: linears(fg), n_sec)
+    lin_probe_ms = timed(lambda: linears(None), n_sec)
+    out["probe_over_plain"] = {"probe_ms": probe_fwd_ms, "plain_ms": plain_ms, "ratio": probe_fwd_ms / plain_ms,
+                               "linears_probe_ms": lin_probe_ms, "linears_plain_ms": lin_plain_ms,
+                               "linears_ratio": lin_probe_ms / lin_plain_ms}
+    # whole step over the same forward with every sequence foreground: the analogue of the paper's
+    # native / matched-inference ratio
+    out["native_over_matched"] = ms_per_step / plain_ms
+    if not full:
+        del d
+        torch.cuda.empty_cache()
+        return out, w
 
-    # Secondary: scoring when only the last 16 tokens of every sequence carry a target (answer tokens):
-    # the head multiplies only those rows.
-    def time_score(n):
-        d.score(stream=stream)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(n):
-            d.score(stream=stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+    # Scoring when only the last 16 tokens of every sequence carry a target (answer tokens): the head
+    # multiplies only those rows.
     all_targets = d.targets.clone()
     tail = np.full(T, -1, np.int32)
     for s_ in range(len(w.seq_cand)):
         lo = max(int(w.cu_seqlens[s_]), int(w.cu_seqlens[s_ + 1]) - 16)
         tail[lo:w.cu_seqlens[s_ + 1]] = w.targets[lo:w.cu_seqlens[s_ + 1]]
     d.targets.copy_(torch.from_numpy(tail))
-    active_ms = time_score(n_sec)
+    active_ms = timed(lambda: d.score(stream=stream), n_sec)
     d.targets.copy_(all_targets)
     torch.cuda.synchronize()
+    out["active_token_scoring"] = {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms}
 
-    # Secondary: the multi-step loop (device-resident seed / bank-block schedule + the whole step), eager
-    # launches against replays of one captured HIP graph.  Run last: it zeroes the banks.
-    from paper_2605_28760_amd.runner import LoopDriver
-    loop_info = None
-    n_blocks = int(w.layers[0].R_used) // (w.r * d.batch.K) if w.layers[0].P is not None else 0
-    if n_blocks >= 1:
-        loop = LoopDriver(d, nu=4, n_blocks=n_blocks, lr=1e-10, base_u=1, base_v=2)   # small enough for the losses to stay put
-
-        def time_loop(fn, n):
-            loop.reset()
-            fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(n):
-                fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / n
-        eager_ms = time_loop(lambda: loop.step(stream=stream), n_sec)
-        loop.capture()
-        graph_ms = time_loop(loop.replay, n_sec)
-        # fold the (tiny) accumulated bank into the base weights: the price of going past nu * n_blocks steps
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        loop.fold(stream=stream)
-        e0.record(stream)
-        loop.fold(stream=stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
-                     "fold_all_layers_ms": e0.elapsed_time(e1)}
-
-    # Secondary: the lazy update of 40 layers (20 copies of this workload's two layer shapes, one rank-r
-    # block per direction, accumulate mode) as one multi-layer call against 40 single-layer calls.
+    # The lazy update of 40 layers (20 copies of this workload's two layer shapes, one rank-r block per
+    # direction, accumulate mode) as one multi-layer call against 40 single-layer calls.
     def bank_update_40():
         shapes = [(l.m, l.n) for l in w.layers] * 20
         R_cap = int(w.layers[0].R_used)
@@ -319,84 +320,97 @@ def main():
             for i, (m, n) in enumerate(shapes):
                 zb.zo_bank_update(banks[i], m, n, w.r, n_upd, d.batch.dir_seed, 2 * i, d.proj_grad, 1e-7, None, col0, 0,
                                   dt, stream)
-
-        def timed(fn):
-            fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(n_sec):
-                fn()
-            e1.record(stream)
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / n_sec
         nbytes = sum(2 * m * w.r * 4 * n_upd for m, _ in shapes)
-        t_multi, t_single = timed(multi), timed(single)
+        t_multi, t_single = timed(multi, n_sec), timed(single, n_sec)
         return {"layers": len(shapes), "bytes": int(nbytes), "multi_ms": t_multi, "per_layer_calls_ms": t_single,
-                "multi_gbs": nbytes / (t_multi * 1e-3) / 1e9}
-    bank40 = bank_update_40() if n_upd > 0 else None
+                "multi_gbs": nbytes / (t_multi * 1e-3) / 1e9, "frac_hbm_peak": nbytes / (t_multi * 1e-3) / 1e9 / PEAK_HBM_GBS}
+    out["bank_update_40_layers"] = bank_update_40() if n_upd > 0 else None
 
-    block_info = None
-    if not args.no_block:
-        block_info = _block_section({"c3": "b3"}.get(args.workload, "b4"), n_sec)
+    # The multi-step loop (device-resident seed / bank-block schedule + the whole step), eager launches
+    # against replays of one captured HIP graph.  Run last: it zeroes the banks.
+    loop_info = None
+    n_blocks = int(w.layers[0].R_used) // (w.r * d.batch.K) if w.layers[0].P is not None else 0
+    if n_blocks >= 1:
+        loop = LoopDriver(d, nu=4, n_blocks=n_blocks, lr=1e-10, base_u=1, base_v=2)   # small enough for the losses to stay put
 
-    layer_set_info = None
-    if args.workload == "c3" and not args.no_layer_set:
-        layer_set_info = _layer_set_section(n_sec)
+        def time_loop(fn, n):
+            loop.reset()
+            return timed(fn, n)
+        eager_ms = time_loop(lambda: loop.step(stream=stream), n_sec)
+        loop.capture()
+        graph_ms = time_loop(loop.replay, n_sec)
+        # fold the (tiny) accumulated bank into the base weights: the price of going past nu * n_blocks steps
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        loop.fold(stream=stream)
+        e0.record(stream)
+        loop.fold(stream=stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        loop_info = {"nu": 4, "n_blocks": n_blocks, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
+                     "fold_all_layers_ms": e0.elapsed_time(e1)}
+    out["loop"] = loop_info
+    del d
+    torch.cuda.empty_cache()
+    out["block"] = _block_section({"c3": "b3"}.get(name, "b4"), n_sec) if block else None
+    if cpu_baseline:
+        out["cpu_baseline"], _, _ = _cpu_baseline(w)
+    return out, w
 
-    seg = np.array([[ev[k][i].elapsed_time(ev[k][i + 1]) for i in range(n_marks - 1)] for k in range(args.steps)])
-    seg_ms = seg.mean(axis=0)
-    breakdown = {n: float(v) for n, v in zip(names, seg_ms)}
-    ms_per_step = elapsed / args.steps * 1e3
-    value = T * args.steps / elapsed
-    cand_rows = int(sum(int(w.cu_seqlens[s_ + 1] - w.cu_seqlens[s_]) for s_ in range(len(w.seq_cand)) if w.seq_cand[s_] >= 0))
 
-    # dominant kernel: the fused head GEMM + log-sum-exp (zo_score; its three merge kernels are < 1 % of it)
-    head_flops = 2.0 * T * hid * vocab
-    head_ms = breakdown["score"]
-    achieved = head_flops / (head_ms * 1e-3) / 1e12
-    roofline = {"kernel": "k_head_score (zo_score)", "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "avg_ms": head_ms}
-    layer_flops = {l.name: 2.0 * T * l.m * l.n for l in d.layers}
-    calls = {n: {"ms": breakdown[n], "tflops": layer_flops[n] / (breakdown[n] * 1e-3) / 1e12,
-                 "frac_mfma_peak": layer_flops[n] / (breakdown[n] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
-             for n in layer_flops}
-    total_flops = head_flops + sum(layer_flops.values())
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c5", choices=["c3", "c4", "c5"],
+                    help="the workload of the headline line (default: the largest chain configuration)")
+    ap.add_argument("--nested", default="c3,c4",
+                    help="comma-separated chain workloads also timed and reported as nested sections ('' for none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-block", action="store_true", help="skip the decoder-block secondary measurement")
+    ap.add_argument("--no-layer-set", action="store_true",
+                    help="skip the secondary measurement of the six OPT-13B-shaped linears at 8192 rows")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by sequences, one replica per GPU); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_28760_amd import binding as zb
+
+    zb.lib()   # fails loudly if the HIP library is missing
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    main_res, _ = _chain(args.workload, args.steps, args.warmup, True, not args.no_block, not args.no_cpu_baseline)
+    nested = {}
+    for nm in [x for x in args.nested.split(",") if x and x != args.workload]:
+        n_steps = max(5, min(args.steps, 30))
+        res, _ = _chain(nm, n_steps, min(args.warmup, 5), False, False, False)
+        res["steps"], res["warmup"] = n_steps, min(args.warmup, 5)
+        nested[nm] = res
+    layer_set_info = None if args.no_layer_set else _layer_set_section(max(3, min(10, args.steps)))
 
     result = {
         "metric": "candidate-tokens scored/sec (probe linear + LM-head scoring)",
-        "value": value, "unit": "candidate-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "rows": T, "sequences": int(len(w.seq_cand)), "candidates": int(len(w.cand_dir)),
-                   "directions": int(len(w.dir_seed)), "r": w.r, "eps": w.eps,
-                   "layers": [[l.name, l.m, l.n] for l in w.layers], "bank_rank": int(w.layers[0].R_used),
-                   "vocab": int(vocab), "hidden": int(hid)},
-        "roofline": roofline,
-        # rows of sequences that carry a candidate (all rows unless the batch mixes in foreground sequences)
-        "candidate_rows": cand_rows, "candidate_rows_per_s": cand_rows * args.steps / elapsed,
-        "chain_tflops": total_flops / (ms_per_step * 1e-3) / 1e12,
-        "chain_frac_mfma_peak": total_flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "breakdown_ms": breakdown, "probe_linear_calls": calls, "input_setup_s": gen_s,
-        # forward (probe linears + scoring) with candidates / the same rows all foreground
-        # whole step over the same forward with every sequence foreground: the analogue of the paper's
-        # native / matched-inference ratio
-        "native_over_matched": ms_per_step / plain_ms,
-        "loop": loop_info,
-        "block": block_info,
-        "layer_set": layer_set_info,
-        "bank_update_40_layers": bank40,
-        "active_token_scoring": {"scored_rows": int((tail >= 0).sum()), "rows": T, "score_ms": active_ms},
-        "probe_over_plain": {"probe_ms": probe_ms, "plain_ms": plain_ms, "ratio": probe_ms / plain_ms},
-        # bytes the update step moves (P read + write per layer) against rewriting the dense weights
-        # once per candidate state and restoring them (4 x read + write of every probed W)
-        "state_transition_bytes": {
-            "bank_update": int(sum(2 * l.m * w.r * 4 * n_upd for l in w.layers)),
-            "dense_rewrite": int(sum(4 * 2 * l.m * l.n * 2 for l in w.layers))},
+        "value": main_res.pop("value"), "unit": "candidate-tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": main_res.pop("ms_per_step"), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": main_res.pop("config"), "roofline": main_res.pop("roofline"),
     }
-    if not args.no_cpu_baseline:
-        base, _, _ = _cpu_baseline(w)
-        result["cpu_baseline"] = base
+    cpu = main_res.pop("cpu_baseline", None)
+    result.update(main_res)
+    result["nested_workloads"] = nested
+    result["layer_set"] = layer_set_info
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     print(json.dumps(result))
 
 

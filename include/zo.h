@@ -14,7 +14,7 @@
  * a 64-bit seed by a counter-based generator (Philox4x32-10 + Box-Muller) and
  * are never passed across this boundary.  Foreground sequences (candidate id
  * -1) see W_0 alone and their results are bit-identical to a call in which
- * every sequence is foreground (Sec. 4, mixed-batch experiment).
+ * every sequence is foreground (Sec. 5.4 and the mixed-batch correctness appendix).
  *
  * Conventions
  *   - A linear layer has W [m x n] row-major (m = out features, n = in
@@ -219,7 +219,7 @@ int32_t zo_estimate(const zo_batch* batch, const float* cand_sum, const int32_t*
                     void* stream);
 
 /*
- * Reward-normalised one-sided estimate (Sec. 4: N candidate evaluations around
+ * Reward-normalised one-sided estimate (Sec. 2.2, Sec. 5.3 and the taxonomy appendix: N candidate evaluations around
  * one centre, reward normalisation, reward-weighted update; the evolution-
  * strategies shape).  Direction k is represented by its lowest-numbered
  * candidate with positive sign, reward R_k = -cand_loss of that candidate;
@@ -256,7 +256,7 @@ int32_t zo_bank_update(zo_bank* bank, int32_t m, int32_t n, int32_t r, int32_t n
                        void* stream);
 
 /*
- * The same lazy update for many layers in one call (Sec. 4 counts the update of the
+ * The same lazy update for many layers in one call (Sec. 5.2, the state-transition traffic table, counts the update of the
  * whole model as one state transition of 26 MB): every layer gets beta_k U_k of its
  * own tensor id in the same column blocks host_col0[k] (and, with append, V_k).  One
  * layer's update moves 2 * m * r * 4 bytes, a few hundred KB at the paper's sizes, so

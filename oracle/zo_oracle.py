@@ -11,7 +11,7 @@ What the path computes, by definition:
     (Sec. 3.2: the +-eps U V^T candidates, the combined probe, and the bank
     W_eff = W_0 + sum_k P_k V_k^T);  a centre candidate (s = 0 or k = -1) sees
     W_0 + P Vb^T;  a foreground sequence (candidate id -1) sees W_0 alone
-    (Sec. 4 and the mixed-batch experiment: foreground requests observe the
+    (Sec. 5.4 and the mixed-batch correctness appendix: foreground requests observe the
     immutable base);
   * every token row is multiplied by its candidate's dense weight, scored
     against an LM head by the ordinary negative log-likelihood, the scores
@@ -238,7 +238,7 @@ def estimate(batch: Batch, cand_sum, cand_cnt, eps, reduction=0):
 
 def estimate_es(batch: Batch, cand_sum, cand_cnt, eps, reduction=0):
     """Reward-normalised one-sided estimate (the evolution-strategies shape of
-    Sec. 4 and the taxonomy table: N candidate evaluations around one centre,
+    Sec. 2.2, Sec. 5.3 and the taxonomy appendix: N candidate evaluations around one centre,
     reward normalisation, a reward-weighted perturbation update).
 
     Direction k is represented by its lowest-numbered candidate with positive

@@ -89,27 +89,14 @@ zo::BatchDev to_dev(const zo_batch* b) {
 
 // ---- workspace plans --------------------------------------------------------------------
 struct ProbePlan {
-  int RP = 0, Rp = 0, max_items = 0, ks_cap = 1;
+  int RP = 0, Rp = 0, max_items = 0, ksplit = 1;
+  int SPD = 0, RpT = 0, n_tn = 0, slot_cap = 0, kt_cap = 0, m_img = 0;   // side K tiles of the bf16 GEMM
+  size_t uimg_bytes = 0, pimg_bytes = 0, xs_bytes = 0;
   size_t seq_kind, seq_scale, tok_seq, n_items, items;
-  size_t Uh, Vt, Ph, Vbt, Aside, partial;   // bf16 path
-  size_t Uf, Vf, Tside;                      // fp32 path
+  size_t tile_hdr, tile_slots, kt_tile, Uimg, Vt, Pimg, Vbt, Xs, partial;   // bf16 path
+  size_t Uf, Vf, Tside;                                                     // fp32 path
   size_t total = 0;
 };
-
-// Rows reserved for the k-split partial sums of the side-down pass: a bound that only grows with T, so
-// a workspace sized for a large batch also serves every smaller one.
-size_t side_partial_rows(int T) { return (size_t)T * 16 < 262144 ? (size_t)T * 16 : 262144; }
-
-// Upper bound of the side-down k-split (the device picks the split once it knows the work items):
-// at most 16, k ranges of at least 512 columns, and split * T rows of partial sums must fit.
-int side_ks_cap(int T, int n) {
-  if (T <= 0) return 1;
-  int cap = n / 512;
-  if (cap > 16) cap = 16;
-  const int fit = (int)(side_partial_rows(T) / (size_t)T);
-  if (cap > fit) cap = fit;
-  return cap < 1 ? 1 : cap;
-}
 
 ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype dt) {
   ProbePlan p;
@@ -124,14 +111,32 @@ ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype d
     p.RP = round16(r);
     p.Rp = round16(R);
     const size_t NC = (size_t)p.RP + p.Rp;
-    p.ks_cap = side_ks_cap(T, n);
-    p.Uh = c.take((size_t)K * m * p.RP * 2);
+    p.ksplit = zo::side_ksplit(n);
+    // Side K tiles.  A token tile's slot list holds one entry per distinct direction among the sequences
+    // that intersect it (times the 32-column blocks of a direction): over all tiles at most tiles +
+    // sequences, and at most min(K, 256) per tile.  A K tile holds two slots; a tile with candidates
+    // also has the bank's K tiles.
+    p.SPD = (r + 31) / 32;
+    p.RpT = (R + zo::kTileK - 1) / zo::kTileK;
+    p.n_tn = (T + zo::kTileN - 1) / zo::kTileN;
+    const int64_t per_tile = K < zo::kTileN ? K : zo::kTileN;
+    int64_t dirs = (int64_t)p.n_tn + S;
+    if (dirs > (int64_t)p.n_tn * per_tile) dirs = (int64_t)p.n_tn * per_tile;
+    p.slot_cap = (int)(dirs * p.SPD);
+    p.kt_cap = (p.slot_cap + p.n_tn + 1) / 2 + p.n_tn * p.RpT;
+    p.m_img = (m + zo::kTileM - 1) / zo::kTileM * zo::kTileM + zo::kTileM / 2;   // a half tile may start 128 rows down
+    p.uimg_bytes = (size_t)K * p.SPD * p.m_img * 64;
+    p.pimg_bytes = (size_t)p.RpT * p.m_img * 128;
+    p.xs_bytes = (size_t)p.kt_cap * zo::kTileN * zo::kTileK * 2;
+    p.tile_hdr = c.take((size_t)p.n_tn * sizeof(zo::TileHdr));
+    p.tile_slots = c.take((size_t)p.slot_cap * 4);
+    p.kt_tile = c.take((size_t)p.kt_cap * 4);
+    p.Uimg = c.take(p.uimg_bytes);
     p.Vt = c.take((size_t)K * p.RP * n * 2);
-    p.Ph = c.take((size_t)m * p.Rp * 2);
+    p.Pimg = c.take(p.pimg_bytes);
     p.Vbt = c.take((size_t)p.Rp * n * 2);
-    p.Aside = c.take((size_t)T * NC * 2);
-    const size_t partial_rows = side_partial_rows(T);
-    p.partial = c.take(partial_rows * NC * 4);
+    p.Xs = c.take(p.xs_bytes);
+    p.partial = c.take((size_t)p.ksplit * T * NC * 4);
   } else {
     p.Uf = c.take((size_t)K * m * r * 4);
     p.Vf = c.take((size_t)K * n * r * 4);
@@ -269,35 +274,48 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   tabs.items = (zo::SideItem*)(ws + plan.items);
   tabs.n_items = (int32_t*)(ws + plan.n_items);
   tabs.max_items = plan.max_items;
-  tabs.side_slots = 2 * zo::compute_units();   // the side-down pass keeps two workgroups per CU
-  tabs.side_ks_cap = plan.ks_cap;
+  tabs.tile_hdr = nullptr; tabs.tile_slots = nullptr; tabs.kt_tile = nullptr;
+  tabs.n_tn = plan.n_tn; tabs.slot_cap = plan.slot_cap; tabs.kt_cap = plan.kt_cap; tabs.SPD = plan.SPD; tabs.RpT = plan.RpT;
   // a batch without candidates (or probes and bank both absent) is a plain GEMM
   const bool has_side = batch->n_cands > 0;
   if (has_side && in_dtype != ZO_BF16) ZO_HIP(zo::launch_seq_tables(bd, eps, tabs, st), "batch tables");
 
   if (in_dtype == ZO_BF16) {
-    uint16_t* Uh = (uint16_t*)(ws + plan.Uh);
+    uint16_t* Uimg = (uint16_t*)(ws + plan.Uimg);
     uint16_t* Vt = (uint16_t*)(ws + plan.Vt);
-    uint16_t* Ph = (uint16_t*)(ws + plan.Ph);
+    uint16_t* Pimg = (uint16_t*)(ws + plan.Pimg);
     uint16_t* Vbt = (uint16_t*)(ws + plan.Vbt);
-    uint16_t* Aside = (uint16_t*)(ws + plan.Aside);
+    uint16_t* Xs = (uint16_t*)(ws + plan.Xs);
     if (has_side) {
+      // the GEMM addresses each image through one buffer window with 31-bit offsets
+      const size_t window = (size_t)0x7FFFFFFF;
+      if (plan.uimg_bytes > window || plan.pimg_bytes > window || plan.xs_bytes > window)
+        return fail(ZO_ERR_UNSUPPORTED, "side-state images of %zu / %zu / %zu bytes exceed the 2 GiB addressing window "
+                    "(directions x rank x output features, bank rank x output features, tokens x side columns)",
+                    plan.uimg_bytes, plan.pimg_bytes, plan.xs_bytes);
+      tabs.tile_hdr = (zo::TileHdr*)(ws + plan.tile_hdr);
+      tabs.tile_slots = (int32_t*)(ws + plan.tile_slots);
+      tabs.kt_tile = (int32_t*)(ws + plan.kt_tile);
       ZO_HIP(zo::launch_probe_prep_bf16(bd, eps, tabs, tensor_id, m, n, r, plan.RP, plan.Rp, R > 0 ? bank->P : nullptr,
-                                        R > 0 ? bank->Vb : nullptr, R > 0 ? bank->R_cap : 0, R, Uh, Vt, Ph, Vbt, st),
+                                        R > 0 ? bank->Vb : nullptr, R > 0 ? bank->R_cap : 0, R, plan.m_img, Uimg, Vt, Pimg,
+                                        Vbt, st),
              "probe preparation");
       zo::SideDownArgs sd;
       sd.X = (const uint16_t*)X; sd.ldx = ldx; sd.Vt = Vt; sd.Vbt = Vbt;
       sd.n = n; sd.RP = plan.RP; sd.Rp = plan.Rp; sd.T = T;
       sd.items = tabs.items; sd.n_items = tabs.n_items; sd.max_items = plan.max_items;
-      sd.ks_cap = plan.ks_cap; sd.partial = (float*)(ws + plan.partial); sd.Aside = Aside;
+      sd.ksplit = plan.ksplit; sd.partial = (float*)(ws + plan.partial);
       sd.tok_seq = tabs.tok_seq; sd.seq_kind = tabs.seq_kind; sd.seq_scale = tabs.seq_scale;
+      sd.tile_hdr = tabs.tile_hdr; sd.tile_slots = tabs.tile_slots; sd.kt_tile = tabs.kt_tile;
+      sd.kt_cap = plan.kt_cap; sd.SPD = plan.SPD; sd.Xs = Xs;
       ZO_HIP(zo::launch_side_down_bf16(sd, st), "side-down");
     }
     zo::ProbeGemmArgs g;
     g.X = (const uint16_t*)X; g.ldx = ldx; g.W = (const uint16_t*)W; g.ldw = ldw; g.bias = bias;
     g.T = T; g.m = m; g.n = n; g.act = act; g.Y = Y; g.ldy = ldy; g.out_bf16 = out_dtype == ZO_BF16;
-    g.has_side = has_side; g.cu = batch->cu_seqlens; g.S = batch->n_seqs; g.tok_seq = tabs.tok_seq;
-    g.seq_kind = tabs.seq_kind; g.Aside = Aside; g.RP = plan.RP; g.Rp = plan.Rp; g.Uh = Uh; g.Ph = Ph;
+    g.has_side = has_side; g.tile_hdr = tabs.tile_hdr; g.tile_slots = tabs.tile_slots;
+    g.Uimg = Uimg; g.Pimg = Pimg; g.Xs = Xs; g.m_img = plan.m_img;
+    g.uimg_bytes = (int64_t)plan.uimg_bytes; g.pimg_bytes = (int64_t)plan.pimg_bytes; g.xs_bytes = (int64_t)plan.xs_bytes;
     ZO_HIP(zo::launch_probe_gemm_bf16(g, st), "probe GEMM");
   } else {
     zo::ProbeF32Args a;

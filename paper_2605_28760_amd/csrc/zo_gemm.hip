@@ -91,14 +91,40 @@ __device__ __forceinline__ void block_barrier() {
   asm volatile("" ::: "memory");
 }
 
-// Per-lane addressing of one output tile's operand stream.  Load j (0..3) of a wave
-// fills the 1 KiB block (wave*4 + j) of an operand tile: 8 rows x 128 B.  Lane i lands at
-// byte 16*i of the block, i.e. row i/8, physical chunk i%8, which holds logical chunk
-// (i%8) ^ ((row>>1)&7).  Rows past the end of a matrix are clamped to its last row (their
-// results are never stored); the buffer resources bound every access to the matrix anyway.
+// Per-lane addressing of the operand stream.  Load j (0..3) of a wave fills the 1 KiB block
+// (wave*4 + j) of an operand tile: 8 rows x 128 B.  Lane i lands at byte 16*i of the block, i.e. row i/8,
+// physical chunk i%8, which holds logical chunk (i%8) ^ ((row>>1)&7).  Rows past the end of a matrix are
+// clamped to its last row (their results are never stored); the buffer resources bound every access to
+// the matrix anyway.
+//
+// The stream is a sequence of runs of K tiles.  Within a run the per-lane offsets stay put and the two
+// scalar offsets advance by a fixed step per K tile.  A plain output tile is one run over the K tiles of
+// its two matrices.  With side state (kSide) a tile's runs are: one per direction K tile, one over its
+// bank K tiles, then the base run (see SideOperands).
 struct OperandStream {
   __amdgpu_buffer_rsrc_t rA, rB;
   uint32_t offA[kLPW], offB[kLPW];
+  int soffA, soffB;     // scalar byte offsets of the run's first K tile
+  int stepA, stepB;     // their increments per K tile within the run
+  int kt, len;          // the cursor's K tile within the run, K tiles of the run
+  int L;                // raster position of the cursor's output tile
+  int dir_next;         // kSide: direction K tiles of the tile already started
+  int phase;            // kSide: 0 direction runs, 1 the bank run is under way, 2 the base run is
+};
+
+// Side operands of the probe GEMM as extra K tiles in front of the base K tiles (Sec. 3.2: the candidate
+// term s eps (X V_k) U_k^T and the bank term (X Vb) P^T as LoRA-style factors).  Token side: pool K tile p
+// is [256 tokens][64 columns] bf16; weight side: Uimg block e is [m_img][32] (one 32-column block of one
+// direction's U), Pimg block b is [m_img][64].  Direction K tile j of a token tile multiplies the slots 2j
+// and 2j+1 of the tile's slot list (columns 0-31 and 32-63 of the K tile); a token row is non-zero only
+// in the slots of its own direction, and a foreground row is zero throughout, so its accumulators are
+// still +0 when the base run starts: the state of a plain GEMM.
+struct SideOperands {
+  const TileHdr* hdr;
+  const int32_t* slots;
+  const bf16_t* Uimg; const bf16_t* Pimg; const bf16_t* Xs;
+  int m_img;
+  int uimg_bytes, pimg_bytes, xs_bytes;
 };
 
 // Rows of B that a lane's kLPW loads of a tile cover, when B's rows are gathered through a list
@@ -109,7 +135,8 @@ __device__ __forceinline__ void gather_rows(int (&idx)[kLPW], const int32_t* b_r
   for (int j = 0; j < kLPW; ++j) idx[j] = b_rows[min(tile_n0 + (wave * kLPW + j) * 8 + (lane >> 3), n_b - 1)];
 }
 
-// B_rows_total: rows of the matrix B (only used with a gather list: the whole matrix is the buffer then).
+// The base run of an output tile.  B_rows_total: rows of the matrix B (only used with a gather list: the
+// whole matrix is the buffer then).
 template <bool kGather>
 __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
                                              const bf16_t* B, int64_t ldb, int N, int tile_n0, int K, int wave,
@@ -130,11 +157,30 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
                                            (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
   o.rB = __builtin_amdgcn_make_buffer_rsrc((void*)(kGather ? B : B + (int64_t)tile_n0 * ldb), 0,
                                            (int)min(bytesB, (int64_t)0x7FFFFFFF), 0x00020000);
+  o.soffA = o.soffB = 0;
+  o.stepA = o.stepB = BK * 2;
+  o.kt = 0;
+  o.len = K / BK;
+  o.phase = 2;
+}
+
+// Per-lane offsets of a side run.  The images hold every row of a tile (they are padded), so a lane's
+// offset is its row in the tile times the image's row pitch plus its swizzled chunk.
+template <bool kDirRun>
+__device__ __forceinline__ void setup_side_offsets(OperandStream& o, int wave, int lane, int base0, int base1) {
+#pragma unroll
+  for (int j = 0; j < kLPW; ++j) {
+    const int row = (wave * kLPW + j) * 8 + (lane >> 3);
+    const int lch = (lane & 7) ^ ((row >> 1) & 7);
+    o.offB[j] = row * 128 + lch * 16;
+    // direction run: columns 0-31 of the K tile come from image block base0, columns 32-63 from base1
+    o.offA[j] = kDirRun ? (uint32_t)((lch >= 4 ? base1 : base0) + row * 64 + (lch & 3) * 16) : o.offB[j];
+  }
 }
 
 // Persistent GEMM driver.  For every output tile of this workgroup:
-//   pre(tm, tn, acc)   may add side terms into the zeroed accumulators,
-//   acc[rb][cb] += A[tile rows] * B[tile rows]^T over K (multiple of 64),
+//   acc[rb][cb] = sum over the tile's K tiles (side K tiles first, then the K / 64 base K tiles) of
+//                 A[tile rows] * B[tile rows]^T, starting from +0,
 //   post(tm, tn, acc)  consumes the accumulators (it may use lds + kStagesLds .. +kEpiLds
 //                      and workgroup barriers; it must not touch the operand stages).
 // 16x16x32 fragments: lane l holds row l%16 and the 8 k-values of group l/16; D: lane l holds
@@ -143,21 +189,22 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
 // Pipeline of the K loop.  K tiles of 64 (128-byte row segments, so every L2 request is a
 // full line) alternate between two LDS stages.  A K tile is two k-steps of 32; the 12 LDS
 // reads of the next k-step's fragments are spread under the 32 MFMAs of the current one
-// (an A fragment's registers are reused once its four MFMAs have issued).  The 8
-// direct-to-LDS loads a wave issues per K tile are spread thinly over the two k-steps: a
-// burst fills the memory pipeline's queues and stalls the wave at issue.  The single
+// (an A fragment's registers are reused once its four MFMAs have issued).  The single
 // barrier of a K tile sits between its two k-steps: by then every wave has read its last
 // fragments of this K tile's stage (so the stage can be refilled) and the next K tile has
 // landed (so its first fragments can be fetched under the second k-step).  The load cursor
-// runs ahead of the compute cursor across output-tile boundaries; past the workgroup's
-// last tile it stays on the final K tile (those loads refill stages nobody reads again).
+// runs ahead of the compute cursor across runs and output-tile boundaries; past the
+// workgroup's last tile it stays on the final K tile (those loads refill stages nobody
+// reads again).  The K loop itself does not know what a K tile holds: side K tiles reach
+// the matrix core through the same LDS stages as the base K tiles.
 //
 // With kGather the N rows of the B operand are rows b_rows[0..N-1] of a matrix of B_rows_total rows
 // (smaller than 2 GiB); the row list of a tile is fetched one tile ahead of the load cursor.
-template <bool kGather, bool kSplit, class Pre, class Post>
+template <bool kGather, bool kSplit, bool kSide, class Post>
 __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, int64_t lda, int M,
                                                 const bf16_t* __restrict__ B, int64_t ldb, int N, int K,
-                                                int n_tm, int n_tn, int tn_super, int n_split, char* lds, Pre pre, Post post,
+                                                int n_tm, int n_tn, int tn_super, int n_split, char* lds, Post post,
+                                                const SideOperands& so,
                                                 const int32_t* __restrict__ b_rows = nullptr, int B_rows_total = 0) {
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -195,11 +242,22 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     }
     int tm, tn;
     tile_at(pos, n_tm, n_tn, tn_super, tm, tn);
-    m0 = tm * BM + half * (BM / 2);
-    n0 = tn * BN;
+    // (the integer divisions of the raster run on the vector ALU; their results are wave-uniform, and
+    // saying so keeps everything derived from them in scalar registers)
+    m0 = __builtin_amdgcn_readfirstlane(tm * BM + half * (BM / 2));
+    n0 = __builtin_amdgcn_readfirstlane(tn * BN);
     return is_half;
   };
   const int nk = K / BK;
+  // the side K tiles of the token tile that starts at row n0
+  auto side_hdr = [&](int n0) -> TileHdr {
+    TileHdr h = so.hdr[n0 / BN];
+    h.kt0 = __builtin_amdgcn_readfirstlane(h.kt0);
+    h.n_slots = __builtin_amdgcn_readfirstlane(h.n_slots);
+    h.n_bank_kt = __builtin_amdgcn_readfirstlane(h.n_bank_kt);
+    h.slot0 = __builtin_amdgcn_readfirstlane(h.slot0);
+    return h;
+  };
 
   // LDS -> register mapping
   const int r16 = lane & 15;
@@ -211,45 +269,97 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
 
   // load cursor
   OperandStream ld;
-  int ld_L = L, ld_kt = 0;
   int idx_next[kLPW] = {};   // gather: B rows of the tile after the cursor's
-  {
+  // the next run of the cursor's output tile (the first one after ld.dir_next = 0, ld.phase = 0)
+  auto next_run = [&]() {
     int m0, n0;
-    item_at(ld_L, m0, n0);
-    int idx[kLPW] = {};
-    if (kGather) gather_rows(idx, b_rows, N, n0, wave, lane);
-    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx, B_rows_total);
+    item_at(ld.L, m0, n0);
+    if constexpr (kSide) {
+      const TileHdr h = side_hdr(n0);
+      const int n_dir_kt = (h.n_slots + 1) >> 1;
+      const int lane_t = opaque(lane);
+      if (ld.dir_next < n_dir_kt) {
+        // direction K tile j: slots 2j and 2j+1 (an odd count leaves the second half of the last tile
+        // to the first slot's block again; the token side holds zeros there)
+        const int j = ld.dir_next;
+        const int e0 = __builtin_amdgcn_readfirstlane(so.slots[h.slot0 + 2 * j]);
+        const int e1 = 2 * j + 1 < h.n_slots ? __builtin_amdgcn_readfirstlane(so.slots[h.slot0 + 2 * j + 1]) : e0;
+        setup_side_offsets<true>(ld, wave, lane_t, e0 * so.m_img * 64, e1 * so.m_img * 64);
+        ld.rA = __builtin_amdgcn_make_buffer_rsrc((void*)so.Uimg, 0, so.uimg_bytes, 0x00020000);
+        ld.rB = __builtin_amdgcn_make_buffer_rsrc((void*)so.Xs, 0, so.xs_bytes, 0x00020000);
+        ld.soffA = m0 * 64;
+        ld.soffB = (h.kt0 + j) * (BN * BK * 2);
+        ld.stepA = ld.stepB = 0;
+        ld.kt = 0;
+        ld.len = 1;
+        ld.dir_next = j + 1;
+        return;
+      }
+      if (ld.phase == 0 && h.n_bank_kt > 0) {
+        setup_side_offsets<false>(ld, wave, lane_t, 0, 0);
+        ld.rA = __builtin_amdgcn_make_buffer_rsrc((void*)so.Pimg, 0, so.pimg_bytes, 0x00020000);
+        ld.rB = __builtin_amdgcn_make_buffer_rsrc((void*)so.Xs, 0, so.xs_bytes, 0x00020000);
+        ld.soffA = m0 * 128;
+        ld.soffB = (h.kt0 + n_dir_kt) * (BN * BK * 2);
+        ld.stepA = so.m_img * 128;
+        ld.stepB = BN * BK * 2;
+        ld.kt = 0;
+        ld.len = h.n_bank_kt;
+        ld.phase = 1;
+        return;
+      }
+    }
+    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total);
     if (kGather) {
-      item_at(min(ld_L + stride, L_end - 1), m0, n0);
+      item_at(min(ld.L + stride, L_end - 1), m0, n0);
       gather_rows(idx_next, b_rows, N, n0, wave, lane);
     }
+  };
+  {
+    // (every scalar of the cursor is defined on every path: an undefined one would be given a vector register)
+    ld.soffA = ld.soffB = ld.stepA = ld.stepB = ld.kt = ld.len = 0;
+    ld.L = L;
+    ld.dir_next = 0;
+    ld.phase = 0;
+    if (kGather) {
+      int m0, n0;
+      item_at(L, m0, n0);
+      gather_rows(idx_next, b_rows, N, n0, wave, lane);
+    }
+    next_run();
   }
   // load i (0..7) of the cursor's K tile: i < 4 -> A chunk i, else B chunk i - 4
   auto issue_range = [&](int stage, int first, int count) {
     char* sbase = lds + stage * kStage + wave * kLPW * 1024;
-    const int koff = ld_kt * (BK * 2);
+    int soffA = ld.soffA + ld.kt * ld.stepA, soffB = ld.soffB + ld.kt * ld.stepB;
+    if constexpr (kSide) {
+      // The cursor's scalars are wave-uniform, but with runs set up on several control-flow paths the
+      // compiler keeps them in vector registers; a load whose scalar offset sits in a vector register is
+      // wrapped in a lane-by-lane loop unless the offset is read back into a scalar register first.
+      soffA = __builtin_amdgcn_readfirstlane(soffA);
+      soffB = __builtin_amdgcn_readfirstlane(soffB);
+    }
 #pragma unroll
     for (int i = first; i < first + count; ++i) {
       if (i < kLPW)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rA, (lds_void*)(sbase + i * 1024), 16, (int)ld.offA[i], koff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rA, (lds_void*)(sbase + i * 1024), 16, (int)ld.offA[i], soffA, 0, 0);
       else
         __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rB, (lds_void*)(sbase + kOperandStage + (i - kLPW) * 1024), 16,
-                                                 (int)ld.offB[i - kLPW], koff, 0, 0);
+                                                 (int)ld.offB[i - kLPW], soffB, 0, 0);
     }
   };
   auto advance_cursor = [&]() {
-    if (ld_kt + 1 < nk) { ++ld_kt; return; }
-    if (ld_L + stride < L_end) {
-      ld_L += stride;
-      ld_kt = 0;
-      int m0, n0;
-      item_at(ld_L, m0, n0);
-      setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total);
-      if (kGather) {
-        item_at(min(ld_L + stride, L_end - 1), m0, n0);
-        gather_rows(idx_next, b_rows, N, n0, wave, lane);
-      }
+    if (ld.kt + 1 < ld.len) {
+      ++ld.kt;
+      return;
     }
+    if (!kSide || ld.phase == 2) {   // the tile's last K tile: on to the next output tile, if there is one
+      if (ld.L + stride >= L_end) return;
+      ld.L += stride;
+      ld.dir_next = 0;
+      ld.phase = 0;
+    }
+    next_run();
   };
 
   bf16x8 fa[2][RB], fb[2][CB];
@@ -288,6 +398,11 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     int m0, n0;
     const bool is_half = item_at(L, m0, n0);
     const bool active = !(kSplit && is_half && wm == 1);   // wave-uniform
+    int nk_tile = nk;
+    if constexpr (kSide) {
+      const TileHdr h = side_hdr(n0);
+      nk_tile += ((h.n_slots + 1) >> 1) + h.n_bank_kt;
+    }
 
     // the K loop of a wave that multiplies (kActive) or only keeps the operand stream and the barriers going
     auto k_loop = [&](auto active_c, Acc& acc) __attribute__((always_inline)) {
@@ -299,7 +414,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
           for (int cb = 0; cb < CB; ++cb)
             acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
       };
-      for (int kt = 0; kt < nk; ++kt) {
+      for (int kt = 0; kt < nk_tile; ++kt) {
         // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
         __builtin_amdgcn_sched_barrier(0);
         issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
@@ -331,9 +446,8 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
         for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
-      pre(m0, n0, acc);
       // The first fragments of this tile were already fetched under the previous tile's last
-      // k-step; fetching them again here keeps their 48 registers free during post() and pre().
+      // k-step; fetching them again here keeps their 48 registers free during post().
       load_frags(0, stage, 0);
       k_loop(std::true_type{}, acc);
       post(m0, n0, acc);
@@ -345,15 +459,16 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads before the workgroup ends
 }
 
+// Compute units of the current device, cached per device.
 int compute_units() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds)
-      n = 256;
-    cus = n;
+  static std::atomic<int> cus[kMaxDevices];
+  const int dev = current_device();
+  int n = cus[dev].load(std::memory_order_relaxed);
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < kXcds) n = 256;
+    cus[dev].store(n, std::memory_order_relaxed);
   }
-  return cus;
+  return n;
 }
 
 // How many of the last tiles of the raster are cut into two halves of 128 weight rows: all tiles of a last
@@ -409,75 +524,14 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
   const int lane = tid & 63;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // side operands have K = RP (direction) and K = Rp (bank), multiples of 16; the K=32
-  // instruction takes them 32 at a time, lanes whose k-group lies past the end supply zeros
-  auto side_phase = [&](int tile_o0, int tile_t0, Acc& acc) {
-    if constexpr (!kSide) return;
-    const int lane_t = opaque(lane);
-    const int r16 = lane_t & 15, kg = (lane_t >> 4) * 8;
-    const int NC = p.RP + p.Rp;
-    const int tile_end = min(tile_t0 + BN, p.T);
-    int feat[RB], tok[CB];
-#pragma unroll
-    for (int i = 0; i < RB; ++i) feat[i] = min(tile_o0 + wm * 128 + i * 16 + r16, p.m - 1);
-#pragma unroll
-    for (int i = 0; i < CB; ++i) tok[i] = tile_t0 + wn * 64 + i * 16 + r16;
-    // walk the sequences that intersect this token tile
-    int s = __builtin_amdgcn_readfirstlane(p.tok_seq[tile_t0]);
-    bool any_cand = false;
-    while (true) {
-      const int seg_lo = max(__builtin_amdgcn_readfirstlane(p.cu[s]), tile_t0);
-      const int seq_end = __builtin_amdgcn_readfirstlane(p.cu[s + 1]);
-      const int seg_hi = min(seq_end, tile_end);
-      const int kind = __builtin_amdgcn_readfirstlane(p.seq_kind[s]);
-      if (seg_hi > seg_lo && kind >= kKindCentre) any_cand = true;
-      if (seg_hi > seg_lo && kind >= 0) {
-        const bf16_t* Ud = p.Uh + (int64_t)kind * p.m * p.RP;
-        for (int ks = 0; ks < p.RP; ks += 32) {
-          const bool kin = ks + kg < p.RP;
-          bf16x8 sa[RB], sb[CB];
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb) sa[rb] = kin ? load_frag(Ud + (int64_t)feat[rb] * p.RP + ks + kg) : zero_frag();
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) {
-            const bool in = kin && tok[cb] >= seg_lo && tok[cb] < seg_hi;
-            sb[cb] = in ? load_frag(p.Aside + (int64_t)tok[cb] * NC + ks + kg) : zero_frag();
-          }
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-              acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[rb], sb[cb], acc[rb][cb], 0, 0, 0);
-        }
-      }
-      if (seq_end >= tile_end || s + 1 >= p.S) break;
-      ++s;
-    }
-    if (any_cand && p.Rp > 0) {
-      for (int ks = 0; ks < p.Rp; ks += 32) {
-        const bool kin = ks + kg < p.Rp;
-        bf16x8 sa[RB], sb[CB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) sa[rb] = kin ? load_frag(p.Ph + (int64_t)feat[rb] * p.Rp + ks + kg) : zero_frag();
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb)
-          sb[cb] = kin ? load_frag(p.Aside + (int64_t)min(tok[cb], p.T - 1) * NC + p.RP + ks + kg) : zero_frag();
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb)
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sa[rb], sb[cb], acc[rb][cb], 0, 0, 0);
-      }
-    }
-  };
-
   // D block (rb, cb): out feature = obase + rb*16 + 4*g + v, token = tbase + cb*16 + r16.
   auto epilogue = [&](int tile_o0, int tile_t0, Acc& acc) {
     const int lane_t = opaque(lane);
     const int r16 = lane_t & 15, g = lane_t >> 4;
     const int obase = tile_o0 + wm * 128;   // first out feature of this wave
     const int tbase = tile_t0 + wn * 64;    // first token of this wave
-    const float floor_val = p.act == 1 ? 0.0f : -INFINITY;   // ReLU as a clamp: no branch in the tile epilogue
+    // ReLU as a select on the sign, which lets a NaN through (a max would replace it by the other operand)
+    const bool relu = p.act == 1;
     if constexpr (!kOutBf16) {
       float* Y = (float*)p.Y;
 #pragma unroll
@@ -499,7 +553,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
           } else {
 #pragma unroll
             for (int v = 0; v < 4; ++v)
-              if (o0 + v < p.m) Y[(int64_t)t * p.ldy + o0 + v] = fmaxf(y[v], floor_val);
+              if (o0 + v < p.m) Y[(int64_t)t * p.ldy + o0 + v] = (relu && y[v] < 0.0f) ? 0.0f : y[v];
           }
         }
       }
@@ -562,7 +616,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
           for (int e = 0; e < 4; ++e) y[e] += p.bias[min(ob + e, p.m - 1)];
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) y[e] = fmaxf(y[e], floor_val);
+        for (int e = 0; e < 4; ++e) y[e] = (relu && y[e] < 0.0f) ? 0.0f : y[e];
         // 16-byte slot rb*2 + g/2 of the token's row, half g&1
         *(u32x2_alias*)(region + wr_base + (((rb * 2 + (g >> 1)) * 16) ^ wr_swz)) =
             u32x2{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
@@ -578,19 +632,21 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
     }
   };
 
-  persistent_gemm<false, kSplit>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, tn_super, n_split, lds, side_phase, epilogue);
+  SideOperands so;
+  so.hdr = p.tile_hdr; so.slots = p.tile_slots; so.Uimg = p.Uimg; so.Pimg = p.Pimg; so.Xs = p.Xs; so.m_img = p.m_img;
+  so.uimg_bytes = (int)p.uimg_bytes; so.pimg_bytes = (int)p.pimg_bytes; so.xs_bytes = (int)p.xs_bytes;
+  persistent_gemm<false, kSplit, kSide>(p.W, p.ldw, p.m, p.X, p.ldx, p.T, p.n, n_tm, n_tn, tn_super, n_split, lds, epilogue, so);
 }
 
 template <bool kSide, bool kOutBf16, bool kBias, bool kGate, bool kSplit>
 static hipError_t launch_probe_kernel(const ProbeGemmArgs& a, int n_tm, int n_tn, int n_split, hipStream_t st) {
   const int tn_super = token_super_block(n_tn, (int64_t)a.T * a.n * 2);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<bool> configured[kMaxDevices];
+  const hipError_t ec = once_per_device(configured, [] {
+    return hipFuncSetAttribute((const void*)k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>,
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+  });
+  if (ec != hipSuccess) return ec;
   hipLaunchKernelGGL((k_probe_gemm<kSide, kOutBf16, kBias, kGate, kSplit>), dim3(gemm_grid(n_tm * n_tn + n_split)),
                      dim3(kThreads), kGemmLds, st, a, n_tm, n_tn, tn_super, n_split);
   return hipGetLastError();
@@ -642,7 +698,6 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
   float* s_sum = s_max + 2 * BN;                // [2][256]
   constexpr float kLog2e = 1.4426950408889634f;
 
-  auto no_side = [](int, int, Acc&) {};
   // D block (rb, cb): vocabulary row = vbase + rb*16 + 4*g + v, token = tile_t0 + wn*64 + cb*16 + r16.
   auto epilogue = [&](int tile_v0, int tile_t0, Acc& acc) {
     const int lane_t = opaque(lane), tid_t = opaque(tid);
@@ -706,17 +761,17 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
     block_barrier();   // the exchange buffers are free again for the next tile
   };
 
-  persistent_gemm<kGather, false>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, tn_super, 0, lds, no_side, epilogue, p.rows, p.T);
+  persistent_gemm<kGather, false, false>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, tn_super, 0, lds, epilogue,
+                                         SideOperands{}, p.rows, p.T);
 }
 
 template <bool kGather>
 static hipError_t launch_head_variant(const HeadScoreArgs& a, hipStream_t st) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_head_score<kGather>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static std::atomic<bool> configured[kMaxDevices];
+  const hipError_t ec = once_per_device(configured, [] {
+    return hipFuncSetAttribute((const void*)k_head_score<kGather>, hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+  });
+  if (ec != hipSuccess) return ec;
   // the grid is sized for every token being scored; with fewer, the surplus workgroups find no tile
   const int n_tm = (a.vocab + BM - 1) / BM, n_tn = (a.T + BN - 1) / BN;
   const int tn_super = token_super_block(n_tn, (int64_t)a.T * a.d * 2);

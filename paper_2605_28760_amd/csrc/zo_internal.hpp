@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace zo {
 
 // Row-tile of the MFMA GEMM kernels and row-chunk of the side-down kernel.
@@ -34,21 +36,53 @@ struct SideItem {
   float scale;    // sign * eps
 };
 
+// Side K tiles of one token tile of the bf16 probe GEMM (a tile = kTileN packed rows).  The side state
+// enters the GEMM as extra K tiles in front of the base K tiles: first the direction tiles (two slots
+// of 32 columns each per K tile; a slot holds one 32-column block of one direction's U), then the bank
+// tiles (64 bank columns each).
+struct TileHdr {
+  int32_t kt0;        // first K tile of this token tile in the pool of token-side images
+  int32_t n_slots;    // direction slots in use (distinct directions of the tile x blocks per direction)
+  int32_t n_bank_kt;  // bank K tiles (0 when the tile holds no candidate row)
+  int32_t slot0;      // first entry of this tile in the slot list
+};
+
 struct SeqTables {
   int32_t* seq_kind;   // [S]
   float* seq_scale;    // [S]
   int32_t* tok_seq;    // [T]
   SideItem* items;     // [max_items]
-  int32_t* n_items;    // [2]: number of items, then the k-split the side-down pass uses for them
+  int32_t* n_items;    // [2]: number of side-down items, number of pool K tiles in use
   int32_t max_items;
-  // how the k-split is chosen on the device once the items are known: as many splits as keep
-  // ceil(n_items / 4) * splits workgroups within `side_slots` (one resident round), at most side_ks_cap
-  int32_t side_slots;
-  int32_t side_ks_cap;
+  // per token tile (null tile_hdr: not wanted)
+  TileHdr* tile_hdr;   // [n_tn]
+  int32_t* tile_slots; // [slot_cap]: block of the U image (direction * SPD + 32-column block) behind a slot
+  int32_t* kt_tile;    // [kt_cap]: token tile that owns a pool K tile
+  int32_t n_tn, slot_cap, kt_cap;
+  int32_t SPD;         // 32-column blocks per direction
+  int32_t RpT;         // bank K tiles of a tile with candidates
 };
 
-// number of compute units of the current device (256 on MI355X; cached)
+// number of compute units of the current device (256 on MI355X; cached per device)
 int compute_units();
+
+// Per-device, thread-safe one-time set-up of a kernel (its dynamic LDS limit).  `done` is a static
+// array of the caller, one flag per device; the set-up call is idempotent, so two threads that race
+// on the first launch both make it and both succeed.
+constexpr int kMaxDevices = 64;
+inline int current_device() {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+  return dev;
+}
+template <class F>
+inline hipError_t once_per_device(std::atomic<bool> (&done)[kMaxDevices], F setup) {
+  const int dev = current_device();
+  if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+  const hipError_t e = setup();
+  if (e == hipSuccess) done[dev].store(true, std::memory_order_release);
+  return e;
+}
 
 // ---- zo_prep.hip ------------------------------------------------------------
 hipError_t launch_philox_words(uint64_t seed, uint32_t tensor_id, uint64_t first_block,
@@ -57,8 +91,9 @@ hipError_t launch_factor_fill(uint64_t seed, uint32_t tensor_id, int64_t rows, i
                               void* out, hipStream_t st);
 hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_cand, hipStream_t st);
 hipError_t launch_seq_tables(const BatchDev& b, float eps, const SeqTables& t, hipStream_t st);
-// bf16 operand images: Uh [K][m][RP] (k-contiguous rows of U, zero padded to RP),
-// Vt [K][RP][n] (V transposed), Ph [m][Rp], Vbt [Rp][n].
+// bf16 operand images.  For the GEMM's side K tiles: Uimg [K * SPD][m_img][32] (32-column blocks of U,
+// 64-byte rows), Pimg [RpT][m_img][64] (64-column blocks of P, 128-byte rows); rows >= m and columns
+// beyond the rank are zero.  For the side-down pass: Vt [K][RP][n] (V transposed), Vbt [Rp][n].
 // fp32 factors: Uf [K][m][r], Vf [K][n][r]
 hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int n, int r,
                               float* Uf, float* Vf, hipStream_t st);
@@ -70,15 +105,21 @@ struct SideDownArgs {
   const uint16_t* Vbt;              // [Rp][n]
   int n, RP, Rp, T;
   const SideItem* items; const int32_t* n_items; int max_items;
-  int ks_cap;                       // >= 1: upper bound of the k-split, which the device picks (n_items[1])
-  float* partial;                   // [k-split][T][RP+Rp] when the k-split is > 1
-  uint16_t* Aside;                  // bf16 [T][RP+Rp]: [s*eps*X V | X Vb]
-  const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;  // for the split-K reduction
+  int ksplit;                       // >= 1: K ranges per row, a function of n alone (side_ksplit)
+  float* partial;                   // [ksplit][T][RP+Rp] partial sums of one K range each
+  const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;
+  // where the finished rows go: the token-side images of the GEMM's side K tiles
+  const TileHdr* tile_hdr; const int32_t* tile_slots; const int32_t* kt_tile;
+  int kt_cap, SPD;
+  uint16_t* Xs;                     // [pool K tile][kTileN][kTileK] bf16
 };
+// K ranges of the side-down pass for an input width n: never a function of the batch, so that the
+// summation order of a row's side term does not depend on what else is in the batch.
+int side_ksplit(int n);
 // sequence tables, token -> sequence map and the four operand images of a bf16 probe linear in one launch
 hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables& tabs, uint32_t tensor_id, int m,
                                   int n, int r, int RP, int Rp, const float* P, const float* Vb, int R_cap,
-                                  int R_used, uint16_t* Uh, uint16_t* Vt, uint16_t* Ph, uint16_t* Vbt,
+                                  int R_used, int m_img, uint16_t* Uimg, uint16_t* Vt, uint16_t* Pimg, uint16_t* Vbt,
                                   hipStream_t st);
 hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st);
 
@@ -90,14 +131,15 @@ struct ProbeGemmArgs {
   int T, m, n;
   int act;
   void* Y; int64_t ldy; int out_bf16;
-  // side state (has_side = 0: plain GEMM for every row)
+  // side state (has_side = 0: plain GEMM for every row): extra K tiles in front of the base K tiles
   int has_side;
-  const int32_t* cu; int S;
-  const int32_t* tok_seq;
-  const int32_t* seq_kind;
-  const uint16_t* Aside; int RP, Rp;
-  const uint16_t* Uh;               // [K][m][RP]
-  const uint16_t* Ph;               // [m][Rp]
+  const TileHdr* tile_hdr;          // [token tiles]
+  const int32_t* tile_slots;
+  const uint16_t* Uimg;             // [K * SPD][m_img][32]
+  const uint16_t* Pimg;             // [RpT][m_img][64]
+  const uint16_t* Xs;               // [pool K tile][kTileN][kTileK]
+  int m_img;                        // rows of the images: the weight-row tiles rounded up, plus half a tile
+  int64_t uimg_bytes, pimg_bytes, xs_bytes;
 };
 hipError_t launch_probe_gemm_bf16(const ProbeGemmArgs& a, hipStream_t st);
 

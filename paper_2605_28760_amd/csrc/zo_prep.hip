@@ -80,15 +80,31 @@ hipError_t launch_tok_index(const BatchDev& b, int32_t* tok_seq, int32_t* tok_ca
   return hipGetLastError();
 }
 
-// Per-sequence kind / scale and the list of side-down work items (chunks of at
-// most kSideRows rows of one sequence).  One workgroup; sequences are scanned in
-// blocks of 1024 so the item order follows the row order.
+// Exclusive prefix sum of one value per thread over a block of 1024 threads; *total = the block's sum.
+__device__ __forceinline__ int block_scan_1024(int v, int* s_scan, int* total) {
+  const int tid = threadIdx.x;
+  s_scan[tid] = v;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const int u = (tid >= off) ? s_scan[tid - off] : 0;
+    __syncthreads();
+    s_scan[tid] += u;
+    __syncthreads();
+  }
+  const int incl = s_scan[tid];
+  *total = s_scan[1023];
+  __syncthreads();
+  return incl - v;
+}
+
+// Per-sequence kind / scale, the list of side-down work items (chunks of at
+// most kSideRows rows of one sequence) and, for the bf16 GEMM, the side K tiles of
+// every token tile.  One workgroup; sequences and tiles are scanned in blocks of
+// 1024 so the item order follows the row order.
 __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, const SeqTables& t) {
   __shared__ int s_scan[1024];
-  __shared__ int s_carry;
   const int tid = threadIdx.x;
-  if (tid == 0) s_carry = 0;
-  __syncthreads();
+  int carry = 0;
   for (int base = 0; base < b.S; base += 1024) {
     const int s = base + tid;
     int row0 = 0, len = 0, kind = kKindForeground, nchunk = 0;
@@ -107,15 +123,8 @@ __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, c
       t.seq_scale[s] = scale;
       nchunk = (len + kSideRows - 1) / kSideRows;
     }
-    s_scan[tid] = nchunk;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-      const int v = (tid >= off) ? s_scan[tid - off] : 0;
-      __syncthreads();
-      s_scan[tid] += v;
-      __syncthreads();
-    }
-    const int first = s_carry + s_scan[tid] - nchunk;
+    int total;
+    const int first = carry + block_scan_1024(nchunk, s_scan, &total);
     for (int j = 0; j < nchunk; ++j) {
       if (first + j < t.max_items) {
         SideItem it;
@@ -126,16 +135,59 @@ __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, c
         t.items[first + j] = it;
       }
     }
-    __syncthreads();
-    if (tid == 1023) s_carry += s_scan[1023];
-    __syncthreads();
+    carry += total;
   }
-  if (tid == 0) {
-    const int n_items = min(s_carry, t.max_items);
-    const int groups = max((n_items + 3) / 4, 1);
-    t.n_items[0] = n_items;
-    t.n_items[1] = max(1, min(t.side_ks_cap, t.side_slots / groups));
+  if (tid == 0) t.n_items[0] = min(carry, t.max_items);
+  if (!t.tile_hdr) return;
+
+  // Token tiles.  A tile's slot list names the distinct directions of the sequences that intersect it, in
+  // order of first appearance, SPD slots each; it lives in a region of the list sized by the number of
+  // those sequences (the sum over the tiles is at most the tiles plus the sequences).  Kinds written by
+  // other threads of this workgroup above are visible after the barriers of the scans.
+  __syncthreads();
+  int slot_carry = 0, kt_carry = 0;
+  for (int base = 0; base < t.n_tn; base += 1024) {
+    const int tn = base + tid;
+    int t0 = 0, t1 = 0, s_first = 0, s_last = -1, bound = 0;
+    if (tn < t.n_tn) {
+      t0 = tn * kTileN;
+      t1 = min(b.T, t0 + kTileN);
+      s_first = seq_of_row(b.cu, b.S, t0);
+      s_last = seq_of_row(b.cu, b.S, t1 - 1);
+      bound = min(min(s_last - s_first + 1, b.K), kTileN) * t.SPD;   // a tile meets at most kTileN non-empty sequences
+    }
+    int total;
+    const int slot0 = slot_carry + block_scan_1024(bound, s_scan, &total);
+    slot_carry += total;
+    int q = 0, n_kt = 0, n_bank = 0;
+    if (tn < t.n_tn) {
+      bool any = false;
+      for (int s = s_first; s <= s_last; ++s) {
+        if (min(b.cu[s + 1], t1) <= max(b.cu[s], t0)) continue;   // no row of s in this tile
+        const int kind = t.seq_kind[s];
+        if (kind >= kKindCentre) any = true;
+        if (kind < 0) continue;
+        bool seen = false;
+        for (int j = 0; j < q && !seen; ++j) seen = t.tile_slots[slot0 + j * t.SPD] == kind * t.SPD;
+        if (!seen && slot0 + (q + 1) * t.SPD <= t.slot_cap) {
+          for (int blk = 0; blk < t.SPD; ++blk) t.tile_slots[slot0 + q * t.SPD + blk] = kind * t.SPD + blk;
+          ++q;
+        }
+      }
+      n_bank = any ? t.RpT : 0;
+      n_kt = (q * t.SPD + 1) / 2 + n_bank;
+    }
+    const int kt0 = kt_carry + block_scan_1024(n_kt, s_scan, &total);
+    kt_carry += total;
+    if (tn < t.n_tn) {
+      TileHdr h;
+      h.kt0 = kt0; h.n_slots = q * t.SPD; h.n_bank_kt = n_bank; h.slot0 = slot0;
+      if (kt0 + n_kt > t.kt_cap) { h.n_slots = 0; h.n_bank_kt = 0; n_kt = 0; }   // cannot happen: the caps are bounds
+      t.tile_hdr[tn] = h;
+      for (int j = 0; j < n_kt; ++j) t.kt_tile[kt0 + j] = tn;
+    }
   }
+  if (tid == 0) t.n_items[1] = min(kt_carry, t.kt_cap);
 }
 
 __global__ __launch_bounds__(1024) void k_seq_tables(BatchDev b, float eps, SeqTables t) { seq_tables_block(b, eps, t); }
@@ -176,17 +228,20 @@ __device__ __forceinline__ void factor_quad(uint64_t seed, uint32_t tid, int64_t
   }
 }
 
-// idx runs over [K][m][RP/4]: one thread writes four neighbouring entries of a row of U (8 bytes)
-__device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint32_t tid_u, int m, int r, int RP, bf16_t* Uh) {
-  const int quads = RP >> 2;
-  const int64_t per_dir = (int64_t)m * quads;
+// idx runs over [K][m_img][RP32/4]: one thread writes four neighbouring entries of a row of U (8 bytes) into
+// the image [K * SPD][m_img][32]; rows >= m and columns >= r are zero
+__device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint32_t tid_u, int m, int m_img, int r, int SPD,
+                                           bf16_t* Uimg) {
+  const int quads = SPD * 8;
+  const int64_t per_dir = (int64_t)m_img * quads;
   if (idx >= per_dir * b.K) return;
   const int k = (int)(idx / per_dir);
   const int64_t rem = idx - (int64_t)k * per_dir;
   const int i = (int)(rem / quads), c0 = (int)(rem % quads) * 4;
   float z[4] = {0.f, 0.f, 0.f, 0.f};
-  if (c0 < r) factor_quad(b.seed[k], tid_u, i, r, c0, z);
-  *reinterpret_cast<uint2*>(Uh + ((int64_t)k * m + i) * RP + c0) = make_uint2(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]));
+  if (i < m && c0 < r) factor_quad(b.seed[k], tid_u, i, r, c0, z);
+  *reinterpret_cast<uint2*>(Uimg + (((int64_t)k * SPD + (c0 >> 5)) * m_img + i) * 32 + (c0 & 31)) =
+      make_uint2(pack_bf16x2(z[0], z[1]), pack_bf16x2(z[2], z[3]));
 }
 
 // idx runs over [K][RP/4][n]: one thread writes entry i of four neighbouring rows of V^T
@@ -203,10 +258,13 @@ __device__ __forceinline__ void image_Vt_at(const BatchDev& b, int64_t idx, uint
   for (int l = 0; l < 4; ++l) Vt[((int64_t)k * RP + c0 + l) * n + i] = f32_to_bf16(z[l]);
 }
 
-__device__ __forceinline__ void image_P_at(int64_t idx, const float* P, int R_cap, int R_used, int Rp, int m, bf16_t* Ph) {
-  if (idx >= (int64_t)m * Rp) return;
-  const int i = (int)(idx / Rp), j = (int)(idx % Rp);
-  Ph[idx] = f32_to_bf16(j < R_used ? P[(int64_t)i * R_cap + j] : 0.0f);
+// idx runs over [m_img][RpT * 64]: image [RpT][m_img][64] of P; rows >= m and columns >= R_used are zero
+__device__ __forceinline__ void image_P_at(int64_t idx, const float* P, int R_cap, int R_used, int RpT, int m, int m_img,
+                                           bf16_t* Pimg) {
+  const int cols = RpT * 64;
+  if (idx >= (int64_t)m_img * cols) return;
+  const int i = (int)(idx / cols), j = (int)(idx % cols);
+  Pimg[((int64_t)(j >> 6) * m_img + i) * 64 + (j & 63)] = f32_to_bf16(i < m && j < R_used ? P[(int64_t)i * R_cap + j] : 0.0f);
 }
 
 __global__ void k_factors_f32(BatchDev b, uint32_t tid, int rows, int r, float* out) {
@@ -232,9 +290,9 @@ hipError_t launch_factors_f32(const BatchDev& b, uint32_t tensor_id, int m, int 
 // [P image] [Vb^T image: 32x32 transposing tiles].  The pieces do not depend on one another.
 struct ProbePrepArgs {
   BatchDev b; float eps; SeqTables tabs;
-  uint32_t tensor_id; int m, n, r, RP, Rp;
+  uint32_t tensor_id; int m, n, r, RP, Rp, m_img;
   const float* P; const float* Vb; int R_cap, R_used;
-  bf16_t* Uh; bf16_t* Vt; bf16_t* Ph; bf16_t* Vbt;
+  bf16_t* Uimg; bf16_t* Vt; bf16_t* Pimg; bf16_t* Vbt;
   int nb_tok, nb_U, nb_Vt, nb_P, nb_Vbt, vbt_tiles_n;
 };
 
@@ -244,11 +302,11 @@ __global__ __launch_bounds__(1024) void k_probe_prep(ProbePrepArgs a) {
   blk -= 1;
   if (blk < a.nb_tok) { tok_index_at(a.b, blk * 1024 + threadIdx.x, a.tabs.tok_seq, nullptr); return; }
   blk -= a.nb_tok;
-  if (blk < a.nb_U) { image_U_at(a.b, (int64_t)blk * 1024 + threadIdx.x, a.tensor_id & ~1u, a.m, a.r, a.RP, a.Uh); return; }
+  if (blk < a.nb_U) { image_U_at(a.b, (int64_t)blk * 1024 + threadIdx.x, a.tensor_id & ~1u, a.m, a.m_img, a.r, a.tabs.SPD, a.Uimg); return; }
   blk -= a.nb_U;
   if (blk < a.nb_Vt) { image_Vt_at(a.b, (int64_t)blk * 1024 + threadIdx.x, a.tensor_id | 1u, a.n, a.r, a.RP, a.Vt); return; }
   blk -= a.nb_Vt;
-  if (blk < a.nb_P) { image_P_at((int64_t)blk * 1024 + threadIdx.x, a.P, a.R_cap, a.R_used, a.Rp, a.m, a.Ph); return; }
+  if (blk < a.nb_P) { image_P_at((int64_t)blk * 1024 + threadIdx.x, a.P, a.R_cap, a.R_used, a.tabs.RpT, a.m, a.m_img, a.Pimg); return; }
   blk -= a.nb_P;
   // Vbt[j][i] = Vb[i][j], one 32x32 tile per block, coalesced on both sides
   __shared__ float tile[32][33];
@@ -267,16 +325,17 @@ __global__ __launch_bounds__(1024) void k_probe_prep(ProbePrepArgs a) {
 
 hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables& tabs, uint32_t tensor_id, int m,
                                   int n, int r, int RP, int Rp, const float* P, const float* Vb, int R_cap,
-                                  int R_used, uint16_t* Uh, uint16_t* Vt, uint16_t* Ph, uint16_t* Vbt,
+                                  int R_used, int m_img, uint16_t* Uimg, uint16_t* Vt, uint16_t* Pimg, uint16_t* Vbt,
                                   hipStream_t st) {
   ProbePrepArgs a;
   a.b = b; a.eps = eps; a.tabs = tabs; a.tensor_id = tensor_id; a.m = m; a.n = n; a.r = r; a.RP = RP; a.Rp = Rp;
-  a.P = P; a.Vb = Vb; a.R_cap = R_cap; a.R_used = R_used; a.Uh = Uh; a.Vt = Vt; a.Ph = Ph; a.Vbt = Vbt;
+  a.P = P; a.Vb = Vb; a.R_cap = R_cap; a.R_used = R_used; a.Uimg = Uimg; a.Vt = Vt; a.Pimg = Pimg; a.Vbt = Vbt;
+  a.m_img = m_img;
   auto blocks = [](int64_t n_elems) { return (int)((n_elems + 1023) / 1024); };
   a.nb_tok = blocks(b.T);
-  a.nb_U = blocks((int64_t)b.K * m * (RP / 4));
+  a.nb_U = blocks((int64_t)b.K * m_img * (tabs.SPD * 8));
   a.nb_Vt = blocks((int64_t)b.K * n * (RP / 4));
-  a.nb_P = Rp > 0 ? blocks((int64_t)m * Rp) : 0;
+  a.nb_P = Rp > 0 ? blocks((int64_t)m_img * tabs.RpT * 64) : 0;
   a.vbt_tiles_n = (n + 31) / 32;
   a.nb_Vbt = Rp > 0 ? a.vbt_tiles_n * ((Rp + 31) / 32) : 0;
   const int64_t total = 1 + (int64_t)a.nb_tok + a.nb_U + a.nb_Vt + a.nb_P + a.nb_Vbt;

@@ -36,11 +36,11 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   // Vb stage: [half h of the K step][16-col block][col][4 chunks of 16 B], chunk index XOR (col>>2)&3
   __shared__ __attribute__((aligned(1024))) char s_vb[2][NBB > 0 ? NBB * 2048 : 16];
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  // The grid is sized for the worst case (most items, largest k-split); the k-split and the number
-  // of items are known on the device.  Block b is (group b / ksplit, split b % ksplit), so the blocks
-  // without work are the last ones of the grid and are dispatched after every block that has some.
+  // The grid is sized for the largest possible number of items; their number is known on the device.
+  // Block b is (group b / ksplit, split b % ksplit), so the blocks without work are the last ones of the
+  // grid and are dispatched after every block that has some.
   const int n_items = a.n_items[0];
-  const int ksplit = a.n_items[1];
+  const int ksplit = a.ksplit;
   const int group = blockIdx.x / ksplit, split = blockIdx.x - group * ksplit;
   if (group * 4 >= n_items) return;
   const int item_raw = group * 4 + wave;
@@ -137,7 +137,9 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   }
   if (!live) return;
 
-  const bool fg = it.kind == kKindForeground;
+  // Rows of foreground sequences get no partial sums: the finishing kernel writes their zeros without
+  // reading any.  Neither do the direction columns of a centre item.
+  if (it.kind == kKindForeground) return;
   const int ndir_cols = a.RP;
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) {
@@ -148,17 +150,9 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
       const int64_t row = it.row0 + lrow;
 #pragma unroll
       for (int cb = 0; cb < NBB + 1; ++cb) {
-        if (cb == 0 && !kDir) continue;
+        if (cb == 0 && (!kDir || !has_dir)) continue;
         const int col = cb == 0 ? lr : ndir_cols + (cb0 + cb - 1) * 16 + lr;
-        const float x = acc[rb][cb][v];
-        if (ksplit == 1) {
-          float y = x;
-          if (cb == 0) y = has_dir ? it.scale * x : 0.0f;
-          if (fg) y = 0.0f;
-          a.Aside[row * NC + col] = f32_to_bf16(y);
-        } else if (!fg) {   // the reduction kernel writes the zeros of foreground rows without reading partials
-          a.partial[((int64_t)split * a.T + row) * NC + col] = x;
-        }
+        a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][cb][v];
       }
     }
   }
@@ -170,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
 template <int NDB>
 __global__ __launch_bounds__(256) void k_side_down_dirblocks(SideDownArgs a, int cbd0) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int ksplit = a.n_items[1];
+  const int ksplit = a.ksplit;
   const int group = blockIdx.x / ksplit, split = blockIdx.x - group * ksplit;
   const int item = group * 4 + wave;
   if (item >= a.n_items[0]) return;
@@ -181,12 +175,13 @@ __global__ __launch_bounds__(256) void k_side_down_dirblocks(SideDownArgs a, int
   const int q = steps_total / ksplit, rem = steps_total - q * ksplit;
   const int k_begin = (split * q + min(split, rem)) * 64, kchunk = (q + (split < rem ? 1 : 0)) * 64;
   const bool has_dir = it.kind >= 0;
+  if (!has_dir) return;   // centre and foreground rows have no direction columns
   f32x4 acc[4][NDB];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
     for (int b = 0; b < NDB; ++b) acc[rb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-  if (has_dir) {
+  {
     const bf16_t* pv = a.Vt + ((int64_t)it.kind * a.RP + cbd0 * 16 + lr) * a.n + k_begin + lg * 8;
     const bf16_t* pa[4];
 #pragma unroll
@@ -213,37 +208,66 @@ __global__ __launch_bounds__(256) void k_side_down_dirblocks(SideDownArgs a, int
       if (lrow >= it.nrows) continue;
       const int64_t row = it.row0 + lrow;
 #pragma unroll
-      for (int b = 0; b < NDB; ++b) {
-        const int col = (cbd0 + b) * 16 + lr;
-        if (ksplit == 1) a.Aside[row * NC + col] = f32_to_bf16(has_dir ? it.scale * acc[rb][b][v] : 0.0f);
-        else a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][b][v];
-      }
+      for (int b = 0; b < NDB; ++b)
+        a.partial[((int64_t)split * a.T + row) * NC + (cbd0 + b) * 16 + lr] = acc[rb][b][v];
     }
 }
 
-// Fixed-order sum of the k-split partials, scaling and rounding to bf16.  Without a split the
-// side-down pass has written Aside itself.
-__global__ void k_side_reduce(SideDownArgs a) {
-  const int ksplit = a.n_items[1];
-  if (ksplit == 1) return;
+// Finishes the side-down pass: sums the K-range partials of every candidate row in range order, scales the
+// direction columns by sign * eps, rounds to bf16 and writes the token-side images of the GEMM's side K
+// tiles: pool K tile p = [256 rows of its token tile][64 columns].  Direction K tile j of a tile holds the
+// slots 2j and 2j+1 (32 columns each): a row has its own direction's block there and zeros in every other
+// slot; the bank K tiles follow.  Rows of foreground sequences, rows past the end of the batch and unused
+// columns are zero.  One workgroup per (pool K tile, 32 rows); a thread writes 8 columns (16 bytes).
+__global__ __launch_bounds__(256) void k_side_finish(SideDownArgs a) {
+  const int p = blockIdx.x >> 3;
+  if (p >= a.n_items[1]) return;
+  const int tn = a.kt_tile[p];
+  const TileHdr h = a.tile_hdr[tn];
+  const int j = p - h.kt0;
+  const int rr = (blockIdx.x & 7) * 32 + (threadIdx.x >> 3), c = threadIdx.x & 7;
+  const int row = tn * kTileN + rr;
   const int NC = a.RP + a.Rp;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= (int64_t)a.T * NC) return;
-  const int row = (int)(idx / NC), col = (int)(idx % NC);
-  const int s = a.tok_seq[row];
-  const int kind = a.seq_kind[s];
-  float y = 0.0f;
-  const bool live = (col < a.RP) ? (kind >= 0) : (kind >= kKindCentre);
-  if (live) {
-    for (int sp = 0; sp < ksplit; ++sp) y += a.partial[((int64_t)sp * a.T + row) * NC + col];
-    if (col < a.RP) y *= a.seq_scale[s];
+  const int n_dir_kt = (h.n_slots + 1) >> 1;
+  float y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (row < a.T) {
+    const int s = a.tok_seq[row];
+    const int kind = a.seq_kind[s];
+    int col = -1, ncol = 0;   // first partial column behind this thread's 8 values, how many of them exist
+    float scale = 1.0f;
+    if (j < n_dir_kt) {
+      const int slot = 2 * j + (c >> 2);
+      if (kind >= 0 && slot < h.n_slots) {
+        const int e = a.tile_slots[h.slot0 + slot];
+        if (e / a.SPD == kind) {
+          col = (e % a.SPD) * 32 + (c & 3) * 8;
+          ncol = min(8, a.RP - col);
+          scale = a.seq_scale[s];
+        }
+      }
+    } else if (kind >= kKindCentre) {
+      const int bcol = (j - n_dir_kt) * 64 + c * 8;
+      col = a.RP + bcol;
+      ncol = min(8, a.Rp - bcol);
+    }
+    if (ncol > 0) {
+      for (int sp = 0; sp < a.ksplit; ++sp) {
+        const float4* src = reinterpret_cast<const float4*>(a.partial + ((int64_t)sp * a.T + row) * NC + col);
+        const float4 u = src[0], w = src[1];   // RP and Rp are multiples of 16: all 8 exist
+        y[0] += u.x; y[1] += u.y; y[2] += u.z; y[3] += u.w;
+        y[4] += w.x; y[5] += w.y; y[6] += w.z; y[7] += w.w;
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) y[e] *= scale;
+    }
   }
-  a.Aside[idx] = f32_to_bf16(y);
+  u32x4 out = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+  *reinterpret_cast<u32x4*>(a.Xs + ((int64_t)p * kTileN + rr) * kTileK + c * 8) = out;
 }
 
 template <int NBB, bool kDir>
 static void launch_pass(const SideDownArgs& a, int cb0, hipStream_t st) {
-  dim3 grid(a.ks_cap * ((a.max_items + 3) / 4));
+  dim3 grid(a.ksplit * ((a.max_items + 3) / 4));
   hipLaunchKernelGGL((k_side_down<NBB, kDir>), grid, dim3(256), 0, st, a, cb0);
 }
 
@@ -274,7 +298,7 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
     done += nb;
   }
   for (int cbd = 1; cbd < a.RP / 16;) {   // ranks above 16: up to 8 further direction blocks per pass over X
-    dim3 grid(a.ks_cap * ((a.max_items + 3) / 4));
+    dim3 grid(a.ksplit * ((a.max_items + 3) / 4));
     const int left = a.RP / 16 - cbd;
     if (left >= 8) { hipLaunchKernelGGL(k_side_down_dirblocks<8>, grid, dim3(256), 0, st, a, cbd); cbd += 8; }
     else if (left >= 4) { hipLaunchKernelGGL(k_side_down_dirblocks<4>, grid, dim3(256), 0, st, a, cbd); cbd += 4; }
@@ -283,11 +307,17 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.ks_cap > 1) {
-    const int64_t total = (int64_t)a.T * (a.RP + a.Rp);
-    hipLaunchKernelGGL(k_side_reduce, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, a);
-  }
+  hipLaunchKernelGGL(k_side_finish, dim3((unsigned)a.kt_cap * 8u), dim3(256), 0, st, a);
   return hipGetLastError();
+}
+
+// K ranges per row: ranges of about 2560 columns for wide inputs, four ranges up to 8192 columns, never
+// narrower than 512 columns, whole 64-column steps.
+int side_ksplit(int n) {
+  int s = n <= 8192 ? 4 : (n + 1280) / 2560;
+  if (s > 8) s = 8;
+  while (s > 1 && n / s < 512) --s;
+  return s < 1 ? 1 : s;
 }
 
 }  // namespace zo

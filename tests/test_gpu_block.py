@@ -282,7 +282,7 @@ def test_block_fp32_stage_by_stage_and_end_to_end():
 
 def test_block_foreground_rows_bit_identical():
     """Foreground sequences of a mixed batch must come out of the block exactly as from a batch
-    in which every sequence is foreground (Sec. 4, mixed-batch experiment)."""
+    in which every sequence is foreground (Sec. 5.4 and the mixed-batch correctness appendix)."""
     batch = _small_batch([70, 131, 9, 200, 140], 2, 2)
     w = wl.decoder_block("blk-mixed", 60, "bf16", 256, 2, 2, 128, 512, 0, True, 8, 1e-3, 32, batch)
     d = DeviceWorkload(w, DEV)

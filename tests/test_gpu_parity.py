@@ -412,7 +412,7 @@ def test_scoring_only_active_tokens():
 
 
 def test_es_style_one_sided_candidates():
-    """N one-sided candidates around a centre (Sec. 4, the evolution-strategies shape): the probe path
+    """N one-sided candidates around a centre (Sec. 2.2 and Sec. 5.3, the evolution-strategies shape): the probe path
     evaluates them like any other candidate table; zo_estimate_es turns the losses into normalised-reward
     coefficients.  Checked against the oracle on the GPU's own candidate sums and end to end."""
     import copy
