@@ -205,6 +205,7 @@ int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh,
                  float* cand_sum, int32_t* cand_cnt,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+
 /*
  * Antithetic two-point estimate (Sec. 2.1, Eq. 2):
  *   cand_loss[c] = cand_sum[c] / max(cand_cnt[c], 1)   (reduction 0, mean)

@@ -8,7 +8,42 @@
 #include <string>
 
 #include "../../include/zo.h"
+#include "zo_host.hpp"
 #include "zo_internal.hpp"
+
+namespace zo {
+
+// ---- launch planning of the side-down pass (host only) ------------------------------------
+// K ranges per row: ranges of about 2560 columns for wide inputs, four ranges up to 8192 columns, never
+// narrower than 512 columns, whole 64-column steps.
+int side_ksplit(int n) {
+  int s = n <= 8192 ? 4 : (n + 1280) / 2560;
+  if (s > 8) s = 8;
+  while (s > 1 && n / s < 512) --s;
+  return s < 1 ? 1 : s;
+}
+
+// Rows per item (64, 48, 32 or 16; how rows are grouped into items does not enter any row's arithmetic).  The
+// workgroups of a pass (eight items each, times the K ranges) run in rounds of one workgroup per compute
+// unit.  A workgroup's time per K step has a part that grows with its items' rows (their bytes of X) and a
+// part that does not (fetching the V and Vb fragments from LDS: about two rows' worth per 16 bank
+// columns): the size that makes rounds x time smallest, the larger one on a tie (it re-reads V less often).
+int side_item_rows(int T, int n, int R) {
+  const int cus = compute_units();
+  const int ks = side_ksplit(n);
+  const int fixed = 2 * ((R + 15) / 16);
+  static const int kSizes[4] = {64, 48, 32, 16};
+  int best = kSideRows;
+  int64_t best_cost = -1;
+  for (int rows : kSizes) {
+    const int64_t wgs = (int64_t)((T + rows * kSideWaves - 1) / (rows * kSideWaves)) * ks;
+    const int64_t cost = ((wgs + cus - 1) / cus) * (rows + fixed);
+    if (best_cost < 0 || cost < best_cost) { best = rows; best_cost = cost; }
+  }
+  return best;
+}
+
+}  // namespace zo
 
 namespace {
 
@@ -89,7 +124,7 @@ zo::BatchDev to_dev(const zo_batch* b) {
 
 // ---- workspace plans --------------------------------------------------------------------
 struct ProbePlan {
-  int RP = 0, Rp = 0, max_items = 0, ksplit = 1;
+  int RP = 0, Rp = 0, max_items = 0, item_rows = zo::kSideRows, ksplit = 1;
   int SPD = 0, RpT = 0, n_tn = 0, slot_cap = 0, kt_cap = 0, m_img = 0;   // side K tiles of the bf16 GEMM
   size_t uimg_bytes = 0, pimg_bytes = 0, xs_bytes = 0;
   size_t seq_kind, seq_scale, tok_seq, n_items, items;
@@ -105,8 +140,10 @@ ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype d
   p.seq_scale = c.take((size_t)S * 4);
   p.tok_seq = c.take((size_t)T * 4);
   p.n_items = c.take(16);
-  p.max_items = (T + zo::kSideRows - 1) / zo::kSideRows + S;
-  p.items = c.take((size_t)p.max_items * sizeof(zo::SideItem));
+  p.item_rows = dt == ZO_BF16 ? zo::side_item_rows(T, n, R) : zo::kSideRows;
+  p.max_items = (T + p.item_rows - 1) / p.item_rows + S;
+  // (sized for the smallest items, so that a workspace sized for a large batch also serves a smaller one)
+  p.items = c.take(((size_t)(T + 15) / 16 + S) * sizeof(zo::SideItem));
   if (dt == ZO_BF16) {
     p.RP = round16(r);
     p.Rp = round16(R);
@@ -274,6 +311,7 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
   tabs.items = (zo::SideItem*)(ws + plan.items);
   tabs.n_items = (int32_t*)(ws + plan.n_items);
   tabs.max_items = plan.max_items;
+  tabs.item_rows = plan.item_rows;
   tabs.tile_hdr = nullptr; tabs.tile_slots = nullptr; tabs.kt_tile = nullptr;
   tabs.n_tn = plan.n_tn; tabs.slot_cap = plan.slot_cap; tabs.kt_cap = plan.kt_cap; tabs.SPD = plan.SPD; tabs.RpT = plan.RpT;
   // a batch without candidates (or probes and bank both absent) is a plain GEMM
@@ -303,7 +341,7 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
       zo::SideDownArgs sd;
       sd.X = (const uint16_t*)X; sd.ldx = ldx; sd.Vt = Vt; sd.Vbt = Vbt;
       sd.n = n; sd.RP = plan.RP; sd.Rp = plan.Rp; sd.T = T;
-      sd.items = tabs.items; sd.n_items = tabs.n_items; sd.max_items = plan.max_items;
+      sd.items = tabs.items; sd.n_items = tabs.n_items; sd.max_items = plan.max_items; sd.item_rows = plan.item_rows;
       sd.ksplit = plan.ksplit; sd.partial = (float*)(ws + plan.partial);
       sd.tok_seq = tabs.tok_seq; sd.seq_kind = tabs.seq_kind; sd.seq_scale = tabs.seq_scale;
       sd.tile_hdr = tabs.tile_hdr; sd.tile_slots = tabs.tile_slots; sd.kt_tile = tabs.kt_tile;
@@ -338,10 +376,12 @@ size_t zo_score_workspace_bytes(int32_t n_tokens, int32_t n_seqs, int32_t vocab,
   return plan_score(n_tokens, n_seqs, vocab, dtype).total;
 }
 
-int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh, const void* W_head, int64_t ldw,
-                 int32_t vocab, int32_t d, zo_dtype dtype, const int32_t* targets, float* tok_nll,
-                 float* seq_nll, float* cand_sum, int32_t* cand_cnt, void* workspace, size_t workspace_bytes,
-                 void* stream) {
+}  // extern "C"
+
+// Everything zo_score checks before it looks at its workspace (no HIP call).
+int32_t zo::score_validate(const zo_batch* batch, const void* H, int64_t ldh, const void* W_head, int64_t ldw,
+                           int32_t vocab, int32_t d, zo_dtype dtype, const int32_t* targets, const float* seq_nll,
+                           const float* cand_sum, const int32_t* cand_cnt) {
   if (int32_t st = check_batch(batch)) return st;
   if (vocab < 1 || d < 1) return fail(ZO_ERR_SHAPE, "vocab = %d, d = %d", vocab, d);
   if (dtype != ZO_F32 && dtype != ZO_BF16) return fail(ZO_ERR_UNSUPPORTED, "dtype %d", (int)dtype);
@@ -355,6 +395,20 @@ int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh, const void* 
     if (dtype == ZO_BF16 && d % zo::kTileK != 0)
       return fail(ZO_ERR_UNSUPPORTED, "bf16 path needs d %% %d == 0 (d = %d)", zo::kTileK, d);
   }
+  return ZO_OK;
+}
+
+int32_t zo::fail_status(int32_t status, const char* message) { return fail((zo_status)status, "%s", message); }
+
+extern "C" {
+
+int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh, const void* W_head, int64_t ldw,
+                 int32_t vocab, int32_t d, zo_dtype dtype, const int32_t* targets, float* tok_nll,
+                 float* seq_nll, float* cand_sum, int32_t* cand_cnt, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  if (int32_t st = zo::score_validate(batch, H, ldh, W_head, ldw, vocab, d, dtype, targets, seq_nll, cand_sum, cand_cnt))
+    return st;
+  const int T = batch->n_tokens, S = batch->n_seqs, C = batch->n_cands;
   const ScorePlan plan = plan_score(T, S, vocab, dtype);
   if (plan.total > 0) {
     if (!workspace) return fail(ZO_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total);

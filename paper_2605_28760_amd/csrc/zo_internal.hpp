@@ -14,7 +14,8 @@ constexpr int kTileM = 256;
 constexpr int kTileN = 256;
 constexpr int kTileK = 64;
 constexpr int kMaxRank = 512;     // largest probe rank r (the rank continuum of Sec. 3.3 goes up to 512)
-constexpr int kSideRows = 64;     // rows per side-down work item (one wave)
+constexpr int kSideRows = 64;     // most rows of a side-down work item (one wave); small batches use 32 or 16
+constexpr int kSideWaves = 8;    // waves (items) per workgroup of the side-down pass
 constexpr int kSideMaxBlocks = 9; // 16-column blocks a side-down wave accumulates at once
 constexpr int kSimtTile = 64;     // tile edge of the fp32 vector-ALU kernels
 
@@ -54,6 +55,7 @@ struct SeqTables {
   SideItem* items;     // [max_items]
   int32_t* n_items;    // [2]: number of side-down items, number of pool K tiles in use
   int32_t max_items;
+  int32_t item_rows;   // rows per side-down item: 64, 48, 32 or 16
   // per token tile (null tile_hdr: not wanted)
   TileHdr* tile_hdr;   // [n_tn]
   int32_t* tile_slots; // [slot_cap]: block of the U image (direction * SPD + 32-column block) behind a slot
@@ -105,6 +107,7 @@ struct SideDownArgs {
   const uint16_t* Vbt;              // [Rp][n]
   int n, RP, Rp, T;
   const SideItem* items; const int32_t* n_items; int max_items;
+  int item_rows;                    // rows per item: 64, 48, 32 or 16
   int ksplit;                       // >= 1: K ranges per row, a function of n alone (side_ksplit)
   float* partial;                   // [ksplit][T][RP+Rp] partial sums of one K range each
   const int32_t* tok_seq; const int32_t* seq_kind; const float* seq_scale;
@@ -116,6 +119,9 @@ struct SideDownArgs {
 // K ranges of the side-down pass for an input width n: never a function of the batch, so that the
 // summation order of a row's side term does not depend on what else is in the batch.
 int side_ksplit(int n);
+// Rows per side-down work item (64, 48, 32 or 16) for a batch of T rows, input width n and bank rank R; how rows
+// are grouped into items does not enter any row's arithmetic.
+int side_item_rows(int T, int n, int R);
 // sequence tables, token -> sequence map and the four operand images of a bf16 probe linear in one launch
 hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables& tabs, uint32_t tensor_id, int m,
                                   int n, int r, int RP, int Rp, const float* P, const float* Vb, int R_cap,

@@ -98,7 +98,7 @@ __device__ __forceinline__ int block_scan_1024(int v, int* s_scan, int* total) {
 }
 
 // Per-sequence kind / scale, the list of side-down work items (chunks of at
-// most kSideRows rows of one sequence) and, for the bf16 GEMM, the side K tiles of
+// most item_rows rows of one sequence) and, for the bf16 GEMM, the side K tiles of
 // every token tile.  One workgroup; sequences and tiles are scanned in blocks of
 // 1024 so the item order follows the row order.
 __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, const SeqTables& t) {
@@ -121,15 +121,15 @@ __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, c
       }
       t.seq_kind[s] = kind;
       t.seq_scale[s] = scale;
-      nchunk = (len + kSideRows - 1) / kSideRows;
+      nchunk = (len + t.item_rows - 1) / t.item_rows;
     }
     int total;
     const int first = carry + block_scan_1024(nchunk, s_scan, &total);
     for (int j = 0; j < nchunk; ++j) {
       if (first + j < t.max_items) {
         SideItem it;
-        it.row0 = row0 + j * kSideRows;
-        it.nrows = min(kSideRows, len - j * kSideRows);
+        it.row0 = row0 + j * t.item_rows;
+        it.nrows = min(t.item_rows, len - j * t.item_rows);
         it.kind = kind;
         it.scale = scale;
         t.items[first + j] = it;

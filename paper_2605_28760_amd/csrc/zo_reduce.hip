@@ -242,31 +242,62 @@ hipError_t launch_estimate_es(const BatchDev& b, const float* cand_sum, const in
 constexpr int kBankBatch = 32;
 struct BankCols { int32_t first_dir; int32_t n; int32_t col0[kBankBatch]; };
 
-// Entry idx of direction kb (within the batch `cols`) of one layer's update.
-__device__ __forceinline__ void bank_update_entry(const BankUpdateArgs& a, const BankCols& cols, int kb, int64_t idx) {
+// Four consecutive entries 4q .. 4q+3 of a [rows x r] factor stream scaled into `dst` (a row-major matrix
+// of pitch R_cap, the factor's block starting at column col0): dst = beta * f (set) or dst += beta * f.
+// One Philox block yields the four normals.  When the rank is a multiple of 4 the four entries are
+// neighbours in one row, and if the block is 16-byte aligned they move as one float4.
+template <bool kAccumulate>
+__device__ __forceinline__ void bank_quad(float* M, int R_cap, int col0, int rows, int r, uint64_t seed, uint32_t tid,
+                                          int64_t q, float beta, bool bf16) {
+  const int64_t e0 = q * 4, total = (int64_t)rows * r;
+  if (e0 >= total) return;
+  const uint4 w = factor_block(seed, tid, (uint64_t)q);
+  float z[4];
+  box_muller(w.x, w.y, z[0], z[1]);
+  box_muller(w.z, w.w, z[2], z[3]);
+#pragma unroll
+  for (int l = 0; l < 4; ++l) {
+    if (bf16) z[l] = bf16_round(z[l]);
+    z[l] *= beta;
+  }
+  const int i = (int)(e0 / r), j = (int)(e0 % r);
+  float* dst = M + (int64_t)i * R_cap + col0 + j;
+  if ((r & 3) == 0 && (((uintptr_t)dst) & 15u) == 0) {
+    float4 v = make_float4(z[0], z[1], z[2], z[3]);
+    if (kAccumulate) {
+      const float4 old = *reinterpret_cast<const float4*>(dst);
+      v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+    }
+    *reinterpret_cast<float4*>(dst) = v;
+    return;
+  }
+#pragma unroll
+  for (int l = 0; l < 4; ++l) {
+    const int64_t e = e0 + l;
+    if (e >= total) break;
+    float* d1 = M + (e / r) * R_cap + col0 + (int)(e % r);
+    *d1 = kAccumulate ? *d1 + z[l] : z[l];
+  }
+}
+
+// Quad q of direction kb (within the batch `cols`) of one layer's update.
+__device__ __forceinline__ void bank_update_entry(const BankUpdateArgs& a, const BankCols& cols, int kb, int64_t q) {
   const int k = cols.first_dir + kb;
   // block and mode: from the host (by value) or from the device-resident schedule
   const int col0 = a.sched ? (a.sched->block * a.n_dirs + k) * a.r : cols.col0[kb];
   const bool append = a.sched ? a.sched->append != 0 : a.append != 0;
   if (col0 < 0 || col0 + a.r > a.R_cap) return;
-  if (idx < (int64_t)a.m * a.r) {
-    const int i = (int)(idx / a.r), j = (int)(idx % a.r);
-    const float w = a.dir_weight ? a.dir_weight[k] : a.default_weight;
-    const float beta = -a.lr * a.proj_grad[k] * w;
-    float u = factor_normal(a.seed[k], a.tensor_id & ~1u, (uint64_t)idx);
-    if (a.bf16) u = bf16_round(u);
-    float* dst = a.P + (int64_t)i * a.R_cap + col0 + j;
-    *dst = append ? beta * u : fmaf(beta, u, *dst);
-  }
-  if (append && idx < (int64_t)a.n * a.r) {
-    const int i = (int)(idx / a.r), j = (int)(idx % a.r);
-    float v = factor_normal(a.seed_v ? a.seed_v[k] : a.seed[k], a.tensor_id | 1u, (uint64_t)idx);
-    if (a.bf16) v = bf16_round(v);
-    a.Vb[(int64_t)i * a.R_cap + col0 + j] = v;
+  const float w = a.dir_weight ? a.dir_weight[k] : a.default_weight;
+  const float beta = -a.lr * a.proj_grad[k] * w;
+  if (append) {
+    bank_quad<false>(a.P, a.R_cap, col0, a.m, a.r, a.seed[k], a.tensor_id & ~1u, q, beta, a.bf16);
+    bank_quad<false>(a.Vb, a.R_cap, col0, a.n, a.r, a.seed_v ? a.seed_v[k] : a.seed[k], a.tensor_id | 1u, q, 1.0f, a.bf16);
+  } else {
+    bank_quad<true>(a.P, a.R_cap, col0, a.m, a.r, a.seed[k], a.tensor_id & ~1u, q, beta, a.bf16);
   }
 }
 
-// grid.y = direction within the batch; grid.x covers max(m, n) * r entries.
+// grid.y = direction within the batch; grid.x covers the quads of max(m, n) * r entries.
 __global__ void k_bank_update(BankUpdateArgs a, BankCols cols) {
   bank_update_entry(a, cols, blockIdx.y, (int64_t)blockIdx.x * blockDim.x + threadIdx.x);
 }
@@ -281,7 +312,7 @@ __global__ void k_bank_update_multi(BankUpdateArgs a, BankCols cols, BankLayerSe
 
 hipError_t launch_bank_update(const BankUpdateArgs& a, int n_dirs, const int32_t* col0, hipStream_t st) {
   const int rows = (a.append || a.sched) ? (a.m > a.n ? a.m : a.n) : a.m;
-  const int64_t total = (int64_t)rows * a.r;
+  const int64_t total = ((int64_t)rows * a.r + 3) / 4;   // quads: a thread takes four entries
   if (total == 0) return hipSuccess;
   for (int first = 0; first < n_dirs; first += kBankBatch) {
     BankCols cols;
@@ -305,7 +336,7 @@ hipError_t launch_bank_update_multi(const BankUpdateArgs& common, const BankLaye
       set.l[i] = layers[l0 + (i < nl ? i : 0)];
       const BankLayer& l = set.l[i];
       const int rows = common.append ? (l.m > l.n ? l.m : l.n) : l.m;
-      if (i < nl && (int64_t)rows * common.r > total) total = (int64_t)rows * common.r;
+      if (i < nl && ((int64_t)rows * common.r + 3) / 4 > total) total = ((int64_t)rows * common.r + 3) / 4;
     }
     if (total == 0) continue;
     for (int first = 0; first < n_dirs; first += kBankBatch) {

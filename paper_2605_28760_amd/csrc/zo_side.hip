@@ -1,16 +1,21 @@
 // Side-down projection: the "A = V^T" half of the LoRA-style side state of
 // Sec. 3.2.  For every candidate row t it forms
-//     Aside[t, :] = [ s_t eps (X[t,:] V_{k_t})  |  X[t,:] Vb ]        (bf16)
-// which the probe GEMM then multiplies by [U_{k_t} | P]^T.  The kernel streams
-// X once and is bound by HBM bandwidth; the skinny contraction runs on
-// v_mfma_f32_16x16x32_bf16 so that the arithmetic (about 2 (r + R) flop per
-// byte of X) stays out of the way.
+//     [ X[t,:] V_{k_t}  |  X[t,:] Vb ]
+// as fp32 partial sums over a few K ranges; a finishing kernel sums the ranges,
+// scales the direction part by s_t eps, rounds to bf16 and lays the rows out as
+// the token-side operand of the probe GEMM's side K tiles, which multiply them
+// by [U_{k_t} | P]^T.  The pass streams X once and is bound by HBM bandwidth;
+// the skinny contraction runs on v_mfma_f32_16x16x32_bf16 so that the
+// arithmetic (about 2 (r + R) flop per byte of X) stays out of the way.
 //
-// Work items are chunks of at most 64 rows of one sequence, so all rows of an
-// item share one direction.  One wave per (item, k-split); the four waves of a
-// workgroup walk the same K range, so the bank operand Vb is staged once per
-// workgroup in LDS (direct-to-LDS loads, double buffered) while each wave keeps
-// its own rows of X and its own direction's V in registers.
+// Work items are chunks of at most 64 (or 32, or 16: small batches get smaller
+// items so that the chip is still filled) rows of one sequence, so all rows of
+// an item share one direction.  One wave per (item, K range); the eight waves
+// of a workgroup walk the same K range in steps of 64 columns, so the bank
+// operand Vb is staged once per workgroup in LDS.  A wave's rows of X land in
+// its own two-stage ring in LDS (direct-to-LDS loads of whole 128-byte lines,
+// no registers tied up by bytes in flight): while a wave multiplies step s, the
+// lines of steps s+1 and s+2 are on their way.
 #include <type_traits>
 
 #include "zo_device.hpp"
@@ -19,34 +24,46 @@
 namespace zo {
 
 typedef __attribute__((address_space(3))) void lds_void;
+constexpr int kNonTemporal = 2;   // cache-policy operand of a buffer load: the nt bit
 
 // 16x16x32 bf16 MFMA: A fragment = 16 rows x 32 k (lane l: row l%16, k = 8*(l/16)..+7),
 // B fragment = 32 k x 16 cols (lane l: col l%16, same k), D: lane l holds rows 4*(l/16)+v, col l%16.
+// Here the columns of V take the A side and the rows of X the B side: D[column of V][row of X].
 //
-// NBB = number of 16-column bank blocks this pass accumulates; kDir = whether the pass
-// also carries the (single) 16-column direction block.  cb0 = first bank block of the pass.
+// NBB = number of 16-column bank blocks this pass accumulates (cb0 = the first of them); kDir = whether
+// the pass also carries the first 16-column direction block; RB = 16-row blocks of an item.
 //
-// One K step of 64: a wave issues the loads of its 64 rows (8 KiB) and of its direction's V, the
-// workgroup's Vb slice goes to one of two alternating LDS stages, everybody waits, one barrier,
-// multiply.  Measured alternatives on this part: keeping a second step of X in flight in registers
-// is slower (3.0 against 4.3 TB/s: the loads of a step already fill the memory pipeline), as are
-// steps of 32 or 128, items of 16 or 32 rows, and a third workgroup per CU (register spills).
-template <int NBB, bool kDir>
-__global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
-  // Vb stage: [half h of the K step][16-col block][col][4 chunks of 16 B], chunk index XOR (col>>2)&3
-  __shared__ __attribute__((aligned(1024))) char s_vb[2][NBB > 0 ? NBB * 2048 : 16];
+// LDS: [wave][2 stages][RB*16 rows][128 B] rings of X, then [2 stages][NBB blocks][2 halves][1 KiB] of Vb.
+// A row of a ring stage holds its eight 16-byte chunks XOR-swizzled by (row >> 1) & 7, which makes the
+// fragment reads (16 rows x 4 chunks per instruction) conflict-free.
+//
+// One step of a wave: wait for the step's lines (leaving the next step's in flight), barrier (the
+// step's Vb stage is complete, and every wave is done with the other stage), request the next step's
+// Vb stage and V fragments, read the step's X fragments into registers, request the lines of the step
+// after next into the ring stage just read, multiply.
+template <int NBB, bool kDir, int RB, int W>
+__global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  constexpr int kRing = RB * 2048;                   // one ring stage: RB*16 rows x 128 B
+  constexpr int kVbStage = (NBB > 0 ? NBB : 1) * 2048;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  char* ring = lds + wave * 2 * kRing;
+  char* s_vb = lds + W * 2 * kRing;
+  char* s_vd = s_vb + 2 * kVbStage + wave * 2048;   // this wave's direction block of V: one stage
   // The grid is sized for the largest possible number of items; their number is known on the device.
   // Block b is (group b / ksplit, split b % ksplit), so the blocks without work are the last ones of the
   // grid and are dispatched after every block that has some.
   const int n_items = a.n_items[0];
   const int ksplit = a.ksplit;
   const int group = blockIdx.x / ksplit, split = blockIdx.x - group * ksplit;
-  if (group * 4 >= n_items) return;
-  const int item_raw = group * 4 + wave;
+  if (group * W >= n_items) return;
+  const int item_raw = group * W + wave;
   const bool live = item_raw < n_items;
   // waves without an item still take part in the workgroup's Vb loads and barriers
-  const SideItem it = a.items[live ? item_raw : n_items - 1];
+  SideItem it = a.items[live ? item_raw : n_items - 1];
+  it.row0 = __builtin_amdgcn_readfirstlane(it.row0);
+  it.nrows = __builtin_amdgcn_readfirstlane(it.nrows);
+  it.kind = __builtin_amdgcn_readfirstlane(it.kind);
   const int NC = a.RP + a.Rp;
   const int lr = lane & 15, lg = lane >> 4;
   // each split walks its own contiguous K range in steps of 64; the first (steps mod k-split) splits
@@ -58,80 +75,141 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   const int nsteps_all = q + (split < rem ? 1 : 0);
   const bool has_dir = kDir && it.kind >= 0;
   const bool work = live && it.kind != kKindForeground;   // wave-uniform; foreground rows are not read at all
-  // a workgroup whose four items are all foreground (or absent) has nothing to multiply: it skips the
-  // K loop and only writes its zeros
-  const bool wg_work = __syncthreads_or(work) != 0;
-
-  // per-lane addresses: 16 B at (row, k + h*32 + lg*8)
-  const bf16_t* pa[4];
+  // a workgroup whose items are all foreground (or absent) has nothing to multiply; every wave looks at
+  // all eight items itself (the whole LDS of the compute unit is taken by the rings and the Vb stages,
+  // which leaves no word for a workgroup-wide vote)
+  bool wg_work = false;
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb) {
-    const int row = it.row0 + min(rb * 16 + lr, it.nrows - 1);
-    pa[rb] = a.X + (int64_t)row * a.ldx + k_begin + lg * 8;
+  for (int w8 = 0; w8 < W; ++w8) {
+    const int i8 = group * W + w8;
+    if (i8 < n_items) wg_work = wg_work || __builtin_amdgcn_readfirstlane(a.items[i8].kind) != kKindForeground;
   }
-  // a centre item has no direction: read a valid address (its own X rows), discard the result
-  const bf16_t* pv = has_dir ? a.Vt + ((int64_t)it.kind * a.RP + lr) * a.n + k_begin + lg * 8 : pa[0];
+  const int nsteps = wg_work ? nsteps_all : 0;
+
+  // X -> ring: load j (0 .. 2*RB-1) covers rows 8j .. 8j+7; lane i lands at byte 16*i of its 1 KiB block:
+  // row 8j + i/8, physical chunk i%8 = logical chunk ^ ((row >> 1) & 7).  Rows past the item's end repeat
+  // its last row (their results are never stored).
+  const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(a.X + (int64_t)it.row0 * a.ldx), 0,
+      (int)min(((int64_t)(it.nrows - 1) * a.ldx + a.n) * 2, (int64_t)0x7FFFFFFF), 0x00020000);
+  uint32_t x_off[2 * RB];
+#pragma unroll
+  for (int j = 0; j < 2 * RB; ++j) {
+    const int row = 8 * j + (lane >> 3);
+    const int lch = (lane & 7) ^ ((row >> 1) & 7);
+    x_off[j] = (uint32_t)min(row, it.nrows - 1) * (uint32_t)(a.ldx * 2) + (uint32_t)(k_begin * 2 + lch * 16);
+  }
+  auto issue_x = [&](int step) {
+    if (!work) return;
+    char* dst = ring + (step & 1) * kRing;
+#pragma unroll
+    for (int j = 0; j < 2 * RB; ++j)
+      // non-temporal: a line of X is used once, and should not push V and Vb out of the L2
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (lds_void*)(dst + j * 1024), 16, (int)x_off[j], step * kstride * 2, 0,
+                                               kNonTemporal);
+  };
+  // fragment (rb, h) of a ring stage: row rb*16 + lr, logical chunk h*4 + lg
+  uint32_t a_off[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) a_off[h] = lr * 128 + (((h * 4 + lg) ^ ((lr >> 1) & 7)) << 4);
+
   // Vb -> LDS: load j (0 .. 2*NBB-1) = (half h = j & 1, block b = j >> 1); lane i fills byte 16*i of
   // the 1 KiB block: col i/4, physical chunk i%4 = logical chunk ^ ((col>>2)&3)
   const int vcol = lane >> 2;
   const int vchunk = (lane & 3) ^ ((vcol >> 2) & 3);
-  // (buffer loads: rows of Vbt from bank column cb0*16 on; the byte offset of this lane's first piece)
   const uint32_t vb_off = (uint32_t)((int64_t)vcol * a.n + k_begin + vchunk * 8) * 2u;
   const __amdgpu_buffer_rsrc_t vb_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(a.Vbt + (int64_t)cb0 * 16 * a.n), 0, (int)((int64_t)(NBB > 0 ? NBB : 1) * 16 * a.n * 2), 0x00020000);
   const uint32_t rd_off = lr * 64 + ((lg ^ ((lr >> 2) & 3)) << 4);
-
-  auto issue_vb = [&](int stage, int step) {
+  constexpr int kVbMine = (2 * NBB + W - 1) / W;   // Vb loads of one wave per step (at most)
+  auto issue_vb = [&](int step) {
+    char* dst = s_vb + (step & 1) * kVbStage;
 #pragma unroll
-    for (int j = 0; j < 2 * NBB; ++j) {
-      if ((j & 3) != wave) continue;
-      const int h = j & 1, b = j >> 1;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vb_rsrc, (lds_void*)(&s_vb[stage][0] + (h * NBB + b) * 1024), 16,
-                                               (int)vb_off, (b * 16 * a.n + step * kstride + h * 32) * 2, 0, 0);
+    for (int i = 0; i < kVbMine; ++i) {
+      const int j = wave + i * W;
+      if (j < 2 * NBB) {
+        const int h = j & 1, b = j >> 1;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(vb_rsrc, (lds_void*)(dst + (h * NBB + b) * 1024), 16, (int)vb_off,
+                                                 (b * 16 * a.n + step * kstride + h * 32) * 2, 0, 0);
+      }
     }
   };
-
-  f32x4 acc[4][NBB + 1];
+  // The item's own direction block of V^T goes through LDS as well, in the layout of a Vb block.  (No load of
+  // the loop returns into registers: for those the compiler places its own waits, and it counts the
+  // direct-to-LDS loads in flight as done, so such a wait would drain the whole prefetch.)  A centre item
+  // has no direction: it reads direction 0's block and discards the result.
+  const __amdgpu_buffer_rsrc_t vd_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)(a.Vt + (int64_t)(has_dir ? it.kind : 0) * a.RP * a.n), 0, (int)((int64_t)16 * a.n * 2), 0x00020000);
+  auto issue_v = [&](int step) {
+    if (!kDir || !work) return;
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb)
+    for (int h = 0; h < 2; ++h)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vd_rsrc, (lds_void*)(s_vd + h * 1024), 16, (int)vb_off,
+                                               (step * kstride + h * 32) * 2, 0, 0);
+  };
+
+  f32x4 acc[RB][NBB + 1];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int cb = 0; cb < NBB + 1; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Refilling stage (step+1)&1 is safe once a wave is past barrier `step`: every wave has then
-  // finished the MFMAs of step-1, the last reader of that stage.
-  const int nsteps = wg_work ? nsteps_all : 0;
+  // In program order a wave requests: X(0) Vb(0) V(0) X(1), then per step s: Vb(s+1) V(s+1) X(s+2).
+  // Memory returns in order, so "at most the 2*RB loads of X(s+1) outstanding" means step s has landed.
+  if (nsteps > 0) {
+    issue_x(0);
+    if (NBB > 0) issue_vb(0);
+    issue_v(0);
+    if (nsteps > 1) issue_x(1);
+  }
   for (int step = 0; step < nsteps; ++step) {
-    bf16x8 fa[2][4], fv[2];   // [half][row block], [half]
+    if (step + 1 < nsteps && work) {
+      if constexpr (RB == 4) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+      else if constexpr (RB == 3) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+      else if constexpr (RB == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    // (a bare barrier: __syncthreads() would also wait for every load in flight, the next step's included)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (step + 1 < nsteps && NBB > 0) issue_vb(step + 1);
+    bf16x8 fa[2][RB], fv[2];
     if (work) {
+      const char* st = ring + (step & 1) * kRing;
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) fa[h][rb] = load_frag(pa[rb] + step * kstride + h * 32);
-        if (kDir) fv[h] = load_frag(pv + step * kstride + h * 32);
+        for (int rb = 0; rb < RB; ++rb) fa[h][rb] = *(const bf16x8*)(st + rb * 2048 + a_off[h]);
+        if (kDir) fv[h] = *(const bf16x8*)(s_vd + h * 1024 + rd_off);
       }
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // both have been read: they can take what comes next
+      if (step + 1 < nsteps) issue_v(step + 1);
+      if (step + 2 < nsteps) issue_x(step + 2);
     } else {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int rb = 0; rb < 4; ++rb) fa[h][rb] = zero_frag();
+        for (int rb = 0; rb < RB; ++rb) fa[h][rb] = zero_frag();
         fv[h] = zero_frag();
       }
     }
-    if (NBB > 0) issue_vb(step & 1, step);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    const char* stage = &s_vb[step & 1][0];
+    const char* stage = s_vb + (step & 1) * kVbStage;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      bf16x8 fb[NBB > 0 ? NBB : 1];
 #pragma unroll
-      for (int b = 0; b < NBB; ++b) fb[b] = *(const bf16x8*)(stage + (h * NBB + b) * 1024 + rd_off);
+      for (int b = 0; b < NBB; ++b) {
+        const bf16x8 fb = *(const bf16x8*)(stage + (h * NBB + b) * 1024 + rd_off);
 #pragma unroll
-      for (int rb = 0; rb < 4; ++rb) {
-        if (kDir) acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[h][rb], fv[h], acc[rb][0], 0, 0, 0);
+        for (int rb = 0; rb < RB; ++rb)
+          acc[rb][b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb, fa[h][rb], acc[rb][b + 1], 0, 0, 0);
+      }
+      if (kDir && work) {
 #pragma unroll
-        for (int b = 0; b < NBB; ++b)
-          acc[rb][b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[h][rb], fb[b], acc[rb][b + 1], 0, 0, 0);
+        for (int rb = 0; rb < RB; ++rb)
+          acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv[h], fa[h][rb], acc[rb][0], 0, 0, 0);
       }
     }
   }
@@ -140,20 +218,19 @@ __global__ __launch_bounds__(256, 2) void k_side_down(SideDownArgs a, int cb0) {
   // Rows of foreground sequences get no partial sums: the finishing kernel writes their zeros without
   // reading any.  Neither do the direction columns of a centre item.
   if (it.kind == kKindForeground) return;
+  // The products are formed with the columns of V as the matrix instruction's rows and the rows of X as its
+  // columns, so a lane holds four neighbouring columns of one row: one 16-byte store each.
   const int ndir_cols = a.RP;
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
+    const int lrow = rb * 16 + lr;
+    if (lrow >= it.nrows) continue;
+    float* dst = a.partial + ((int64_t)split * a.T + it.row0 + lrow) * NC + lg * 4;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      const int lrow = rb * 16 + lg * 4 + v;
-      if (lrow >= it.nrows) continue;
-      const int64_t row = it.row0 + lrow;
-#pragma unroll
-      for (int cb = 0; cb < NBB + 1; ++cb) {
-        if (cb == 0 && (!kDir || !has_dir)) continue;
-        const int col = cb == 0 ? lr : ndir_cols + (cb0 + cb - 1) * 16 + lr;
-        a.partial[((int64_t)split * a.T + row) * NC + col] = acc[rb][cb][v];
-      }
+    for (int cb = 0; cb < NBB + 1; ++cb) {
+      if (cb == 0 && (!kDir || !has_dir)) continue;
+      const int col = cb == 0 ? 0 : ndir_cols + (cb0 + cb - 1) * 16;
+      *reinterpret_cast<f32x4*>(dst + col) = acc[rb][cb];
     }
   }
   // direction columns 16 .. RP-1 exist only for ranks above 16 and are handled by extra passes below
@@ -265,24 +342,48 @@ __global__ __launch_bounds__(256) void k_side_finish(SideDownArgs a) {
   *reinterpret_cast<u32x4*>(a.Xs + ((int64_t)p * kTileN + rr) * kTileK + c * 8) = out;
 }
 
+// Waves (items) per workgroup: eight, or seven when the rings of eight would not leave room for the V stages
+// in the 160 KiB of LDS (64-row items next to eight bank blocks).
+template <int NBB, int RB>
+constexpr int side_waves() {
+  return (kSideWaves * (2 * RB * 2048 + 2048) + 2 * (NBB > 0 ? NBB : 1) * 2048 <= 160 * 1024) ? kSideWaves : kSideWaves - 1;
+}
+
+template <int NBB, bool kDir, int RB>
+static hipError_t launch_pass_rb(const SideDownArgs& a, int cb0, hipStream_t st) {
+  constexpr int W = side_waves<NBB, RB>();
+  constexpr int lds_bytes = W * (2 * RB * 2048 + 2048) + 2 * (NBB > 0 ? NBB : 1) * 2048;
+  static_assert(lds_bytes <= 160 * 1024, "side-down LDS layout exceeds a compute unit's LDS");
+  static std::atomic<bool> configured[kMaxDevices];
+  const hipError_t ec = once_per_device(configured, [] {
+    return hipFuncSetAttribute((const void*)k_side_down<NBB, kDir, RB, W>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  });
+  if (ec != hipSuccess) return ec;
+  dim3 grid(a.ksplit * ((a.max_items + W - 1) / W));
+  hipLaunchKernelGGL((k_side_down<NBB, kDir, RB, W>), grid, dim3(W * 64), lds_bytes, st, a, cb0);
+  return hipGetLastError();
+}
+
 template <int NBB, bool kDir>
-static void launch_pass(const SideDownArgs& a, int cb0, hipStream_t st) {
-  dim3 grid(a.ksplit * ((a.max_items + 3) / 4));
-  hipLaunchKernelGGL((k_side_down<NBB, kDir>), grid, dim3(256), 0, st, a, cb0);
+static hipError_t launch_pass(const SideDownArgs& a, int cb0, hipStream_t st) {
+  if (a.item_rows > 48) return launch_pass_rb<NBB, kDir, 4>(a, cb0, st);
+  if (a.item_rows > 32) return launch_pass_rb<NBB, kDir, 3>(a, cb0, st);
+  if (a.item_rows > 16) return launch_pass_rb<NBB, kDir, 2>(a, cb0, st);
+  return launch_pass_rb<NBB, kDir, 1>(a, cb0, st);
 }
 
 template <bool kDir>
-static void launch_pass_n(int nbb, const SideDownArgs& a, int cb0, hipStream_t st) {
+static hipError_t launch_pass_n(int nbb, const SideDownArgs& a, int cb0, hipStream_t st) {
   switch (nbb) {
-    case 0: launch_pass<0, kDir>(a, cb0, st); break;
-    case 1: launch_pass<1, kDir>(a, cb0, st); break;
-    case 2: launch_pass<2, kDir>(a, cb0, st); break;
-    case 3: launch_pass<3, kDir>(a, cb0, st); break;
-    case 4: launch_pass<4, kDir>(a, cb0, st); break;
-    case 5: launch_pass<5, kDir>(a, cb0, st); break;
-    case 6: launch_pass<6, kDir>(a, cb0, st); break;
-    case 7: launch_pass<7, kDir>(a, cb0, st); break;
-    default: launch_pass<8, kDir>(a, cb0, st); break;
+    case 0: return launch_pass<0, kDir>(a, cb0, st);
+    case 1: return launch_pass<1, kDir>(a, cb0, st);
+    case 2: return launch_pass<2, kDir>(a, cb0, st);
+    case 3: return launch_pass<3, kDir>(a, cb0, st);
+    case 4: return launch_pass<4, kDir>(a, cb0, st);
+    case 5: return launch_pass<5, kDir>(a, cb0, st);
+    case 6: return launch_pass<6, kDir>(a, cb0, st);
+    case 7: return launch_pass<7, kDir>(a, cb0, st);
+    default: return launch_pass<8, kDir>(a, cb0, st);
   }
 }
 
@@ -291,10 +392,12 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
   const int bank_blocks = a.Rp / 16;
   // first pass: direction block 0 together with up to 8 bank blocks
   int done = bank_blocks < kSideMaxBlocks - 1 ? bank_blocks : kSideMaxBlocks - 1;
-  launch_pass_n<true>(done, a, 0, st);
+  hipError_t e0 = launch_pass_n<true>(done, a, 0, st);
+  if (e0 != hipSuccess) return e0;
   while (done < bank_blocks) {   // bank ranks above 128: further passes over X
     const int nb = bank_blocks - done < kSideMaxBlocks - 1 ? bank_blocks - done : kSideMaxBlocks - 1;
-    launch_pass_n<false>(nb, a, done, st);
+    e0 = launch_pass_n<false>(nb, a, done, st);
+    if (e0 != hipSuccess) return e0;
     done += nb;
   }
   for (int cbd = 1; cbd < a.RP / 16;) {   // ranks above 16: up to 8 further direction blocks per pass over X
@@ -309,15 +412,6 @@ hipError_t launch_side_down_bf16(const SideDownArgs& a, hipStream_t st) {
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_side_finish, dim3((unsigned)a.kt_cap * 8u), dim3(256), 0, st, a);
   return hipGetLastError();
-}
-
-// K ranges per row: ranges of about 2560 columns for wide inputs, four ranges up to 8192 columns, never
-// narrower than 512 columns, whole 64-column steps.
-int side_ksplit(int n) {
-  int s = n <= 8192 ? 4 : (n + 1280) / 2560;
-  if (s > 8) s = 8;
-  while (s > 1 && n / s < 512) --s;
-  return s < 1 ? 1 : s;
 }
 
 }  // namespace zo

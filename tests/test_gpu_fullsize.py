@@ -9,11 +9,12 @@ import pytest
 torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
+from oracle import philox as px
 from oracle import zo_block as ob
 from oracle import zo_oracle as zo
 from paper_2605_28760_amd import workloads as wl
 from paper_2605_28760_amd.runner import DeviceBlock, DeviceWorkload
-from zo_testlib import assert_close, oracle_batch, oracle_layer, to_np
+from zo_testlib import assert_close, oracle_batch, oracle_chain, oracle_layer, to_np
 
 DEV = "cuda:0"
 
@@ -80,6 +81,36 @@ def _check_scoring(w, d, rows):
     assert_close(to_np(d.proj_grad), grad, 5e-2, "proj_grad from the GPU's candidate sums")
 
 
+def _check_outputs_end_to_end(w, d, dirs, extra_seqs=()):
+    """The method's outputs at full size against the oracle's own chain (its own activations from the
+    first layer on, nothing taken from the device): the oracle evaluates the sequences of the directions
+    `dirs` (all of them when None) alone, the device has evaluated the whole batch; a sequence's results do
+    not depend on the rest of the batch, so each kept sequence's NLL, each kept candidate's mean loss
+    (abs 1e-3) and each kept direction's projected gradient (rel 5e-2) must agree."""
+    S = len(w.seq_cand)
+    if dirs is None:
+        keep = np.arange(S)
+    else:
+        of_dir = np.where(w.seq_cand >= 0, w.cand_dir[np.maximum(w.seq_cand, 0)], -1)
+        keep = np.array(sorted(set(np.nonzero(np.isin(of_dir, dirs))[0].tolist()) | set(extra_seqs)), np.int64)
+    sub = wl.subset_sequences(w, keep)
+    ref = oracle_chain(sub)
+    cu = w.cu_seqlens
+    cnt = np.array([(w.targets[cu[s]:cu[s + 1]] >= 0).sum() for s in keep], np.float64)
+    got_seq = to_np(d.seq_nll)[keep].astype(np.float64)
+    # per-sequence mean NLL: the abs 1e-3 bar of a per-candidate mean loss holds for every sequence too
+    np.testing.assert_allclose(got_seq / np.maximum(cnt, 1), ref["seq_nll"] / np.maximum(cnt, 1), rtol=0, atol=1e-3)
+    cands = np.unique(w.seq_cand[keep][w.seq_cand[keep] >= 0])
+    got_cnt = to_np(d.cand_cnt)[cands]
+    assert np.array_equal(got_cnt, ref["cand_cnt"][cands])
+    mean_got = to_np(d.cand_sum)[cands].astype(np.float64) / np.maximum(got_cnt, 1)
+    mean_want = ref["cand_sum"][cands] / np.maximum(ref["cand_cnt"][cands], 1)
+    np.testing.assert_allclose(mean_got, mean_want, rtol=0, atol=1e-3)
+    kdirs = np.arange(len(w.dir_seed)) if dirs is None else np.asarray(dirs)
+    assert_close(to_np(d.proj_grad)[kdirs], ref["proj_grad"][kdirs], 5e-2, "proj_grad against the oracle chain")
+    return ref
+
+
 def test_config2_layer_set_full_size():
     w = wl.opt_layer_set()
     d = DeviceWorkload(w, DEV)
@@ -89,6 +120,32 @@ def test_config2_layer_set_full_size():
     _check_layers(w, d, _sample_rows(w, n_cands=2, per_cand=8))
 
 
+def test_config2_side_term_isolated_full_size():
+    """Y_+ - Y_- on the duplicated rows of a +/- pair equals 2 eps (X V) U^T at the full shapes (fp32
+    output; input widths 5120 and 20480, so the side-down pass sums several K ranges): at eps = 1e-3
+    the probe term is a small part of Y, and only the difference checks it to 2e-2."""
+    w = wl.opt_layer_set()
+    d = DeviceWorkload(w, DEV, out_dtype="f32")
+    L = 256                     # rows of one sequence; sequences 2e, 2e+1 are the +/- pair of example e
+    cu = w.cu_seqlens
+    assert w.seq_cand[0] != w.seq_cand[1] and cu[1] - cu[0] == L
+    rng = np.random.default_rng(11)
+    for i in (0, 4, 5):         # q (5120 -> 5120), fc1 (5120 -> 20480), fc2 (20480 -> 5120)
+        l = w.layers[i]
+        assert np.array_equal(l.X[cu[0]:cu[1]], l.X[cu[1]:cu[2]])
+        y = d.probe_linear(i)
+        torch.cuda.synchronize()
+        U = px.factor_matrix(int(w.dir_seed[0]), l.tensor_id, l.m, w.r, "bf16")
+        V = px.factor_matrix(int(w.dir_seed[0]), l.tensor_id + 1, l.n, w.r, "bf16")
+        sign = float(w.cand_sign[w.seq_cand[0]])
+        for e in (0, 7, 15):
+            rows = np.sort(rng.choice(L, size=24, replace=False))
+            rp, rm = cu[2 * e] + rows, cu[2 * e + 1] + rows
+            diff = to_np(y[torch.from_numpy(rp).to(DEV)]) - to_np(y[torch.from_numpy(rm).to(DEV)])
+            want = sign * 2 * w.eps * (l.X[rp].astype(np.float64) @ V) @ U.T
+            assert_close(diff, want, 2e-2, "side term of %s, example %d" % (l.name, e), atol=2e-5)
+
+
 def test_config3_scoring_full_size():
     w = wl.opt_scoring()
     d = DeviceWorkload(w, DEV)
@@ -96,6 +153,9 @@ def test_config3_scoring_full_size():
     torch.cuda.synchronize()
     rows = _check_layers(w, d, _sample_rows(w, n_cands=2, per_cand=8))
     _check_scoring(w, d, rows)
+    # the whole oracle chain (every row, both candidates): per-candidate summed NLL and the projected gradient
+    ref = _check_outputs_end_to_end(w, d, None)
+    assert_close(to_np(d.cand_sum), ref["cand_sum"], 1e-5, "per-candidate summed NLL")
     first = [y.clone() for y in d.Y] + [d.tok_nll.clone(), d.cand_sum.clone()]
     d.step(update=False)
     torch.cuda.synchronize()
@@ -110,6 +170,7 @@ def test_config4_ragged_full_size():
     torch.cuda.synchronize()
     rows = _check_layers(w, d, _sample_rows(w, n_cands=3, per_cand=5))
     _check_scoring(w, d, rows)
+    _check_outputs_end_to_end(w, d, [0, 9])      # two directions: four +/- sequences each
 
 
 def test_config5_mixed_full_size_with_foreground_identity():
@@ -120,6 +181,8 @@ def test_config5_mixed_full_size_with_foreground_identity():
     torch.cuda.synchronize()
     rows = _check_layers(w, d, _sample_rows(w, n_cands=3, per_cand=5))
     _check_scoring(w, d, rows)
+    fg_seq = int(np.nonzero(w.seq_cand < 0)[0][0])
+    _check_outputs_end_to_end(w, d, [2, 13, 23], extra_seqs=[fg_seq])   # three +/- pairs and a foreground sequence
     assert [l.W.view(torch.int16).to(torch.int64).sum().item() for l in d.layers] == w_sum   # base immutable
     tok_cand = zo.batch_indices(oracle_batch(w))[1]
     fg_rows = torch.from_numpy(np.nonzero(tok_cand < 0)[0]).to(DEV)

@@ -233,6 +233,29 @@ def test_batch_invariance_and_determinism():
     assert torch.equal(first[3][torch.from_numpy(perm.copy()).to(DEV)], d2.seq_nll)
 
 
+def test_side_term_does_not_depend_on_the_rest_of_the_batch():
+    """Input widths of 1024 and 2048 make the side-down pass sum several K ranges per row.  How a row's
+    side term is summed must depend on the width alone: a subset of the sequences, packed in another
+    order (fewer rows, fewer work items), must reproduce the shared sequences bit for bit."""
+    w = wl.ragged_packed(hidden=1024, ffn=2048, vocab=1187, n_ex=10, n_dirs=5, len_lo=1, len_hi=300, r=16, R=32)
+    d = DeviceWorkload(w, DEV)
+    d.step(update=False); _sync()
+    keep = np.array([7, 6, 18, 19, 2, 3, 11], np.int64)
+    sub = wl.subset_sequences(w, keep)
+    assert sub.T < w.T // 2
+    d2 = DeviceWorkload(sub, DEV)
+    d2.step(update=False); _sync()
+    rows_t = torch.from_numpy(sub.meta["rows"]).to(DEV)
+    for a, b_ in zip(d.Y, d2.Y):
+        assert torch.equal(a[rows_t], b_)
+    assert torch.equal(d.tok_nll[rows_t], d2.tok_nll)
+    assert torch.equal(d.seq_nll[torch.from_numpy(keep).to(DEV)], d2.seq_nll)
+    # and against the oracle, so that the shared bits are the right ones
+    H = _per_layer_parity(sub, d2)
+    tok = zo.token_nll(H, sub.head, sub.targets)
+    assert_close(to_np(d2.tok_nll), tok, 1e-4, "tok_nll of the subset", atol=1e-4)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_bank_update_parity(dtype):
     m, n, r, K, R_cap = 300, 200, 4, 3, 16
