@@ -205,6 +205,26 @@ int32_t zo_score(const zo_batch* batch, const void* H, int64_t ldh,
                  float* cand_sum, int32_t* cand_cnt,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * zo_score for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors as zo_score, without the workspace: the scratch of the scoring
+ * kernels (list of scored tokens, per-vocabulary-tile partial maxima and sums,
+ * target logits) lives in a static device array of zo_score_static_capacity() bytes
+ * (32 MiB) that every GPU the library runs on holds until the process ends.  The
+ * call allocates nothing.  A batch whose scratch (zo_score_workspace_bytes) exceeds
+ * the capacity is rejected with ZO_ERR_WORKSPACE before anything is launched: e.g.
+ * 4096 tokens at a vocabulary of 151936, or 16384 tokens at 50272, still fit.  All
+ * calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ * (different streams, or different threads) race; calls on one stream do not.
+ */
+size_t zo_score_static_capacity(void);
+
+int32_t zo_score_static(const zo_batch* batch, const void* H, int64_t ldh,
+                        const void* W_head, int64_t ldw, int32_t vocab, int32_t d,
+                        zo_dtype dtype, const int32_t* targets,
+                        float* tok_nll, float* seq_nll, float* cand_sum, int32_t* cand_cnt,
+                        void* stream);
 
 /*
  * Antithetic two-point estimate (Sec. 2.1, Eq. 2):

@@ -70,6 +70,10 @@ _PROTOS = {
     "zo_score": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32, C.c_int32,
                              C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                              C.c_void_p, C.c_size_t, C.c_void_p]),
+    "zo_score_static_capacity": (C.c_size_t, []),
+    "zo_score_static": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int32,
+                                    C.c_int32, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p]),
     "zo_estimate": (C.c_int32, [C.POINTER(zo_batch), C.c_void_p, C.c_void_p, C.c_float, C.c_int32, C.c_void_p,
                                 C.c_void_p, C.c_void_p]),
     "zo_bank_update": (C.c_int32, [C.POINTER(zo_bank), C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
@@ -209,6 +213,16 @@ def zo_score(batch, H, ldh, W_head, ldw, vocab, d, dtype, targets, tok_nll, seq_
     _check(lib().zo_score(C.byref(batch), _ptr(H), ldh, _ptr(W_head), ldw, vocab, d, dtype, _ptr(targets),
                           _ptr(tok_nll), _ptr(seq_nll), _ptr(cand_sum), _ptr(cand_cnt), _ptr(workspace),
                           workspace_bytes, _stream(stream)))
+
+
+def zo_score_static_capacity():
+    return lib().zo_score_static_capacity()
+
+
+def zo_score_static(batch, H, ldh, W_head, ldw, vocab, d, dtype, targets, tok_nll, seq_nll, cand_sum, cand_cnt,
+                    stream=None):
+    _check(lib().zo_score_static(C.byref(batch), _ptr(H), ldh, _ptr(W_head), ldw, vocab, d, dtype, _ptr(targets),
+                                 _ptr(tok_nll), _ptr(seq_nll), _ptr(cand_sum), _ptr(cand_cnt), _stream(stream)))
 
 
 def zo_estimate(batch, cand_sum, cand_cnt, eps, reduction, cand_loss, proj_grad, stream=None):

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libzo.so")
-SOURCES = ["zo_abi.cpp", "zo_prep.hip", "zo_side.hip", "zo_gemm.hip", "zo_simt.hip", "zo_reduce.hip", "zo_block.hip", "zo_fold.hip"]
+SOURCES = ["zo_abi.cpp", "zo_prep.hip", "zo_side.hip", "zo_gemm.hip", "zo_simt.hip", "zo_reduce.hip", "zo_block.hip", "zo_fold.hip", "zo_static.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-ignored-attributes"]
