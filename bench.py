@@ -27,12 +27,11 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # Bytes per launch of the dominant kernel that crossed the L2 <-> fabric boundary, from the rocprofv3
-# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in the named files under profiles/ (FETCH_SIZE scaled by the
+# --pmc FETCH_SIZE and WRITE_SIZE runs summarised in the named file under profiles/ (FETCH_SIZE scaled by the
 # factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  They are figures of those profile
-# runs, not of this run: the line names their source next to them.
-MEASURED_TRAFFIC = {"c3": (1.241e10, "profiles/hbm_bytes_bench_c3.txt"),
-                    "c4": (3.778e10, "profiles/hbm_bytes_bench_c4_c5.txt"),
-                    "c5": (6.704e10, "profiles/hbm_bytes_bench_c4_c5.txt")}
+# runs, not of this run: the line names their source next to them (null for a workload without such a run).
+MEASURED_TRAFFIC = {"c3": (1.241e10, "profiles/hbm_bytes_bench_c5_c3.txt"),
+                    "c5": (6.829e10, "profiles/hbm_bytes_bench_c5_c3.txt")}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):

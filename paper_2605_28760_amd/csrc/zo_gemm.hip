@@ -499,10 +499,10 @@ static int gemm_grid(int total_tiles) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Probe linear.  Side state first, base GEMM second: the accumulators of a foreground
-// token are +0 after the side phase (its side operand rows are zero), i.e. exactly the
-// state a plain GEMM starts from, so foreground rows come out bit-identical to an
-// all-foreground call.
+// Probe linear.  Side K tiles first, base K tiles second: the accumulators of a foreground
+// token are still +0 when the base K tiles start (its side operand rows are zero), i.e.
+// exactly the state a plain GEMM starts from, so foreground rows come out bit-identical
+// to an all-foreground call.
 // ---------------------------------------------------------------------------------------
 // 16-byte store of finished outputs with the non-temporal hint: a tile's 128 KiB of Y are written once
 // and read by a later kernel at the earliest, so they should not displace operand slices from the
