@@ -407,20 +407,24 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     // the K loop of a wave that multiplies (kActive) or only keeps the operand stream and the barriers going
     auto k_loop = [&](auto active_c, Acc& acc) __attribute__((always_inline)) {
       constexpr bool kActive = decltype(active_c)::value;
-      auto mfmas = [&](int set) __attribute__((always_inline)) {
+      // first_c: the tile's very first k-step, whose products start the accumulators (C = +0 as an operand,
+      // so the accumulators need no clearing between tiles)
+      auto mfmas = [&](int set, auto first_c) __attribute__((always_inline)) {
+        constexpr bool kFirst = decltype(first_c)::value;
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int cb = 0; cb < CB; ++cb)
-            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb], acc[rb][cb], 0, 0, 0);
+            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb],
+                                                                   kFirst ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[rb][cb], 0, 0, 0);
       };
-      for (int kt = 0; kt < nk_tile; ++kt) {
+      auto k_tile = [&](auto first_c) __attribute__((always_inline)) {
         // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
         __builtin_amdgcn_sched_barrier(0);
         issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
         if constexpr (kActive) {
           load_frags(1, stage, 1);
-          mfmas(0);
+          mfmas(0, first_c);
           pattern(std::integral_constant<int, kLoadsEarly>{});
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -433,19 +437,17 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
         issue_range(stage, 0, kLoadsLate);
         if constexpr (kActive) {
           load_frags(0, stage ^ 1, 0);
-          mfmas(1);
+          mfmas(1, std::false_type{});
           pattern(std::integral_constant<int, kLoadsLate>{});
         }
         __builtin_amdgcn_sched_barrier(0);
         stage ^= 1;
-      }
+      };
+      k_tile(std::true_type{});   // (a tile has at least one K tile)
+      for (int kt = 1; kt < nk_tile; ++kt) k_tile(std::false_type{});
     };
     if (active) {
-      Acc acc;
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) acc[rb][cb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      Acc acc;   // started by the first k-step's products
       // The first fragments of this tile were already fetched under the previous tile's last
       // k-step; fetching them again here keeps their 48 registers free during post().
       load_frags(0, stage, 0);
@@ -694,8 +696,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int wm = wave >> 2, wn = wave & 3;
-  float* s_max = (float*)(lds + kStagesLds);   // [2][256]
-  float* s_sum = s_max + 2 * BN;                // [2][256]
+  float* s_max = (float*)(lds + kStagesLds);   // [2 wave rows][256 tokens]
+  float* s_sum = s_max + 2 * BN;                // [2 wave rows][256 tokens]
   constexpr float kLog2e = 1.4426950408889634f;
 
   // D block (rb, cb): vocabulary row = vbase + rb*16 + 4*g + v, token = tile_t0 + wn*64 + cb*16 + r16.
@@ -704,6 +706,15 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
     const int r16 = lane_t & 15, g = lane_t >> 4;
     const int tm = tile_v0 / BM;   // vocabulary tile: the index of this tile's partials
     const int vbase = tile_v0 + wm * 128;  // first vocabulary row of this wave
+    if (tile_v0 + BM > p.vocab) {   // the last vocabulary tile: rows past the end count as -inf
+#pragma unroll
+      for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            if (vbase + rb * 16 + 4 * g + v >= p.vocab) acc[rb][cb][v] = -INFINITY;
+    }
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
       const int tl = wn * 64 + cb * 16 + r16;   // token within the tile
@@ -712,19 +723,16 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int vr = vbase + rb * 16 + 4 * g + v;
-          if (vr >= p.vocab) acc[rb][cb][v] = -INFINITY;
-          mx = fmaxf(mx, acc[rb][cb][v]);
-        }
+        for (int v = 0; v < 4; ++v) mx = fmaxf(mx, acc[rb][cb][v]);
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float mref = (mx == -INFINITY) ? 0.0f : mx;
+      // sum of exp(z - max) as 2^(z log2(e) - max log2(e)), one multiply-add per logit
+      const float mref2 = (mx == -INFINITY) ? 0.0f : -mx * kLog2e;
       float sum = 0.0f;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f((acc[rb][cb][v] - mref) * kLog2e);
+        for (int v = 0; v < 4; ++v) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[rb][cb][v], kLog2e, mref2));
       sum += __shfl_xor(sum, 16);
       sum += __shfl_xor(sum, 32);
       if (g == 0) { s_max[wm * BN + tl] = mx; s_sum[wm * BN + tl] = sum; }
@@ -757,8 +765,8 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
         p.part_sum[(int64_t)tm * p.T + t] = S;
       }
     }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    block_barrier();   // the exchange buffers are free again for the next tile
+    // (no barrier here: the exchange buffers are written again after the next tile's K loop, whose barriers
+    // every thread passes only after these reads)
   };
 
   persistent_gemm<kGather, false, false>(p.Wh, p.ldw, p.vocab, p.H, p.ldh, n_tok, p.d, n_tm, n_tn, tn_super, 0, lds, epilogue,
