@@ -121,7 +121,8 @@ __device__ __forceinline__ void seq_tables_block(const BatchDev& b, float eps, c
       }
       t.seq_kind[s] = kind;
       t.seq_scale[s] = scale;
-      nchunk = (len + t.item_rows - 1) / t.item_rows;
+      // (a foreground sequence has no side term: no items, none of its rows is read by the side-down pass)
+      nchunk = kind == kKindForeground ? 0 : (len + t.item_rows - 1) / t.item_rows;
     }
     int total;
     const int first = carry + block_scan_1024(nchunk, s_scan, &total);

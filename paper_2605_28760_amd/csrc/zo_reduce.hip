@@ -260,7 +260,9 @@ __device__ __forceinline__ void bank_quad(float* M, int R_cap, int col0, int row
     if (bf16) z[l] = bf16_round(z[l]);
     z[l] *= beta;
   }
-  const int i = (int)(e0 / r), j = (int)(e0 % r);
+  // (32-bit division when the factor has fewer than 2^31 entries: the 64-bit one costs more than the normals)
+  const int i = total < (1ll << 31) ? (int)((uint32_t)e0 / (uint32_t)r) : (int)(e0 / r);
+  const int j = (int)(e0 - (int64_t)i * r);
   float* dst = M + (int64_t)i * R_cap + col0 + j;
   if ((r & 3) == 0 && (((uintptr_t)dst) & 15u) == 0) {
     float4 v = make_float4(z[0], z[1], z[2], z[3]);
