@@ -98,14 +98,16 @@ __global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0
     const int lch = (lane & 7) ^ ((row >> 1) & 7);
     x_off[j] = (uint32_t)min(row, it.nrows - 1) * (uint32_t)(a.ldx * 2) + (uint32_t)(k_begin * 2 + lch * 16);
   }
+  // load j of the step's rows of X (non-temporal: a line of X is used once, and should not push V and Vb
+  // out of the L2)
+  auto issue_x1 = [&](int step, int j) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (lds_void*)(ring + (step & 1) * kRing + j * 1024), 16, (int)x_off[j],
+                                             step * kstride * 2, 0, kNonTemporal);
+  };
   auto issue_x = [&](int step) {
     if (!work) return;
-    char* dst = ring + (step & 1) * kRing;
 #pragma unroll
-    for (int j = 0; j < 2 * RB; ++j)
-      // non-temporal: a line of X is used once, and should not push V and Vb out of the L2
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (lds_void*)(dst + j * 1024), 16, (int)x_off[j], step * kstride * 2, 0,
-                                               kNonTemporal);
+    for (int j = 0; j < 2 * RB; ++j) issue_x1(step, j);
   };
   // fragment (rb, h) of a ring stage: row rb*16 + lr, logical chunk h*4 + lg
   uint32_t a_off[2];
@@ -139,12 +141,14 @@ __global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0
   // has no direction: it reads direction 0's block and discards the result.
   const __amdgpu_buffer_rsrc_t vd_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(a.Vt + (int64_t)(has_dir ? it.kind : 0) * a.RP * a.n), 0, (int)((int64_t)16 * a.n * 2), 0x00020000);
+  auto issue_v1 = [&](int step, int h) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(vd_rsrc, (lds_void*)(s_vd + h * 1024), 16, (int)vb_off,
+                                             (step * kstride + h * 32) * 2, 0, 0);
+  };
   auto issue_v = [&](int step) {
     if (!kDir || !work) return;
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vd_rsrc, (lds_void*)(s_vd + h * 1024), 16, (int)vb_off,
-                                               (step * kstride + h * 32) * 2, 0, 0);
+    for (int h = 0; h < 2; ++h) issue_v1(step, h);
   };
 
   f32x4 acc[RB][NBB + 1];
@@ -185,8 +189,6 @@ __global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0
         if (kDir) fv[h] = *(const bf16x8*)(s_vd + h * 1024 + rd_off);
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // both have been read: they can take what comes next
-      if (step + 1 < nsteps) issue_v(step + 1);
-      if (step + 2 < nsteps) issue_x(step + 2);
     } else {
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -195,20 +197,52 @@ __global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0
         fv[h] = zero_frag();
       }
     }
+    // The requests for V(s+1) and X(s+2) are spread through the products, one after each group of them:
+    // a wave that issued them in one burst would stand at the memory pipeline's queue while its matrix
+    // instructions wait behind them in program order.  (Their order, V before X, is what the count of the
+    // wait above relies on.)
+    const bool more_v = kDir && work && step + 1 < nsteps, more_x = work && step + 2 < nsteps;
+    constexpr int kSlots = 2 * (NBB + (kDir ? 1 : 0));      // groups of products in a step
+    constexpr int kLoads = (kDir ? 2 : 0) + 2 * RB;          // requests of a step: V halves, then X row blocks
+    auto issue_slot = [&](int slot) {
+#pragma unroll
+      for (int i = 0; i < kLoads; ++i) {
+        if (i * kSlots / kLoads != slot) continue;
+        if (kDir && i < 2) {
+          if (more_v) issue_v1(step + 1, i);
+        } else {
+          if (more_x) issue_x1(step + 2, i - (kDir ? 2 : 0));
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // The Vb fragments of the first half are all read before the first product; a fragment of the second
+    // half is read as soon as its slot's first-half fragment has been handed to the matrix core, so the
+    // latency of an LDS read is paid once per step, not once per fragment.
     const char* stage = s_vb + (step & 1) * kVbStage;
+    bf16x8 cur[NBB > 0 ? NBB : 1];
+#pragma unroll
+    for (int b = 0; b < NBB; ++b) cur[b] = *(const bf16x8*)(stage + b * 1024 + rd_off);
+    __builtin_amdgcn_sched_barrier(0);
+    int slot = 0;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
 #pragma unroll
       for (int b = 0; b < NBB; ++b) {
-        const bf16x8 fb = *(const bf16x8*)(stage + (h * NBB + b) * 1024 + rd_off);
+        const bf16x8 fb = cur[b];
+        if (h == 0) cur[b] = *(const bf16x8*)(stage + (NBB + b) * 1024 + rd_off);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
           acc[rb][b + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb, fa[h][rb], acc[rb][b + 1], 0, 0, 0);
+        issue_slot(slot++);
       }
-      if (kDir && work) {
+      if (kDir) {
+        if (work) {
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv[h], fa[h][rb], acc[rb][0], 0, 0, 0);
+          for (int rb = 0; rb < RB; ++rb)
+            acc[rb][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv[h], fa[h][rb], acc[rb][0], 0, 0, 0);
+        }
+        issue_slot(slot++);
       }
     }
   }

@@ -65,7 +65,10 @@ def test_loop_step_by_step_against_the_oracle(dtype):
     must be the oracle's update of the banks before it."""
     nu, B = 2, 2
     if dtype == "bf16":
-        w = wl.ragged_packed(hidden=128, ffn=256, vocab=300, n_ex=6, n_dirs=2, r=8, R=2 * 2 * 8, len_lo=20, len_hi=90)
+        # (enough tokens per candidate for the 5e-2 bar on the projected gradient: the difference quotient
+        # multiplies the bf16 rounding noise of the two mean losses by 1 / (2 eps) = 500, and that noise
+        # falls with the square root of the tokens averaged; 12 sequences of 40-160 tokens per direction)
+        w = wl.ragged_packed(hidden=128, ffn=256, vocab=300, n_ex=24, n_dirs=2, r=8, R=2 * 2 * 8, len_lo=40, len_hi=160)
     else:
         w = wl.opt_scoring(hidden=64, ffn=128, vocab=200, n_ex=3, seq_len=40, r=4, R=2 * 1 * 4, dtype="f32")
     K = len(w.dir_seed)
