@@ -152,6 +152,9 @@ def test_bf16_side_term_isolated_fp32_out():
     (wl.ragged_packed, dict(hidden=128, ffn=256, vocab=300, n_ex=6, n_dirs=3, len_lo=1, len_hi=50, r=2, R=0)),
     (wl.ragged_packed, dict(hidden=128, ffn=256, vocab=300, n_ex=4, n_dirs=2, len_lo=1, len_hi=90, r=40, R=160)),
     (wl.mixed_foreground, dict(hidden=64, ffn=192, vocab=515, n_ex=3, n_fg=2, len_lo=60, len_hi=300, r=64, R=16)),
+    # vocabularies that end exactly on a 256-row tile of the head kernel, and one row into the next tile
+    (wl.opt_scoring, dict(hidden=256, ffn=512, vocab=768, n_ex=5, seq_len=77, r=8, R=64)),
+    (wl.ragged_packed, dict(hidden=256, ffn=384, vocab=257, n_ex=8, n_dirs=4, len_lo=1, len_hi=140, r=16, R=32)),
 ])
 def test_bf16_chain_parity(builder, kw):
     w = builder(**kw)
