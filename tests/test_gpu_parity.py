@@ -41,8 +41,10 @@ def test_factor_fill_matches_oracle(rows, r):
     zb.zo_factor_fill(seed, tid, rows, r, zb.ZO_F32, out); _sync()
     want = px.factor_matrix(seed, tid, rows, r, "f32")
     got = out.cpu().numpy().astype(np.float64)
-    assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want) + 1e-6)
-    assert np.mean(got == want) > 0.5          # most entries agree to the last bit
+    assert np.all(np.abs(got - want) <= 1e-5 * np.abs(want) + 1e-6)        # the bar: rel 1e-5, abs 1e-6 near zero
+    # far inside it: the radius is good to 1.4e-7 (relative) and the sine / cosine to 1.3e-7 (absolute) for
+    # every uniform the generator can produce, the radius is at most sqrt(48 ln 2) = 5.77
+    assert np.all(np.abs(got - want) <= 3e-7 * np.abs(want) + 8e-7)
     ob = torch.empty((rows, r), device=DEV, dtype=torch.bfloat16)
     zb.zo_factor_fill(seed, tid, rows, r, zb.ZO_BF16, ob); _sync()
     wantb = px.factor_matrix(seed, tid, rows, r, "bf16")
