@@ -31,7 +31,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  They are figures of those profile
 # runs, not of this run: the line names their source next to them (null for a workload without such a run).
 MEASURED_TRAFFIC = {"c3": (1.241e10, "profiles/hbm_bytes_bench_c5_c3.txt"),
-                    "c5": (6.829e10, "profiles/hbm_bytes_bench_c5_c3.txt")}
+                    "c4": (3.720e10, "profiles/hbm_bytes_bench_c5_c3.txt"),
+                    "c5": (6.581e10, "profiles/hbm_bytes_bench_c5_c3.txt")}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):
@@ -356,6 +357,44 @@ def _chain(name, steps, warmup, full, block, cpu_baseline):
     return out, w
 
 
+def _operand_data_section(n_rep=20):
+    """The head kernel (zo_score, all rows foreground) on the OPT-13B head shape with operands of different
+    content: the same launch, addresses and traffic, so a difference in time is the chip's clock answering the
+    switching activity of the data (a power-limited kernel), not the kernel's schedule."""
+    import torch
+    from paper_2605_28760_amd import binding as zb
+    dev = "cuda:0"
+    T, V, d = 16384, 50272, 5120
+    cu = torch.tensor([0, T], dtype=torch.int32, device=dev)
+    fg = torch.tensor([-1], dtype=torch.int32, device=dev)
+    b = zb.make_batch(T, cu, fg, fg, fg, fg, n_seqs=1, n_cands=0, n_dirs=0)
+    g = torch.Generator(device=dev); g.manual_seed(7)
+    tg = torch.randint(0, V, (T,), device=dev, dtype=torch.int32, generator=g)
+    wsb = zb.zo_score_workspace_bytes(T, 1, V, d, zb.ZO_BF16)
+    ws = torch.empty(wsb + 256, dtype=torch.uint8, device=dev)
+    tok = torch.empty(T, device=dev); seq = torch.empty(1, device=dev)
+    st = torch.cuda.current_stream()
+
+    def timed(H, W):
+        fn = lambda: zb.zo_score(b, H, d, W, d, V, d, zb.ZO_BF16, tg, tok, seq, None, None, ws, wsb, st)
+        for _ in range(3): fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(n_rep): fn()
+        e1.record(st); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n_rep
+    Hr = torch.randn(T, d, device=dev, generator=g).to(torch.bfloat16)
+    Wr = (torch.randn(V, d, device=dev, generator=g) * d ** -0.5).to(torch.bfloat16)
+    Hz, Wz = torch.zeros_like(Hr), torch.zeros_like(Wr)
+    out = {"shape": [T, d, V]}
+    for name, (H, W) in (("random", (Hr, Wr)), ("zeros", (Hz, Wz)), ("random_tokens_zero_weights", (Hr, Wz)),
+                         ("random_again", (Hr, Wr))):
+        ms = timed(H, W)
+        out[name] = {"ms": ms, "tflops": 2.0 * T * V * d / ms / 1e9}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -369,6 +408,8 @@ def main():
     ap.add_argument("--no-block", action="store_true", help="skip the decoder-block secondary measurement")
     ap.add_argument("--no-layer-set", action="store_true",
                     help="skip the secondary measurement of the six OPT-13B-shaped linears at 8192 rows")
+    ap.add_argument("--operand-data", action="store_true",
+                    help="also time the head kernel on random, zero and half-zero operands (is the clock power-bound?)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -408,6 +449,8 @@ def main():
     result.update(main_res)
     result["nested_workloads"] = nested
     result["layer_set"] = layer_set_info
+    if args.operand_data:
+        result["head_operand_data"] = _operand_data_section()
     if cpu is not None:
         result["cpu_baseline"] = cpu
     print(json.dumps(result))

@@ -30,12 +30,6 @@ constexpr int kNonTemporal = 2;   // cache-policy operand of a buffer load: the 
 // B fragment = 32 k x 16 cols (lane l: col l%16, same k), D: lane l holds rows 4*(l/16)+v, col l%16.
 // Here the columns of V take the A side and the rows of X the B side: D[column of V][row of X].
 //
-// XOR swizzle of the four 16-byte chunks of a 64-byte row (one of 16 columns of V, 32 k-values) of a Vb or V
-// block in LDS.  A fragment read takes chunk lane/16 of column lane%16; whether the LDS serves 8 or 16
-// lanes per cycle, those lanes then hit distinct banks: the value is a bijection of (col>>2) for fixed
-// col&3 and of ((col>>1)&3) for fixed col&1 within either half of the columns.
-__device__ __forceinline__ int vb_swizzle(int col) { return (((col >> 2) & 1) << 1) | (((col >> 1) ^ (col >> 3)) & 1); }
-
 // NBB = number of 16-column bank blocks this pass accumulates (cb0 = the first of them); kDir = whether
 // the pass also carries the first 16-column direction block; RB = 16-row blocks of an item.
 //
@@ -115,13 +109,13 @@ __global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0
   for (int h = 0; h < 2; ++h) a_off[h] = lr * 128 + (((h * 4 + lg) ^ ((lr >> 1) & 7)) << 4);
 
   // Vb -> LDS: load j (0 .. 2*NBB-1) = (half h = j & 1, block b = j >> 1); lane i fills byte 16*i of
-  // the 1 KiB block: col i/4, physical chunk i%4 = logical chunk ^ vb_swizzle(col)
+  // the 1 KiB block: col i/4, physical chunk i%4 = logical chunk ^ ((col>>2)&3)
   const int vcol = lane >> 2;
-  const int vchunk = (lane & 3) ^ vb_swizzle(vcol);
+  const int vchunk = (lane & 3) ^ ((vcol >> 2) & 3);
   const uint32_t vb_off = (uint32_t)((int64_t)vcol * a.n + k_begin + vchunk * 8) * 2u;
   const __amdgpu_buffer_rsrc_t vb_rsrc = __builtin_amdgcn_make_buffer_rsrc(
       (void*)(a.Vbt + (int64_t)cb0 * 16 * a.n), 0, (int)((int64_t)(NBB > 0 ? NBB : 1) * 16 * a.n * 2), 0x00020000);
-  const uint32_t rd_off = lr * 64 + ((lg ^ vb_swizzle(lr)) << 4);
+  const uint32_t rd_off = lr * 64 + ((lg ^ ((lr >> 2) & 3)) << 4);
   constexpr int kVbMine = (2 * NBB + W - 1) / W;   // Vb loads of one wave per step (at most)
   auto issue_vb = [&](int step) {
     char* dst = s_vb + (step & 1) * kVbStage;
