@@ -14,29 +14,41 @@
 namespace zo {
 
 // ---- launch planning of the side-down pass (host only) ------------------------------------
-// K ranges per row: ranges of about 2560 columns for wide inputs, four ranges up to 8192 columns, never
-// narrower than 512 columns, whole 64-column steps.
+// K ranges per row: four ranges up to 12288 columns, ranges of about 2560 columns for wider inputs, never
+// narrower than 512 columns, whole 64-column steps.  A function of the input width alone: the range a
+// column falls in, and with it the order in which a row's products are summed, must not depend on the batch.
 int side_ksplit(int n) {
-  int s = n <= 8192 ? 4 : (n + 1280) / 2560;
+  int s = n <= 12288 ? 4 : (n + 1280) / 2560;
   if (s > 8) s = 8;
   while (s > 1 && n / s < 512) --s;
   return s < 1 ? 1 : s;
 }
 
 // Rows per item (64, 48, 32 or 16; how rows are grouped into items does not enter any row's arithmetic).  The
-// workgroups of a pass (eight items each, times the K ranges) run in rounds of one workgroup per compute
-// unit.  A workgroup's time per K step has a part that grows with its items' rows (their bytes of X) and a
-// part that does not (fetching the V and Vb fragments from LDS: about two rows' worth per 16 bank
-// columns): the size that makes rounds x time smallest, the larger one on a tie (it re-reads V less often).
-int side_item_rows(int T, int n, int R) {
+// workgroups of a pass (seven or eight items each, times the K ranges) run in rounds of one workgroup per
+// compute unit, and a round that is mostly empty takes as long as a full one.  A workgroup's time per K step
+// has a part that grows with its items' rows (their bytes of X) and a part that does not (the V and Vb
+// blocks: about two rows' worth per 16 bank columns): the size that makes rounds x time smallest, the larger
+// one on a tie (it re-reads V less often).  With the host mirrors of the batch the items are counted as the
+// device will build them (none for foreground sequences); without, every row counts.
+int side_item_rows(const int32_t* host_cu, const int32_t* host_seq_cand, int S, int T, int n, int R) {
   const int cus = compute_units();
   const int ks = side_ksplit(n);
   const int fixed = 2 * ((R + 15) / 16);
+  const int nbb = (R + 15) / 16 < kSideMaxBlocks - 1 ? (R + 15) / 16 : kSideMaxBlocks - 1;   // bank blocks of the first pass
   static const int kSizes[4] = {64, 48, 32, 16};
   int best = kSideRows;
   int64_t best_cost = -1;
   for (int rows : kSizes) {
-    const int64_t wgs = (int64_t)((T + rows * kSideWaves - 1) / (rows * kSideWaves)) * ks;
+    int64_t items = 0;
+    if (host_cu && host_seq_cand) {
+      for (int q = 0; q < S; ++q)
+        if (host_seq_cand[q] >= 0) items += (host_cu[q + 1] - host_cu[q] + rows - 1) / rows;
+    } else {
+      items = (T + rows - 1) / rows;
+    }
+    const int w = side_waves_of(nbb, rows / 16);
+    const int64_t wgs = ((items + w - 1) / w) * ks;
     const int64_t cost = ((wgs + cus - 1) / cus) * (rows + fixed);
     if (best_cost < 0 || cost < best_cost) { best = rows; best_cost = cost; }
   }
@@ -133,14 +145,17 @@ struct ProbePlan {
   size_t total = 0;
 };
 
-ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype dt) {
+ProbePlan plan_probe(int T, int S, int K, int m, int n, int r, int R, zo_dtype dt, const int32_t* host_cu = nullptr,
+                     const int32_t* host_seq_cand = nullptr) {
   ProbePlan p;
   Carver c;
   p.seq_kind = c.take((size_t)S * 4);
   p.seq_scale = c.take((size_t)S * 4);
   p.tok_seq = c.take((size_t)T * 4);
   p.n_items = c.take(16);
-  p.item_rows = dt == ZO_BF16 ? zo::side_item_rows(T, n, R) : zo::kSideRows;
+  // (the choice of the item size does not enter the layout below: a workspace query, which has no batch, and
+  // the call agree on every offset)
+  p.item_rows = dt == ZO_BF16 ? zo::side_item_rows(host_cu, host_seq_cand, S, T, n, R) : zo::kSideRows;
   p.max_items = (T + p.item_rows - 1) / p.item_rows + S;
   // (sized for the smallest items, so that a workspace sized for a large batch also serves a smaller one)
   p.items = c.take(((size_t)(T + 15) / 16 + S) * sizeof(zo::SideItem));
@@ -295,7 +310,8 @@ int32_t zo_probe_linear(const zo_batch* batch, const void* X, int64_t ldx, const
     return fail(ZO_ERR_UNSUPPORTED, "bf16 path needs n %% %d == 0 (n = %d)", zo::kTileK, n);
   if (out_dtype == ZO_BF16 && m_out % 8 != 0)
     return fail(ZO_ERR_UNSUPPORTED, "bf16 output needs a multiple of 8 output columns (m = %d, activation %d)", m, act);
-  const ProbePlan plan = plan_probe(T, batch->n_seqs, batch->n_dirs, m, n, r, R, in_dtype);
+  const ProbePlan plan = plan_probe(T, batch->n_seqs, batch->n_dirs, m, n, r, R, in_dtype, batch->host_cu_seqlens,
+                                    batch->host_seq_cand);
   if (!workspace) return fail(ZO_ERR_WORKSPACE, "workspace is NULL (%zu bytes needed)", plan.total);
   if (((uintptr_t)workspace & 255u) != 0) return fail(ZO_ERR_WORKSPACE, "workspace not 256-byte aligned");
   if (workspace_bytes < plan.total)

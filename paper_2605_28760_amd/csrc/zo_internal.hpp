@@ -15,7 +15,13 @@ constexpr int kTileN = 256;
 constexpr int kTileK = 64;
 constexpr int kMaxRank = 512;     // largest probe rank r (the rank continuum of Sec. 3.3 goes up to 512)
 constexpr int kSideRows = 64;     // most rows of a side-down work item (one wave); small batches use 32 or 16
-constexpr int kSideWaves = 8;    // waves (items) per workgroup of the side-down pass
+constexpr int kSideWaves = 8;    // waves (items) per workgroup of the side-down pass, at most
+// LDS of a side-down workgroup of w waves whose items have rb 16-row blocks, next to nbb 16-column bank blocks:
+// per wave two stages of its rows of X and one of its direction block of V, per workgroup two stages of Vb.
+constexpr int side_lds_bytes(int nbb, int rb, int w) { return w * (2 * rb * 2048 + 2048) + 2 * (nbb > 0 ? nbb : 1) * 2048; }
+// Waves (items) per workgroup: eight, or seven where eight would not fit the 160 KiB of a compute unit's LDS
+// (64-row items next to eight bank blocks).
+constexpr int side_waves_of(int nbb, int rb) { return side_lds_bytes(nbb, rb, kSideWaves) <= 160 * 1024 ? kSideWaves : kSideWaves - 1; }
 constexpr int kSideMaxBlocks = 9; // 16-column blocks a side-down wave accumulates at once
 constexpr int kSimtTile = 64;     // tile edge of the fp32 vector-ALU kernels
 
@@ -121,7 +127,7 @@ struct SideDownArgs {
 int side_ksplit(int n);
 // Rows per side-down work item (64, 48, 32 or 16) for a batch of T rows, input width n and bank rank R; how rows
 // are grouped into items does not enter any row's arithmetic.
-int side_item_rows(int T, int n, int R);
+int side_item_rows(const int32_t* host_cu, const int32_t* host_seq_cand, int S, int T, int n, int R);
 // sequence tables, token -> sequence map and the four operand images of a bf16 probe linear in one launch
 hipError_t launch_probe_prep_bf16(const BatchDev& b, float eps, const SeqTables& tabs, uint32_t tensor_id, int m,
                                   int n, int r, int RP, int Rp, const float* P, const float* Vb, int R_cap,

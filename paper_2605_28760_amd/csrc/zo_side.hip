@@ -367,17 +367,10 @@ __global__ __launch_bounds__(256) void k_side_finish(SideDownArgs a) {
   *reinterpret_cast<u32x4*>(a.Xs + ((int64_t)p * kTileN + rr) * kTileK + c * 8) = out;
 }
 
-// Waves (items) per workgroup: eight, or seven when the rings of eight would not leave room for the V stages
-// in the 160 KiB of LDS (64-row items next to eight bank blocks).
-template <int NBB, int RB>
-constexpr int side_waves() {
-  return (kSideWaves * (2 * RB * 2048 + 2048) + 2 * (NBB > 0 ? NBB : 1) * 2048 <= 160 * 1024) ? kSideWaves : kSideWaves - 1;
-}
-
 template <int NBB, bool kDir, int RB>
 static hipError_t launch_pass_rb(const SideDownArgs& a, int cb0, hipStream_t st) {
-  constexpr int W = side_waves<NBB, RB>();
-  constexpr int lds_bytes = W * (2 * RB * 2048 + 2048) + 2 * (NBB > 0 ? NBB : 1) * 2048;
+  constexpr int W = side_waves_of(NBB, RB);
+  constexpr int lds_bytes = side_lds_bytes(NBB, RB, W);
   static_assert(lds_bytes <= 160 * 1024, "side-down LDS layout exceeds a compute unit's LDS");
   static std::atomic<bool> configured[kMaxDevices];
   const hipError_t ec = once_per_device(configured, [] {
