@@ -8,11 +8,12 @@
 // the skinny contraction runs on v_mfma_f32_16x16x32_bf16 so that the
 // arithmetic (about 2 (r + R) flop per byte of X) stays out of the way.
 //
-// Work items are chunks of at most 64 (or 32, or 16: small batches get smaller
-// items so that the chip is still filled) rows of one sequence, so all rows of
-// an item share one direction.  One wave per (item, K range); the eight waves
-// of a workgroup walk the same K range in steps of 64 columns, so the bank
-// operand Vb is staged once per workgroup in LDS.  A wave's rows of X land in
+// Work items are chunks of at most 64 (or 48, 32 or 16: the host picks the size
+// that fills the chip in the fewest rounds of workgroups) rows of one candidate
+// sequence, so all rows of an item share one direction; foreground sequences
+// have no items.  One wave per (item, K range); the seven or eight waves of a
+// workgroup walk the same K range in steps of 64 columns, so the bank operand
+// Vb is staged once per workgroup in LDS.  A wave's rows of X land in
 // its own two-stage ring in LDS (direct-to-LDS loads of whole 128-byte lines,
 // no registers tied up by bytes in flight): while a wave multiplies step s, the
 // lines of steps s+1 and s+2 are on their way.
@@ -33,14 +34,16 @@ constexpr int kNonTemporal = 2;   // cache-policy operand of a buffer load: the 
 // NBB = number of 16-column bank blocks this pass accumulates (cb0 = the first of them); kDir = whether
 // the pass also carries the first 16-column direction block; RB = 16-row blocks of an item.
 //
-// LDS: [wave][2 stages][RB*16 rows][128 B] rings of X, then [2 stages][NBB blocks][2 halves][1 KiB] of Vb.
+// LDS: [wave][2 stages][RB*16 rows][128 B] rings of X, then [2 stages][NBB blocks][2 halves][1 KiB] of Vb,
+// then [wave][2 KiB] for each wave's direction block of V (one stage).
 // A row of a ring stage holds its eight 16-byte chunks XOR-swizzled by (row >> 1) & 7, which makes the
 // fragment reads (16 rows x 4 chunks per instruction) conflict-free.
 //
 // One step of a wave: wait for the step's lines (leaving the next step's in flight), barrier (the
 // step's Vb stage is complete, and every wave is done with the other stage), request the next step's
-// Vb stage and V fragments, read the step's X fragments into registers, request the lines of the step
-// after next into the ring stage just read, multiply.
+// Vb stage, read the step's X and V fragments into registers, then multiply, with the requests for the
+// next step's V block and for the lines of the step after next (into the ring stage just read) spread
+// through the products.
 template <int NBB, bool kDir, int RB, int W>
 __global__ __launch_bounds__(W * 64, 1) void k_side_down(SideDownArgs a, int cb0) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
