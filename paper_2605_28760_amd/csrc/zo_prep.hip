@@ -229,6 +229,21 @@ __device__ __forceinline__ void factor_quad(uint64_t seed, uint32_t tid, int64_t
   }
 }
 
+// idx = (a * per_a) + b * inner + c with b * inner + c < per_a and c < inner.  32-bit divisions when the numbers
+// allow (a 64-bit division costs more instructions than the normals a thread generates).
+__device__ __forceinline__ void split3(int64_t idx, int64_t per_a, int inner, int& a, int& b, int& c) {
+  if (idx < (1ll << 31) && per_a < (1ll << 31)) {
+    const uint32_t x = (uint32_t)idx, pa = (uint32_t)per_a;
+    const uint32_t qa = x / pa, rem = x - qa * pa;
+    const uint32_t qb = rem / (uint32_t)inner;
+    a = (int)qa; b = (int)qb; c = (int)(rem - qb * (uint32_t)inner);
+  } else {
+    const int64_t qa = idx / per_a, rem = idx - qa * per_a;
+    const int64_t qb = rem / inner;
+    a = (int)qa; b = (int)qb; c = (int)(rem - qb * inner);
+  }
+}
+
 // idx runs over [K][m_img][RP32/4]: one thread writes four neighbouring entries of a row of U (8 bytes) into
 // the image [K * SPD][m_img][32]; rows >= m and columns >= r are zero
 __device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint32_t tid_u, int m, int m_img, int r, int SPD,
@@ -236,9 +251,9 @@ __device__ __forceinline__ void image_U_at(const BatchDev& b, int64_t idx, uint3
   const int quads = SPD * 8;
   const int64_t per_dir = (int64_t)m_img * quads;
   if (idx >= per_dir * b.K) return;
-  const int k = (int)(idx / per_dir);
-  const int64_t rem = idx - (int64_t)k * per_dir;
-  const int i = (int)(rem / quads), c0 = (int)(rem % quads) * 4;
+  int k, i, c0;
+  split3(idx, per_dir, quads, k, i, c0);
+  c0 *= 4;
   float z[4] = {0.f, 0.f, 0.f, 0.f};
   if (i < m && c0 < r) factor_quad(b.seed[k], tid_u, i, r, c0, z);
   *reinterpret_cast<uint2*>(Uimg + (((int64_t)k * SPD + (c0 >> 5)) * m_img + i) * 32 + (c0 & 31)) =
@@ -250,9 +265,9 @@ __device__ __forceinline__ void image_Vt_at(const BatchDev& b, int64_t idx, uint
   const int quads = RP >> 2;
   const int64_t per_dir = (int64_t)n * quads;
   if (idx >= per_dir * b.K) return;
-  const int k = (int)(idx / per_dir);
-  const int64_t rem = idx - (int64_t)k * per_dir;
-  const int c0 = (int)(rem / n) * 4, i = (int)(rem % n);
+  int k, c0, i;
+  split3(idx, per_dir, n, k, c0, i);
+  c0 *= 4;
   float z[4] = {0.f, 0.f, 0.f, 0.f};
   if (c0 < r) factor_quad(b.seed_v ? b.seed_v[k] : b.seed[k], tid_v, i, r, c0, z);
 #pragma unroll
@@ -264,7 +279,8 @@ __device__ __forceinline__ void image_P_at(int64_t idx, const float* P, int R_ca
                                            bf16_t* Pimg) {
   const int cols = RpT * 64;
   if (idx >= (int64_t)m_img * cols) return;
-  const int i = (int)(idx / cols), j = (int)(idx % cols);
+  int zero, i, j;
+  split3(idx, (int64_t)m_img * cols, cols, zero, i, j);
   Pimg[((int64_t)(j >> 6) * m_img + i) * 64 + (j & 63)] = f32_to_bf16(i < m && j < R_used ? P[(int64_t)i * R_cap + j] : 0.0f);
 }
 
