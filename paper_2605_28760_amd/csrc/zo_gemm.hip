@@ -140,7 +140,7 @@ __device__ __forceinline__ void gather_rows(int (&idx)[kLPW], const int32_t* b_r
 template <bool kGather>
 __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
                                              const bf16_t* B, int64_t ldb, int N, int tile_n0, int K, int wave,
-                                             int lane, const int (&idx)[kLPW], int B_rows_total) {
+                                             int lane, const int (&idx)[kLPW], int B_rows_total, bool half = false) {
 #pragma unroll
   for (int j = 0; j < kLPW; ++j) {
     const int row = (wave * kLPW + j) * 8 + (lane >> 3);
@@ -153,8 +153,11 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
   }
   const int64_t bytesA = ((int64_t)(M - tile_m0 - 1) * lda + K) * 2;
   const int64_t bytesB = kGather ? ((int64_t)(B_rows_total - 1) * ldb + K) * 2 : ((int64_t)(N - tile_n0 - 1) * ldb + K) * 2;
+  // In a half tile only the first 128 A rows are multiplied.  The waves whose loads cover the other 128 rows
+  // (waves 4-7: load j of wave w covers rows (4 w + j) * 8 ...) get an empty buffer: their loads still run, in
+  // step with everybody else's, but every address is out of range, so they fetch nothing and write zeros.
   o.rA = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (int64_t)tile_m0 * lda), 0,
-                                           (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
+                                           (half && wave >= kWaves / 2) ? 0 : (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
   o.rB = __builtin_amdgcn_make_buffer_rsrc((void*)(kGather ? B : B + (int64_t)tile_n0 * ldb), 0,
                                            (int)min(bytesB, (int64_t)0x7FFFFFFF), 0x00020000);
   o.soffA = o.soffB = 0;
@@ -181,7 +184,7 @@ __device__ __forceinline__ void setup_side_offsets(OperandStream& o, int wave, i
 // Persistent GEMM driver.  For every output tile of this workgroup:
 //   acc[rb][cb] = sum over the tile's K tiles (side K tiles first, then the K / 64 base K tiles) of
 //                 A[tile rows] * B[tile rows]^T, starting from +0,
-//   post(tm, tn, acc)  consumes the accumulators (it may use lds + kStagesLds .. +kEpiLds
+//   post(m0, n0, acc, row blocks per wave)  consumes the accumulators (it may use lds + kStagesLds .. +kEpiLds
 //                      and workgroup barriers; it must not touch the operand stages).
 // 16x16x32 fragments: lane l holds row l%16 and the 8 k-values of group l/16; D: lane l holds
 // rows 4*(l/16) + v (v = 0..3) of column l%16.
@@ -220,10 +223,11 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   //
   // With kSplit the last n_split raster positions are two work items each, the halves of 128 A rows
   // of the tile: a last round that would occupy at most half of the workgroups with whole tiles
-  // occupies twice as many with halves.  A half is a tile whose A rows start 128 further down and in
-  // which only the waves of the upper wave row (one per SIMD) multiply and store; the others only
-  // take part in the loads (the whole 256-row stage is still filled: a branch around a load would split
-  // the K loop's schedule) and barriers.  The K order of an output element is the same either way.
+  // occupies twice as many with halves.  A half is a tile whose A rows start 128 further down and of
+  // which only the first 128 A rows are multiplied: the two wave rows take 64 of them each (4 instead
+  // of 8 row blocks per wave), so every SIMD still has its two waves feeding the matrix core.  The
+  // whole 256-row stage is still filled (a branch around a load would split the K loop's schedule).
+  // The K order of an output element is the same either way.
   const int total = n_tm * n_tn;
   const int first_split = total - (kSplit ? n_split : 0);
   const int xcd = blockIdx.x % kXcds;
@@ -265,7 +269,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   uint32_t roff[2];
 #pragma unroll
   for (int ks = 0; ks < 2; ++ks) roff[ks] = r16 * 128 + (((ks * 4 + (lane >> 4)) ^ swz) << 4);
-  const uint32_t aBase = wm * 128 * 128, bBase = kOperandStage + wn * 64 * 128;
+  const uint32_t aBaseWhole = wm * 128 * 128, aBaseHalf = wm * 64 * 128, bBase = kOperandStage + wn * 64 * 128;
 
   // load cursor
   OperandStream ld;
@@ -273,7 +277,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   // the next run of the cursor's output tile (the first one after ld.dir_next = 0, ld.phase = 0)
   auto next_run = [&]() {
     int m0, n0;
-    item_at(ld.L, m0, n0);
+    const bool half = item_at(ld.L, m0, n0);
     if constexpr (kSide) {
       const TileHdr h = side_hdr(n0);
       const int n_dir_kt = (h.n_slots + 1) >> 1;
@@ -309,7 +313,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
         return;
       }
     }
-    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total);
+    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total, half);
     if (kGather) {
       item_at(min(ld.L + stride, L_end - 1), m0, n0);
       gather_rows(idx_next, b_rows, N, n0, wave, lane);
@@ -364,23 +368,26 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
 
   bf16x8 fa[2][RB], fb[2][CB];
   // token fragments first: every MFMA of the next k-step needs one of them
-  auto load_frags = [&](int set, int stage, int ks) {
+  auto load_frags = [&](int set, int stage, int ks, auto rb_c) {
+    constexpr int kRB = decltype(rb_c)::value;   // row blocks of this wave: 8 in a whole tile, 4 in a half
     const char* s = lds + stage * kStage;
+    const uint32_t aBase = kRB == RB ? aBaseWhole : aBaseHalf;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) fb[set][cb] = *(const bf16x8*)(s + bBase + cb * 2048 + roff[ks]);
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 2048 + roff[ks]);
+    for (int rb = 0; rb < kRB; ++rb) fa[set][rb] = *(const bf16x8*)(s + aBase + rb * 2048 + roff[ks]);
   };
   // scheduling of one k-step with n_loads direct-to-LDS loads: in every group of 8 MFMAs,
-  // 3 LDS reads and n_loads/4 loads
-  auto pattern = [&](auto n_loads_c) {
+  // 3 LDS reads (4 in a half, which has 8 reads for 16 MFMAs) and the loads spread evenly
+  auto pattern = [&](auto n_loads_c, auto rb_c) {
     constexpr int n_loads = decltype(n_loads_c)::value;
+    constexpr int kRB = decltype(rb_c)::value;
 #pragma unroll
-    for (int i = 0; i < RB * CB; ++i) {
+    for (int i = 0; i < kRB * CB; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA
       const int j = i & 7;
-      if (j == 0 || j == 3 || j == 5) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
-      if (n_loads * (i + 1) / (RB * CB) != n_loads * i / (RB * CB))
+      if (kRB == RB ? (j == 0 || j == 3 || j == 5) : (j & 1) == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // LDS read
+      if (n_loads * (i + 1) / (kRB * CB) != n_loads * i / (kRB * CB))
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);   // direct-to-LDS load
     }
   };
@@ -390,29 +397,28 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   advance_cursor();
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   block_barrier();
-  load_frags(0, 0, 0);
+  load_frags(0, 0, 0, std::integral_constant<int, RB>{});
   issue_range(1, 0, kLoadsLate);
 
   int stage = 0;
   for (; L < L_end; L += stride) {
     int m0, n0;
     const bool is_half = item_at(L, m0, n0);
-    const bool active = !(kSplit && is_half && wm == 1);   // wave-uniform
     int nk_tile = nk;
     if constexpr (kSide) {
       const TileHdr h = side_hdr(n0);
       nk_tile += ((h.n_slots + 1) >> 1) + h.n_bank_kt;
     }
 
-    // the K loop of a wave that multiplies (kActive) or only keeps the operand stream and the barriers going
-    auto k_loop = [&](auto active_c, Acc& acc) __attribute__((always_inline)) {
-      constexpr bool kActive = decltype(active_c)::value;
+    // the K loop of a whole tile (8 row blocks per wave) or of a half (4)
+    auto k_loop = [&](auto rb_c, Acc& acc) __attribute__((always_inline)) {
+      constexpr int kRB = decltype(rb_c)::value;
       // first_c: the tile's very first k-step, whose products start the accumulators (C = +0 as an operand,
       // so the accumulators need no clearing between tiles)
       auto mfmas = [&](int set, auto first_c) __attribute__((always_inline)) {
         constexpr bool kFirst = decltype(first_c)::value;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < kRB; ++rb)
 #pragma unroll
           for (int cb = 0; cb < CB; ++cb)
             acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb],
@@ -422,40 +428,39 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
         // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
         __builtin_amdgcn_sched_barrier(0);
         issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
-        if constexpr (kActive) {
-          load_frags(1, stage, 1);
-          mfmas(0, first_c);
-          pattern(std::integral_constant<int, kLoadsEarly>{});
-        }
+        load_frags(1, stage, 1, rb_c);
+        mfmas(0, first_c);
+        pattern(std::integral_constant<int, kLoadsEarly>{}, rb_c);
         __builtin_amdgcn_sched_barrier(0);
         // the next K tile has landed; every wave is done reading this K tile's stage
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         block_barrier();
         advance_cursor();
         __builtin_amdgcn_sched_barrier(0);
-        // k-step 1: first fragments of the next K tile, first loads of the one after it
+        // k-step 1: first fragments of the next K tile, first loads of the one after it.  (The next K tile
+        // may belong to the next work item, whole or half; its first fragments are fetched again at the
+        // start of that item, so here they are fetched in this item's shape.)
         issue_range(stage, 0, kLoadsLate);
-        if constexpr (kActive) {
-          load_frags(0, stage ^ 1, 0);
-          mfmas(1, std::false_type{});
-          pattern(std::integral_constant<int, kLoadsLate>{});
-        }
+        load_frags(0, stage ^ 1, 0, rb_c);
+        mfmas(1, std::false_type{});
+        pattern(std::integral_constant<int, kLoadsLate>{}, rb_c);
         __builtin_amdgcn_sched_barrier(0);
         stage ^= 1;
       };
       k_tile(std::true_type{});   // (a tile has at least one K tile)
       for (int kt = 1; kt < nk_tile; ++kt) k_tile(std::false_type{});
     };
-    if (active) {
-      Acc acc;   // started by the first k-step's products
-      // The first fragments of this tile were already fetched under the previous tile's last
-      // k-step; fetching them again here keeps their 48 registers free during post().
-      load_frags(0, stage, 0);
-      k_loop(std::true_type{}, acc);
-      post(m0, n0, acc);
-    } else if constexpr (kSplit) {
-      Acc none;   // never touched: this instance of the loop multiplies nothing
-      k_loop(std::false_type{}, none);
+    Acc acc;   // started by the first k-step's products
+    // The first fragments of this tile were already fetched under the previous tile's last
+    // k-step; fetching them again here keeps their registers free during post().
+    if (kSplit && is_half) {
+      load_frags(0, stage, 0, std::integral_constant<int, RB / 2>{});
+      k_loop(std::integral_constant<int, RB / 2>{}, acc);
+      post(m0, n0, acc, std::integral_constant<int, RB / 2>{});
+    } else {
+      load_frags(0, stage, 0, std::integral_constant<int, RB>{});
+      k_loop(std::integral_constant<int, RB>{}, acc);
+      post(m0, n0, acc, std::integral_constant<int, RB>{});
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads before the workgroup ends
@@ -526,12 +531,14 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
   const int lane = tid & 63;
   const int wm = wave >> 2, wn = wave & 3;
 
-  // D block (rb, cb): out feature = obase + rb*16 + 4*g + v, token = tbase + cb*16 + r16.
-  auto epilogue = [&](int tile_o0, int tile_t0, Acc& acc) {
+  // D block (rb, cb): out feature = obase + rb*16 + 4*g + v, token = tbase + cb*16 + r16.  kRB = row blocks of
+  // this wave: 8 (128 out features) in a whole tile, 4 (64) in a half.
+  auto epilogue = [&](int tile_o0, int tile_t0, Acc& acc, auto rb_c) {
+    constexpr int kRB = decltype(rb_c)::value;
     const int lane_t = opaque(lane);
     const int r16 = lane_t & 15, g = lane_t >> 4;
-    const int obase = tile_o0 + wm * 128;   // first out feature of this wave
-    const int tbase = tile_t0 + wn * 64;    // first token of this wave
+    const int obase = tile_o0 + wm * (kRB * 16);   // first out feature of this wave
+    const int tbase = tile_t0 + wn * 64;           // first token of this wave
     // ReLU as a select on the sign, which lets a NaN through (a max would replace it by the other operand)
     const bool relu = p.act == 1;
     if constexpr (!kOutBf16) {
@@ -541,7 +548,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
         const int t = tbase + cb * 16 + r16;
         if (t >= p.T) continue;
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
           const int o0 = obase + rb * 16 + 4 * g;   // this lane's 4 consecutive out features
           float y[4];
 #pragma unroll
@@ -562,17 +569,18 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
       return;
     }
     if constexpr (kGate) {
-      // bf16, gated: a lane's 4 features become 2 outputs (one dword); 16 tokens x 64 outputs at a time
-      // through 2 KiB of this wave's LDS region (16-byte slots XOR-swizzled by the token), then 16-byte
-      // stores covering 128 contiguous bytes per token row.
+      // bf16, gated: a lane's 4 features become 2 outputs (one dword); 16 tokens x (kRB * 8) outputs at a time
+      // through this wave's LDS region (16-byte slots XOR-swizzled by the token), then 16-byte stores
+      // covering kRB * 16 contiguous bytes per token row.
+      constexpr int CH = kRB;                   // 16-byte chunks of a token row
       char* region = lds + kStagesLds + wave * 4096;
       bf16_t* Y = (bf16_t*)p.Y;
-      const int chunk = lane_t & 7;             // 8 outputs (16 bytes) of a token row
+      const int chunk = lane_t & (CH - 1);      // 8 outputs (16 bytes) of a token row
       const int oo = (obase >> 1) + chunk * 8;  // first of them
 #pragma unroll
       for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
+        for (int rb = 0; rb < kRB; ++rb) {
           float y[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) y[e] = acc[rb][cb][e];
@@ -581,34 +589,35 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
 #pragma unroll
             for (int e = 0; e < 4; ++e) y[e] += p.bias[min(ob + e, p.m - 1)];
           }
-          // outputs rb*8 + 2g, +1 of the token's 64: slot rb, bytes 4g..4g+3
-          *(uint32_t*)(region + r16 * 128 + ((rb ^ (r16 & 7)) << 4) + 4 * g) =
+          // outputs rb*8 + 2g, +1 of the token's kRB*8: slot rb, bytes 4g..4g+3
+          *(uint32_t*)(region + r16 * (CH * 16) + ((rb ^ (r16 & (CH - 1))) << 4) + 4 * g) =
               pack_bf16x2(silu_mul(y[0], y[1]), silu_mul(y[2], y[3]));
         }
         // the wave reads back what it wrote itself: LDS operations of one wave complete in order
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-          const int tl = it * 8 + (lane_t >> 3);
+        for (int it = 0; it < CH / 4; ++it) {
+          const int tl = it * (64 / CH) + lane_t / CH;
           const int t = tbase + cb * 16 + tl;
-          const u32x4 val = *(const u32x4_alias*)(region + tl * 128 + ((chunk ^ (tl & 7)) << 4));
+          const u32x4 val = *(const u32x4_alias*)(region + tl * (CH * 16) + ((chunk ^ (tl & (CH - 1))) << 4));
           if (t < p.T && oo < (p.m >> 1)) store_streaming(Y + (int64_t)t * p.ldy + oo, val);   // m % 16 == 0
         }
       }
       return;
     }
-    // bf16: bias / activation / rounding in registers, then 16 tokens x 128 features at a
+    // bf16: bias / activation / rounding in registers, then 16 tokens x (kRB * 16) features at a
     // time through this wave's own 4 KiB of LDS (XOR-swizzled 16-byte slots) so that the
-    // global stores are 16 bytes per lane and cover 256 contiguous bytes per token row.
+    // global stores are 16 bytes per lane and cover kRB * 32 contiguous bytes per token row.
+    constexpr int CH = kRB * 2;                 // 16-byte chunks of a token row
     char* region = lds + kStagesLds + wave * 4096;
     bf16_t* Y = (bf16_t*)p.Y;
-    const int chunk = lane_t & 15;            // 8 out features (16 bytes) of a token row
+    const int chunk = lane_t & (CH - 1);        // 8 out features (16 bytes) of a token row
     const int o = obase + chunk * 8;
-    const uint32_t wr_base = r16 * 256 + (g & 1) * 8;
-    const uint32_t wr_swz = r16 * 16;
+    const uint32_t wr_base = r16 * (CH * 16) + (g & 1) * 8;
+    const uint32_t wr_swz = (r16 & (CH - 1)) * 16;
 #pragma unroll
     for (int cb = 0; cb < CB; ++cb) {
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
+      for (int rb = 0; rb < kRB; ++rb) {
         float y[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) y[e] = acc[rb][cb][e];
@@ -625,10 +634,10 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
       }
       // the wave reads back what it wrote itself: LDS operations of one wave complete in order
 #pragma unroll
-      for (int it = 0; it < 4; ++it) {
-        const int tl = it * 4 + (lane_t >> 4);
+      for (int it = 0; it < CH / 4; ++it) {
+        const int tl = it * (64 / CH) + lane_t / CH;
         const int t = tbase + cb * 16 + tl;
-        const u32x4 val = *(const u32x4_alias*)(region + tl * 256 + ((chunk ^ tl) * 16));
+        const u32x4 val = *(const u32x4_alias*)(region + tl * (CH * 16) + ((chunk ^ (tl & (CH - 1))) * 16));
         if (t < p.T && o < p.m) store_streaming(Y + (int64_t)t * p.ldy + o, val);   // m % 8 == 0
       }
     }
@@ -701,7 +710,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_head_score(HeadScoreArgs p, int
   constexpr float kLog2e = 1.4426950408889634f;
 
   // D block (rb, cb): vocabulary row = vbase + rb*16 + 4*g + v, token = tile_t0 + wn*64 + cb*16 + r16.
-  auto epilogue = [&](int tile_v0, int tile_t0, Acc& acc) {
+  auto epilogue = [&](int tile_v0, int tile_t0, Acc& acc, auto) {
     const int lane_t = opaque(lane), tid_t = opaque(tid);
     const int r16 = lane_t & 15, g = lane_t >> 4;
     const int tm = tile_v0 / BM;   // vocabulary tile: the index of this tile's partials
