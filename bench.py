@@ -31,8 +31,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # factor 2.000 a plain 1 GiB copy calibrates; WRITE_SIZE factor 1.000).  They are figures of those profile
 # runs, not of this run: the line names their source next to them (null for a workload without such a run).
 MEASURED_TRAFFIC = {"c3": (1.241e10, "profiles/hbm_bytes_bench_c5_c3.txt"),
-                    "c4": (3.746e10, "profiles/hbm_bytes_bench_c5_c3.txt"),
-                    "c5": (6.688e10, "profiles/hbm_bytes_bench_c5_c3.txt")}
+                    "c4": (3.730e10, "profiles/hbm_bytes_bench_c5_c3.txt"),
+                    "c5": (6.545e10, "profiles/hbm_bytes_bench_c5_c3.txt")}
 
 
 def _cpu_baseline(w, budget_hint_s=20.0):
