@@ -40,6 +40,10 @@ constexpr int kStage = 2 * kOperandStage;         // A tile then B tile
 constexpr int kStagesLds = 2 * kStage;            // double buffered operand stages: 128 KiB
 constexpr int kEpiLds = 32 * 1024;                // epilogue scratch, disjoint from the stages
 constexpr int kGemmLds = kStagesLds + kEpiLds;    // 160 KiB: the whole LDS of a CU
+// A half tile (128 A rows) needs 16 + 32 KiB per stage, so three stages fit next to 16 KiB of epilogue scratch
+constexpr int kHalfA = (BM / 2) * BK * 2;         // 16 KiB: 128 rows x 128 B
+constexpr int kHalfStage = kHalfA + kOperandStage;
+constexpr int kHalfStagesLds = 3 * kHalfStage;    // 144 KiB
 constexpr int kGroupM = 8;                        // raster: weight-row tiles per group
 constexpr int kXcds = 8;
 constexpr int kWaves = 8;                         // 2 (weight rows) x 4 (tokens)
@@ -141,23 +145,23 @@ template <bool kGather>
 __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, int64_t lda, int M, int tile_m0,
                                              const bf16_t* B, int64_t ldb, int N, int tile_n0, int K, int wave,
                                              int lane, const int (&idx)[kLPW], int B_rows_total, bool half = false) {
+  // (half: the A side of a half tile is 128 rows, two loads per wave: load j covers rows (2 wave + j) * 8 ...)
 #pragma unroll
   for (int j = 0; j < kLPW; ++j) {
     const int row = (wave * kLPW + j) * 8 + (lane >> 3);
     const int lch = (lane & 7) ^ ((row >> 1) & 7);
-    const int ra = min(tile_m0 + row, M - 1) - tile_m0;
+    const int rowA = half ? (wave * 2 + (j & 1)) * 8 + (lane >> 3) : row;
+    const int lchA = (lane & 7) ^ ((rowA >> 1) & 7);
+    const int ra = min(tile_m0 + rowA, M - 1) - tile_m0;
     const int rbn = kGather ? idx[j] : min(tile_n0 + row, N - 1) - tile_n0;
     // 24-bit multiply: fewer than 2^24 rows, and the launchers reject row pitches of 16 MiB or more
-    o.offA[j] = __umul24((uint32_t)ra, (uint32_t)lda * 2u) + lch * 16;
+    o.offA[j] = __umul24((uint32_t)ra, (uint32_t)lda * 2u) + lchA * 16;
     o.offB[j] = __umul24((uint32_t)rbn, (uint32_t)ldb * 2u) + lch * 16;
   }
   const int64_t bytesA = ((int64_t)(M - tile_m0 - 1) * lda + K) * 2;
   const int64_t bytesB = kGather ? ((int64_t)(B_rows_total - 1) * ldb + K) * 2 : ((int64_t)(N - tile_n0 - 1) * ldb + K) * 2;
-  // In a half tile only the first 128 A rows are multiplied.  The waves whose loads cover the other 128 rows
-  // (waves 4-7: load j of wave w covers rows (4 w + j) * 8 ...) get an empty buffer: their loads still run, in
-  // step with everybody else's, but every address is out of range, so they fetch nothing and write zeros.
   o.rA = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (int64_t)tile_m0 * lda), 0,
-                                           (half && wave >= kWaves / 2) ? 0 : (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
+                                           (int)min(bytesA, (int64_t)0x7FFFFFFF), 0x00020000);
   o.rB = __builtin_amdgcn_make_buffer_rsrc((void*)(kGather ? B : B + (int64_t)tile_n0 * ldb), 0,
                                            (int)min(bytesB, (int64_t)0x7FFFFFFF), 0x00020000);
   o.soffA = o.soffB = 0;
@@ -170,14 +174,16 @@ __device__ __forceinline__ void setup_stream(OperandStream& o, const bf16_t* A, 
 // Per-lane offsets of a side run.  The images hold every row of a tile (they are padded), so a lane's
 // offset is its row in the tile times the image's row pitch plus its swizzled chunk.
 template <bool kDirRun>
-__device__ __forceinline__ void setup_side_offsets(OperandStream& o, int wave, int lane, int base0, int base1) {
+__device__ __forceinline__ void setup_side_offsets(OperandStream& o, int wave, int lane, int base0, int base1, bool half) {
 #pragma unroll
   for (int j = 0; j < kLPW; ++j) {
     const int row = (wave * kLPW + j) * 8 + (lane >> 3);
     const int lch = (lane & 7) ^ ((row >> 1) & 7);
+    const int rowA = half ? (wave * 2 + (j & 1)) * 8 + (lane >> 3) : row;   // (as in setup_stream)
+    const int lchA = (lane & 7) ^ ((rowA >> 1) & 7);
     o.offB[j] = row * 128 + lch * 16;
     // direction run: columns 0-31 of the K tile come from image block base0, columns 32-63 from base1
-    o.offA[j] = kDirRun ? (uint32_t)((lch >= 4 ? base1 : base0) + row * 64 + (lch & 3) * 16) : o.offB[j];
+    o.offA[j] = kDirRun ? (uint32_t)((lchA >= 4 ? base1 : base0) + rowA * 64 + (lchA & 3) * 16) : (uint32_t)(rowA * 128 + lchA * 16);
   }
 }
 
@@ -271,7 +277,8 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   for (int ks = 0; ks < 2; ++ks) roff[ks] = r16 * 128 + (((ks * 4 + (lane >> 4)) ^ swz) << 4);
   const uint32_t aBaseWhole = wm * 128 * 128, aBaseHalf = wm * 64 * 128, bBase = kOperandStage + wn * 64 * 128;
 
-  // load cursor
+  // load cursor.  It does not run past cursor_end: the whole tiles of the workgroup first, then (kSplit) its half.
+  int cursor_end = first_split;
   OperandStream ld;
   int idx_next[kLPW] = {};   // gather: B rows of the tile after the cursor's
   // the next run of the cursor's output tile (the first one after ld.dir_next = 0, ld.phase = 0)
@@ -288,7 +295,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
         const int j = ld.dir_next;
         const int e0 = __builtin_amdgcn_readfirstlane(so.slots[h.slot0 + 2 * j]);
         const int e1 = 2 * j + 1 < h.n_slots ? __builtin_amdgcn_readfirstlane(so.slots[h.slot0 + 2 * j + 1]) : e0;
-        setup_side_offsets<true>(ld, wave, lane_t, e0 * so.m_img * 64, e1 * so.m_img * 64);
+        setup_side_offsets<true>(ld, wave, lane_t, e0 * so.m_img * 64, e1 * so.m_img * 64, half);
         ld.rA = __builtin_amdgcn_make_buffer_rsrc((void*)so.Uimg, 0, so.uimg_bytes, 0x00020000);
         ld.rB = __builtin_amdgcn_make_buffer_rsrc((void*)so.Xs, 0, so.xs_bytes, 0x00020000);
         ld.soffA = m0 * 64;
@@ -300,7 +307,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
         return;
       }
       if (ld.phase == 0 && h.n_bank_kt > 0) {
-        setup_side_offsets<false>(ld, wave, lane_t, 0, 0);
+        setup_side_offsets<false>(ld, wave, lane_t, 0, 0, half);
         ld.rA = __builtin_amdgcn_make_buffer_rsrc((void*)so.Pimg, 0, so.pimg_bytes, 0x00020000);
         ld.rB = __builtin_amdgcn_make_buffer_rsrc((void*)so.Xs, 0, so.xs_bytes, 0x00020000);
         ld.soffA = m0 * 128;
@@ -315,23 +322,23 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     }
     setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total, half);
     if (kGather) {
-      item_at(min(ld.L + stride, L_end - 1), m0, n0);
+      item_at(min(ld.L + stride, cursor_end - 1), m0, n0);
       gather_rows(idx_next, b_rows, N, n0, wave, lane);
     }
   };
-  {
-    // (every scalar of the cursor is defined on every path: an undefined one would be given a vector register)
-    ld.soffA = ld.soffB = ld.stepA = ld.stepB = ld.kt = ld.len = 0;
-    ld.L = L;
+  // (every scalar of the cursor is defined on every path: an undefined one would be given a vector register)
+  ld.soffA = ld.soffB = ld.stepA = ld.stepB = ld.kt = ld.len = 0;
+  auto start_cursor = [&](int at) {
+    ld.L = at;
     ld.dir_next = 0;
     ld.phase = 0;
     if (kGather) {
       int m0, n0;
-      item_at(L, m0, n0);
+      item_at(at, m0, n0);
       gather_rows(idx_next, b_rows, N, n0, wave, lane);
     }
     next_run();
-  }
+  };
   // load i (0..7) of the cursor's K tile: i < 4 -> A chunk i, else B chunk i - 4
   auto issue_range = [&](int stage, int first, int count) {
     char* sbase = lds + stage * kStage + wave * kLPW * 1024;
@@ -358,7 +365,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
       return;
     }
     if (!kSide || ld.phase == 2) {   // the tile's last K tile: on to the next output tile, if there is one
-      if (ld.L + stride >= L_end) return;
+      if (ld.L + stride >= cursor_end) return;
       ld.L += stride;
       ld.dir_next = 0;
       ld.phase = 0;
@@ -392,6 +399,8 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
     }
   };
 
+  if (L < first_split) {
+  start_cursor(L);
   // prologue: first K tile of the first output tile, and the late part of the second K tile's loads
   issue_range(0, 0, 2 * kLPW);
   advance_cursor();
@@ -401,69 +410,145 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   issue_range(1, 0, kLoadsLate);
 
   int stage = 0;
-  for (; L < L_end; L += stride) {
+  for (; L < first_split; L += stride) {
     int m0, n0;
-    const bool is_half = item_at(L, m0, n0);
+    item_at(L, m0, n0);
     int nk_tile = nk;
     if constexpr (kSide) {
       const TileHdr h = side_hdr(n0);
       nk_tile += ((h.n_slots + 1) >> 1) + h.n_bank_kt;
     }
+    Acc acc;   // started by the first k-step's products
+    // first_c: the tile's very first k-step, whose products start the accumulators (C = +0 as an operand,
+    // so the accumulators need no clearing between tiles)
+    auto mfmas = [&](int set, auto first_c) __attribute__((always_inline)) {
+      constexpr bool kFirst = decltype(first_c)::value;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb)
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb],
+                                                                 kFirst ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[rb][cb], 0, 0, 0);
+    };
+    constexpr std::integral_constant<int, RB> rb_c{};
+    auto k_tile = [&](auto first_c) __attribute__((always_inline)) {
+      // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
+      __builtin_amdgcn_sched_barrier(0);
+      issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
+      load_frags(1, stage, 1, rb_c);
+      mfmas(0, first_c);
+      pattern(std::integral_constant<int, kLoadsEarly>{}, rb_c);
+      __builtin_amdgcn_sched_barrier(0);
+      // the next K tile has landed; every wave is done reading this K tile's stage
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+      block_barrier();
+      advance_cursor();
+      __builtin_amdgcn_sched_barrier(0);
+      // k-step 1: first fragments of the next K tile, first loads of the one after it
+      issue_range(stage, 0, kLoadsLate);
+      load_frags(0, stage ^ 1, 0, rb_c);
+      mfmas(1, std::false_type{});
+      pattern(std::integral_constant<int, kLoadsLate>{}, rb_c);
+      __builtin_amdgcn_sched_barrier(0);
+      stage ^= 1;
+    };
+    // The first fragments of this tile were already fetched under the previous tile's last
+    // k-step; fetching them again here keeps their registers free during post().
+    load_frags(0, stage, 0, rb_c);
+    k_tile(std::true_type{});   // (a tile has at least one K tile)
+    for (int kt = 1; kt < nk_tile; ++kt) k_tile(std::false_type{});
+    post(m0, n0, acc, rb_c);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads
+  }
 
-    // the K loop of a whole tile (8 row blocks per wave) or of a half (4)
-    auto k_loop = [&](auto rb_c, Acc& acc) __attribute__((always_inline)) {
-      constexpr int kRB = decltype(rb_c)::value;
-      // first_c: the tile's very first k-step, whose products start the accumulators (C = +0 as an operand,
-      // so the accumulators need no clearing between tiles)
+  // The workgroup's half tile, if it has one (at most one: the halves are the last 2 n_split <= gridDim.x work
+  // items, and it is the workgroup's last item).  With half the products per K tile, a K tile's period would
+  // meet the latency of loads requested one period ahead; a half needs only 48 KiB per stage, so it runs on
+  // three stages with every K tile requested two periods ahead.
+  if constexpr (kSplit) {
+    if (L < L_end) {
+      constexpr std::integral_constant<int, RB / 2> rb_c{};
+      constexpr int kHalfLoads = 2 + kLPW;   // loads of a wave per K tile: 2 of the 128 A rows, 4 of the 256 B rows
+      block_barrier();   // the whole tiles' stages and epilogue scratch are free: every wave is past them
+      cursor_end = L_end;
+      start_cursor(L);
+      int m0, n0;
+      item_at(L, m0, n0);
+      int nk_tile = nk;
+      if constexpr (kSide) {
+        const TileHdr h = side_hdr(n0);
+        nk_tile += ((h.n_slots + 1) >> 1) + h.n_bank_kt;
+      }
+      auto issue_half = [&](int stg) {
+        char* sb = lds + stg * kHalfStage;
+        int soffA = ld.soffA + ld.kt * ld.stepA, soffB = ld.soffB + ld.kt * ld.stepB;
+        if constexpr (kSide) {
+          soffA = __builtin_amdgcn_readfirstlane(soffA);
+          soffB = __builtin_amdgcn_readfirstlane(soffB);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rA, (lds_void*)(sb + (wave * 2 + j) * 1024), 16, (int)ld.offA[j], soffA, 0, 0);
+#pragma unroll
+        for (int j = 0; j < kLPW; ++j)
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(ld.rB, (lds_void*)(sb + kHalfA + (wave * kLPW + j) * 1024), 16,
+                                                   (int)ld.offB[j], soffB, 0, 0);
+      };
+      auto frags_half = [&](int set, int stg, int ks) {
+        const char* sb = lds + stg * kHalfStage;
+#pragma unroll
+        for (int cb = 0; cb < CB; ++cb) fb[set][cb] = *(const bf16x8*)(sb + kHalfA + wn * 64 * 128 + cb * 2048 + roff[ks]);
+#pragma unroll
+        for (int rb = 0; rb < RB / 2; ++rb) fa[set][rb] = *(const bf16x8*)(sb + wm * 64 * 128 + rb * 2048 + roff[ks]);
+      };
+      Acc acc;
       auto mfmas = [&](int set, auto first_c) __attribute__((always_inline)) {
         constexpr bool kFirst = decltype(first_c)::value;
 #pragma unroll
-        for (int rb = 0; rb < kRB; ++rb)
+        for (int rb = 0; rb < RB / 2; ++rb)
 #pragma unroll
           for (int cb = 0; cb < CB; ++cb)
             acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set][rb], fb[set][cb],
                                                                    kFirst ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[rb][cb], 0, 0, 0);
       };
+      // K tiles 0, 1, 2 into the three stages (past the item's last K tile the cursor stays on it)
+      issue_half(0);
+      advance_cursor();
+      issue_half(1);
+      advance_cursor();
+      issue_half(2);
+      asm volatile("s_waitcnt vmcnt(12)" ::: "memory");   // K tile 0 has landed (2 x 6 loads may be outstanding)
+      static_assert(kHalfLoads == 6, "the counts of the waits above and below");
+      block_barrier();
+      frags_half(0, 0, 0);
+      int stg = 0;
       auto k_tile = [&](auto first_c) __attribute__((always_inline)) {
-        // k-step 0: the rest of the next K tile's loads, fragments of k-step 1
         __builtin_amdgcn_sched_barrier(0);
-        issue_range(stage ^ 1, kLoadsLate, kLoadsEarly);
-        load_frags(1, stage, 1, rb_c);
+        frags_half(1, stg, 1);
         mfmas(0, first_c);
-        pattern(std::integral_constant<int, kLoadsEarly>{}, rb_c);
+        pattern(std::integral_constant<int, 0>{}, rb_c);
         __builtin_amdgcn_sched_barrier(0);
-        // the next K tile has landed; every wave is done reading this K tile's stage
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        // the next K tile has landed (only the six loads of the one after it may be outstanding); every wave is
+        // done reading this K tile's stage, which takes the K tile three ahead
+        asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)" ::: "memory");
         block_barrier();
         advance_cursor();
         __builtin_amdgcn_sched_barrier(0);
-        // k-step 1: first fragments of the next K tile, first loads of the one after it.  (The next K tile
-        // may belong to the next work item, whole or half; its first fragments are fetched again at the
-        // start of that item, so here they are fetched in this item's shape.)
-        issue_range(stage, 0, kLoadsLate);
-        load_frags(0, stage ^ 1, 0, rb_c);
+        issue_half(stg);
+        const int nxt = stg == 2 ? 0 : stg + 1;
+        frags_half(0, nxt, 0);
         mfmas(1, std::false_type{});
-        pattern(std::integral_constant<int, kLoadsLate>{}, rb_c);
+        pattern(std::integral_constant<int, kHalfLoads>{}, rb_c);
         __builtin_amdgcn_sched_barrier(0);
-        stage ^= 1;
+        stg = nxt;
       };
-      k_tile(std::true_type{});   // (a tile has at least one K tile)
+      k_tile(std::true_type{});
       for (int kt = 1; kt < nk_tile; ++kt) k_tile(std::false_type{});
-    };
-    Acc acc;   // started by the first k-step's products
-    // The first fragments of this tile were already fetched under the previous tile's last
-    // k-step; fetching them again here keeps their registers free during post().
-    if (kSplit && is_half) {
-      load_frags(0, stage, 0, std::integral_constant<int, RB / 2>{});
-      k_loop(std::integral_constant<int, RB / 2>{}, acc);
-      post(m0, n0, acc, std::integral_constant<int, RB / 2>{});
-    } else {
-      load_frags(0, stage, 0, std::integral_constant<int, RB>{});
-      k_loop(std::integral_constant<int, RB>{}, acc);
-      post(m0, n0, acc, std::integral_constant<int, RB>{});
+      post(m0, n0, acc, rb_c);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads before the workgroup ends
     }
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // drain the trailing loads before the workgroup ends
 }
 
 // Compute units of the current device, cached per device.
@@ -573,7 +658,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
       // through this wave's LDS region (16-byte slots XOR-swizzled by the token), then 16-byte stores
       // covering kRB * 16 contiguous bytes per token row.
       constexpr int CH = kRB;                   // 16-byte chunks of a token row
-      char* region = lds + kStagesLds + wave * 4096;
+      char* region = kRB == RB ? lds + kStagesLds + wave * 4096 : lds + kHalfStagesLds + wave * 2048;
       bf16_t* Y = (bf16_t*)p.Y;
       const int chunk = lane_t & (CH - 1);      // 8 outputs (16 bytes) of a token row
       const int oo = (obase >> 1) + chunk * 8;  // first of them
@@ -608,7 +693,7 @@ __global__ __launch_bounds__(kThreads, 1) void k_probe_gemm(ProbeGemmArgs p, int
     // time through this wave's own 4 KiB of LDS (XOR-swizzled 16-byte slots) so that the
     // global stores are 16 bytes per lane and cover kRB * 32 contiguous bytes per token row.
     constexpr int CH = kRB * 2;                 // 16-byte chunks of a token row
-    char* region = lds + kStagesLds + wave * 4096;
+    char* region = kRB == RB ? lds + kStagesLds + wave * 4096 : lds + kHalfStagesLds + wave * 2048;   // (a half: 2 KiB)
     bf16_t* Y = (bf16_t*)p.Y;
     const int chunk = lane_t & (CH - 1);        // 8 out features (16 bytes) of a token row
     const int o = obase + chunk * 8;
