@@ -230,9 +230,9 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
   // With kSplit the last n_split raster positions are two work items each, the halves of 128 A rows
   // of the tile: a last round that would occupy at most half of the workgroups with whole tiles
   // occupies twice as many with halves.  A half is a tile whose A rows start 128 further down and of
-  // which only the first 128 A rows are multiplied: the two wave rows take 64 of them each (4 instead
-  // of 8 row blocks per wave), so every SIMD still has its two waves feeding the matrix core.  The
-  // whole 256-row stage is still filled (a branch around a load would split the K loop's schedule).
+  // which only the first 128 A rows exist: the two wave rows take 64 of them each (4 instead of 8 row
+  // blocks per wave), so every SIMD still has its two waves feeding the matrix core.  A workgroup has at
+  // most one half and takes it last, on a pipeline of its own (three smaller stages; see below).
   // The K order of an output element is the same either way.
   const int total = n_tm * n_tn;
   const int first_split = total - (kSplit ? n_split : 0);
