@@ -547,6 +547,9 @@ def test_bf16_probe_linear_half_tiles_of_the_last_round(act, bias):
     dt.probe_linear(0); _sync()
     a, b = to_np(d.Y[0])[24576:], to_np(dt.Y[0])
     assert a.shape == b.shape and np.array_equal(a, b)
+    # the same tiling with fp32 outputs (the halves' other epilogue)
+    y32 = to_np(DeviceWorkload(w, DEV, out_dtype="f32").probe_linear(0))
+    assert_close(y32, oracle_layer(w, 0, w.layers[0].X, out_dtype="f32"), 2e-2, "fp32 output of a tiling with halves")
 
 
 def test_scoring_with_an_input_pitch_beyond_the_gather_window():
