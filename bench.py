@@ -357,26 +357,18 @@ def _chain(name, steps, warmup, full, block, cpu_baseline):
     return out, w
 
 
-def _operand_data_section(n_rep=20):
-    """The head kernel (zo_score, all rows foreground) on the OPT-13B head shape with operands of different
-    content: the same launch, addresses and traffic, so a difference in time is the chip's clock answering the
-    switching activity of the data (a power-limited kernel), not the kernel's schedule."""
+def _operand_data_section(n_rep=10):
+    """The head kernel (zo_score, all rows foreground) on the OPT-13B and Qwen3-8B head shapes with operands of
+    different content: the same launch, addresses and traffic, so a difference in time is the chip's clock
+    answering the switching activity of the data (a power-limited kernel), not the kernel's schedule.  Beside
+    it, as context on the same box and data, the vendor library's plain GEMM of the same contraction
+    (torch.matmul, which also writes the T x V logits that the head kernel never materialises)."""
     import torch
     from paper_2605_28760_amd import binding as zb
     dev = "cuda:0"
-    T, V, d = 16384, 50272, 5120
-    cu = torch.tensor([0, T], dtype=torch.int32, device=dev)
-    fg = torch.tensor([-1], dtype=torch.int32, device=dev)
-    b = zb.make_batch(T, cu, fg, fg, fg, fg, n_seqs=1, n_cands=0, n_dirs=0)
-    g = torch.Generator(device=dev); g.manual_seed(7)
-    tg = torch.randint(0, V, (T,), device=dev, dtype=torch.int32, generator=g)
-    wsb = zb.zo_score_workspace_bytes(T, 1, V, d, zb.ZO_BF16)
-    ws = torch.empty(wsb + 256, dtype=torch.uint8, device=dev)
-    tok = torch.empty(T, device=dev); seq = torch.empty(1, device=dev)
     st = torch.cuda.current_stream()
 
-    def timed(H, W):
-        fn = lambda: zb.zo_score(b, H, d, W, d, V, d, zb.ZO_BF16, tg, tok, seq, None, None, ws, wsb, st)
+    def avg_ms(fn):
         for _ in range(3): fn()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -384,14 +376,33 @@ def _operand_data_section(n_rep=20):
         for _ in range(n_rep): fn()
         e1.record(st); torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n_rep
-    Hr = torch.randn(T, d, device=dev, generator=g).to(torch.bfloat16)
-    Wr = (torch.randn(V, d, device=dev, generator=g) * d ** -0.5).to(torch.bfloat16)
-    Hz, Wz = torch.zeros_like(Hr), torch.zeros_like(Wr)
-    out = {"shape": [T, d, V]}
-    for name, (H, W) in (("random", (Hr, Wr)), ("zeros", (Hz, Wz)), ("random_tokens_zero_weights", (Hr, Wz)),
-                         ("random_again", (Hr, Wr))):
-        ms = timed(H, W)
-        out[name] = {"ms": ms, "tflops": 2.0 * T * V * d / ms / 1e9}
+
+    out = {}
+    for key, (T, d, V) in (("c3_head", (16384, 5120, 50272)), ("c5_head", (33451, 4096, 151936))):
+        cu = torch.tensor([0, T], dtype=torch.int32, device=dev)
+        fg = torch.tensor([-1], dtype=torch.int32, device=dev)
+        b = zb.make_batch(T, cu, fg, fg, fg, fg, n_seqs=1, n_cands=0, n_dirs=0)
+        g = torch.Generator(device=dev); g.manual_seed(7)
+        tg = torch.randint(0, V, (T,), device=dev, dtype=torch.int32, generator=g)
+        wsb = zb.zo_score_workspace_bytes(T, 1, V, d, zb.ZO_BF16)
+        ws = torch.empty(wsb + 256, dtype=torch.uint8, device=dev)
+        tok = torch.empty(T, device=dev); seq = torch.empty(1, device=dev)
+        Hr = torch.randn(T, d, device=dev, generator=g).to(torch.bfloat16)
+        Wr = (torch.randn(V, d, device=dev, generator=g) * d ** -0.5).to(torch.bfloat16)
+        Hz, Wz = torch.zeros_like(Hr), torch.zeros_like(Wr)
+        logits = torch.empty(T, V, dtype=torch.bfloat16, device=dev)
+        flop = 2.0 * T * V * d
+        sec = {"shape": [T, d, V]}
+        for name, (H, W) in (("random", (Hr, Wr)), ("zeros", (Hz, Wz)), ("random_tokens_zero_weights", (Hr, Wz)),
+                             ("random_again", (Hr, Wr))):
+            ms = avg_ms(lambda: zb.zo_score(b, H, d, W, d, V, d, zb.ZO_BF16, tg, tok, seq, None, None, ws, wsb, st))
+            sec[name] = {"ms": ms, "tflops": flop / ms / 1e9}
+        for name, (H, W) in (("library_gemm_random", (Hr, Wr)), ("library_gemm_zeros", (Hz, Wz))):
+            ms = avg_ms(lambda: torch.matmul(H, W.t(), out=logits))
+            sec[name] = {"ms": ms, "tflops": flop / ms / 1e9}
+        out[key] = sec
+        del Hr, Wr, Hz, Wz, logits, ws
+        torch.cuda.empty_cache()
     return out
 
 
@@ -409,7 +420,8 @@ def main():
     ap.add_argument("--no-layer-set", action="store_true",
                     help="skip the secondary measurement of the six OPT-13B-shaped linears at 8192 rows")
     ap.add_argument("--operand-data", action="store_true",
-                    help="also time the head kernel on random, zero and half-zero operands (is the clock power-bound?)")
+                    help="also time the head kernel, and the library GEMM of the same contraction, on random, zero and half-zero "
+                         "operands (is the clock power-bound?)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
