@@ -133,8 +133,8 @@ def _layer_set_section(n_rep):
     fg = DeviceBatch(w.cu_seqlens, np.full_like(w.seq_cand, -1), w.cand_dir, w.cand_sign, w.dir_seed, "cuda:0")
 
     def timed(fn):
-        fn()
-        fn()
+        for _ in range(5):
+            fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(st)
         for _ in range(n_rep):
@@ -143,6 +143,8 @@ def _layer_set_section(n_rep):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n_rep
     layers, total_ms, total_flops = {}, 0.0, 0.0
+    for _ in range(60):   # the device sat idle while the host built the inputs: let its clocks settle first
+        d.probe_linear(0, stream=st)
     for i, l in enumerate(w.layers):
         ms = timed(lambda: d.probe_linear(i, stream=st))
         plain = timed(lambda: d.probe_linear(i, stream=st, batch=fg))
@@ -448,7 +450,7 @@ def main():
         res, _ = _chain(nm, n_steps, min(args.warmup, 5), False, False, False)
         res["steps"], res["warmup"] = n_steps, min(args.warmup, 5)
         nested[nm] = res
-    layer_set_info = None if args.no_layer_set else _layer_set_section(max(3, min(10, args.steps)))
+    layer_set_info = None if args.no_layer_set else _layer_set_section(max(3, min(30, args.steps)))
 
     result = {
         "metric": "candidate-tokens scored/sec (probe linear + LM-head scoring)",
