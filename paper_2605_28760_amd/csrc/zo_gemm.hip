@@ -320,7 +320,7 @@ __device__ __forceinline__ void persistent_gemm(const bf16_t* __restrict__ A, in
         return;
       }
     }
-    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, lane, idx_next, B_rows_total, half);
+    setup_stream<kGather>(ld, A, lda, M, m0, B, ldb, N, n0, K, wave, opaque(lane), idx_next, B_rows_total, half);
     if (kGather) {
       item_at(min(ld.L + stride, cursor_end - 1), m0, n0);
       gather_rows(idx_next, b_rows, N, n0, wave, lane);
